@@ -1,0 +1,256 @@
+/*
+ * ee.h -- libee: the batched early-exit decode step on AMD MI355X (gfx950).
+ *
+ * One decode step produces one token for every request (row) of a batch.  Each
+ * decoder layer runs only on the rows whose token is still in the layer stack;
+ * at each exit layer an exit head gives every remaining token a confidence;
+ * tokens whose confidence meets the threshold leave, and the layers they skip
+ * still receive their keys and values.  The operations follow HELIOS
+ * (arXiv 2504.10724): confidence-threshold early exit (Sec. 1, Sec. 2.1),
+ * keys/values for skipped layers (Sec. 2.2), greedy partial loading with a
+ * forced exit at the last resident layer (Sec. 3.3.3, Sec. 5.4) and the
+ * per-token "confidence not met" signal that feeds the Confidence Breach
+ * Counter (Sec. 3.3.3, Algorithm 1).  The decoder layer itself is the
+ * Llama-family layer (RMSNorm, rotary embedding, grouped-query attention,
+ * SwiGLU).
+ *
+ * Conventions
+ *   - Plain C ABI.  Every call returns EE_OK (0) or a negative ee_status;
+ *     ee_last_error() gives a thread-local message for the last failure.
+ *   - "dev" pointers are device (HBM) pointers, "host" pointers are host
+ *     pointers.  The caller allocates and owns every large device buffer
+ *     (weights, key/value pool, batch state, workspace); the library borrows
+ *     them.  The library itself allocates only small per-handle tables (rotary
+ *     table, row tables) when a handle is created or bound, never in a
+ *     hot-path call.
+ *   - Hot-path calls only enqueue kernels on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and return; results are valid after
+ *     the caller synchronises the stream.  The number of active rows lives on
+ *     the device, so no call waits for the GPU.
+ *   - Layers are numbered from 1.  Exits are numbered from 0 in the order of
+ *     ee_model_config.exit_layers.
+ *   - There is no CPU fallback: without a gfx950 device every compute call
+ *     fails with EE_ERR_HIP.
+ *
+ * Precision contract (dtype EE_BF16): weights, the embedding, cached K and V
+ * and the left operand of every matrix product (normalised activations, the
+ * attention output, the SwiGLU product) are bfloat16, rounded to nearest even;
+ * products accumulate in fp32; the residual stream, queries, rotary
+ * embedding, attention scores and softmax, SiLU, norm statistics and the
+ * exit-head logits, scale and softmax are fp32.  dtype EE_F32 rounds nowhere.
+ */
+#ifndef EE_H
+#define EE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EE_MAX_EXITS 16
+
+typedef enum {
+    EE_OK = 0,
+    EE_ERR_INVALID_ARG = -1,        /* null pointer, NaN threshold, wrong count ...          */
+    EE_ERR_SHAPE = -2,              /* dimensions the kernels do not support                 */
+    EE_ERR_CAPACITY = -3,           /* batch or buffer larger than what was bound            */
+    EE_ERR_LAYER_NOT_RESIDENT = -4, /* layer was never set (not loaded)                      */
+    EE_ERR_EXIT_NOT_RESIDENT = -5,  /* exit head not set, or deepest resident layer no exit  */
+    EE_ERR_DTYPE = -6,
+    EE_ERR_HIP = -7                 /* a HIP runtime call failed                             */
+} ee_status;
+
+typedef enum { EE_F32 = 0, EE_BF16 = 1 } ee_dtype;
+
+typedef struct {
+    int32_t n_layers;    /* L, depth of the full model                                      */
+    int32_t d_model;     /* d                                                               */
+    int32_t n_q_heads;   /* H_q                                                             */
+    int32_t n_kv_heads;  /* H_kv, divides H_q; H_q / H_kv <= 16                             */
+    int32_t head_dim;    /* hd; EE_BF16 requires 128, EE_F32 any even value <= 256          */
+    int32_t d_ffn;       /* F                                                               */
+    int32_t vocab;       /* V                                                               */
+    int32_t dtype;       /* ee_dtype                                                        */
+    float   rms_eps;
+    float   rope_theta;  /* rotary base (10000 for the Llama family)                        */
+    int32_t max_pos;     /* positions 0 .. max_pos-1 can be decoded                         */
+    int32_t n_exits;     /* exit heads of the full model, <= EE_MAX_EXITS                   */
+    int32_t exit_layers[EE_MAX_EXITS]; /* ascending, 1-based                                */
+} ee_model_config;
+/* EE_BF16 additionally requires d, F, H_q*hd multiples of 64 and (H_q+2H_kv)*hd, V
+ * multiples of 32 (violations: EE_ERR_SHAPE). */
+
+/* Device pointers to the weights of one layer.
+ * EE_F32 : row-major [out_features][in_features] fp32, used in place.
+ * EE_BF16: tile-packed bf16 produced by ee_pack_weight (see there).
+ *   w_qkv : [(H_q + 2 H_kv) hd][d]; rows are H_q*hd query rows, then H_kv*hd key rows,
+ *           then H_kv*hd value rows
+ *   w_o   : [d][H_q hd]
+ *   w_gate_up : EE_F32: [2F][d], the F gate rows followed by the F up rows;
+ *               EE_BF16: packed with gate tile j at tile 2j and up tile j at tile 2j+1
+ *   w_down: [d][F]
+ *   g_attn, g_ffn: fp32 [d] RMSNorm gains. */
+typedef struct {
+    const float* g_attn;
+    const void*  w_qkv;
+    const void*  w_o;
+    const float* g_ffn;
+    const void*  w_gate_up;
+    const void*  w_down;
+} ee_layer_weights;
+
+typedef struct ee_model ee_model;
+typedef struct ee_kv    ee_kv;
+typedef struct ee_batch ee_batch;
+
+const char* ee_last_error(void);
+/* Number of HIP devices visible, or a negative ee_status. */
+int ee_device_count(void);
+
+/* ------------------------------------------------------------------ weights */
+
+/* Bytes of the packed form of an [n_out][n_in] bf16 matrix (= n_out*n_in*2). */
+size_t ee_packed_bytes(int n_out, int n_in);
+
+/* Repack a row-major bf16 matrix src[n_out][n_in] (dev) into the tile order the
+ * MFMA kernels stream: the matrix is cut into tiles of 32 output rows x 16 input
+ * columns; tile (r, c) is stored as 64 x 8 values where entry (l, j) is
+ * src[32 r + l % 32][16 c + 8 (l / 32) + j]; the tiles of one tile-row are
+ * contiguous and tile-row r goes to slot (tile_offset + r * tile_stride) of dst.
+ * (tile_offset, tile_stride) = (0, 1) packs a matrix on its own; (0, 2) and
+ * (1, 2) interleave the gate and up matrices into one w_gate_up buffer.
+ * n_out % 32 == 0 and n_in % 16 == 0, else EE_ERR_SHAPE.  Runs on `stream`;
+ * src may be freed after the stream is synchronised. */
+int ee_pack_weight(const void* dev_src, int n_out, int n_in, void* dev_dst,
+                   int tile_offset, int tile_stride, void* stream);
+
+/* ------------------------------------------------------------------ handles */
+
+/* Creates a model description with no layer resident.  Builds the rotary
+ * cos/sin table for positions < max_pos on the current device. */
+int ee_model_create(const ee_model_config* cfg, ee_model** out);
+int ee_model_destroy(ee_model* m);
+/* Makes layer `layer` resident (Sec. 3.3.3: only the layers up to the chosen
+ * exit are loaded).  The pointed-to buffers must outlive the model. */
+int ee_model_set_layer(ee_model* m, int layer, const ee_layer_weights* dev_w);
+/* Exit head exit_idx: fp32 gain [d] and W_exit [V][d] (packed if EE_BF16). */
+int ee_model_set_exit(ee_model* m, int exit_idx, const float* dev_gain, const void* dev_w_exit);
+/* Embedding [V][d], row-major in the model dtype (never packed). */
+int ee_model_set_embed(ee_model* m, const void* dev_emb);
+/* Deepest resident layer R if exactly layers 1..R are resident, else EE_ERR_INVALID_ARG. */
+int ee_model_resident_depth(const ee_model* m);
+
+/* Key/value pool.  Row b owns capacity[b] positions (EE_BF16: a multiple of 32)
+ * and the rows are laid out back to back: with T_b = capacity[0]+..+capacity[b-1]
+ * and T the sum over all rows, the block of (layer l, row b, kv-head g) starts at
+ * element  ((l-1)*T + T_b) * 2*H_kv*hd + g * 2*capacity[b]*hd  and holds
+ *   K: capacity[b] x hd, position-major  K[p][i]
+ *   V: EE_F32 : capacity[b] x hd, position-major, right after K
+ *      EE_BF16: right after K, in groups of 32 positions; inside group q the value
+ *               of position p = 32 q + r, feature i sits at
+ *               ((q*4 + (r%16)/4) * hd + i) * 8 + (r/16)*4 + r%4
+ * ee_kv_pool_bytes gives the size for R resident layers.  host_capacity is a
+ * host array [B]; the library keeps a device copy. */
+size_t ee_kv_pool_bytes(const ee_model* m, int n_resident_layers, const int32_t* host_capacity, int B);
+int ee_kv_bind(const ee_model* m, void* dev_pool, size_t pool_bytes, int n_resident_layers,
+               const int32_t* host_capacity, int B, ee_kv** out);
+int ee_kv_destroy(ee_kv* kv);
+/* Copy `n_pos` positions of plain position-major context into / out of the pool
+ * layout for (layer, row): dev_k, dev_v are [H_kv][n_pos][hd] in the model dtype. */
+int ee_kv_write_context(const ee_model* m, ee_kv* kv, int layer, int row, int pos0, int n_pos,
+                        const void* dev_k, const void* dev_v, void* stream);
+int ee_kv_read_context(const ee_model* m, const ee_kv* kv, int layer, int row, int pos0, int n_pos,
+                       void* dev_k, void* dev_v, void* stream);
+
+/* Batch state: residual stream, row lists, positions, outputs.  The caller
+ * provides dev_state (ee_batch_state_bytes) and dev_workspace
+ * (ee_workspace_bytes), both 256-byte aligned. */
+size_t ee_batch_state_bytes(const ee_model* m, int B);
+size_t ee_workspace_bytes(const ee_model* m, int B);
+int ee_batch_bind(const ee_model* m, int B, void* dev_state, size_t state_bytes,
+                  void* dev_workspace, size_t workspace_bytes, ee_batch** out);
+int ee_batch_destroy(ee_batch* b);
+
+/* Byte offsets of the fields of the batch state inside dev_state. */
+typedef struct {
+    size_t h;            /* fp32 [B][d]   residual stream, indexed by row id            */
+    size_t tok_in;       /* int32 [B]     input token of the coming step                */
+    size_t pos;          /* int32 [B]     position of that token (= cached positions)   */
+    size_t row_scale;    /* fp32 [B]      multiplier of the exit-head logits            */
+    size_t active_idx;   /* int32 [B]     row ids still in the stack, ascending         */
+    size_t n_active;     /* int32         how many                                      */
+    size_t exited_idx;   /* int32 [B]     row ids that left at the last compaction      */
+    size_t n_exited;     /* int32                                                       */
+    size_t head_conf;    /* fp32 [B]      last exit head: confidence of active_idx[i]   */
+    size_t head_tok;     /* int32 [B]     last exit head: argmax token of active_idx[i] */
+    size_t head_exit;    /* uint8 [B]     last exit head: 1 = leaves                    */
+    size_t head_breach;  /* uint8 [B]     last exit head: leaves below the threshold    */
+    size_t out_tok;      /* int32 [B]     emitted token per row id                      */
+    size_t out_layer;    /* int32 [B]     layer the row left at (0 = not yet)           */
+    size_t out_conf;     /* fp32 [B]      its confidence there                          */
+    size_t out_breach;   /* uint8 [B]     1 = left at the last resident layer below th. */
+    size_t exit_counts;  /* int32 [EE_MAX_EXITS] rows that left at each exit (cumulative) */
+    size_t breach_count; /* int32         cumulative number of breaches                  */
+    size_t status;       /* int32         0, or a bit set by a kernel that refused work: */
+                         /*               1 = a row's position reached its capacity      */
+                         /*               2 = an input token outside the vocabulary      */
+} ee_batch_layout;
+int ee_batch_get_layout(const ee_model* m, int B, ee_batch_layout* out);
+
+/* Start from given tokens / positions / scales (device arrays [B]; dev_row_scale
+ * may be NULL = 1.0): all B rows active, outputs and counters cleared. */
+int ee_batch_reset(ee_batch* b, const int32_t* dev_tok_in, const int32_t* dev_pos,
+                   const float* dev_row_scale, void* stream);
+/* New per-row logit scales for the coming step. */
+int ee_batch_set_row_scale(ee_batch* b, const float* dev_row_scale, void* stream);
+/* All B rows active again, h = embedding of tok_in (what ee_decode_step does first). */
+int ee_batch_begin_step(const ee_model* m, ee_batch* b, void* stream);
+
+/* ------------------------------------------------------------------ hot path */
+
+/* One decoder layer on the active rows (Sec. 5.1: time is layers traversed x
+ * time per layer): h += Attn(RMSNorm(h)) W_o, then h += SwiGLU-FFN(RMSNorm(h));
+ * appends the rows' K and V of this layer at their positions.
+ * Errors: EE_ERR_LAYER_NOT_RESIDENT if the layer was never set. */
+int ee_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, void* stream);
+
+/* Exit head `exit_idx` on the active rows (Sec. 2.1: a token leaves if its
+ * probability meets the threshold): z = scale_b * (RMSNorm(h_b) W_exit),
+ * confidence = max softmax probability, token = lowest-index argmax,
+ * leaves = confidence >= threshold or force_exit (the layer is the last
+ * resident one, Sec. 3.3.3), breach = force_exit and confidence < threshold.
+ * Writes head_conf/head_tok/head_exit/head_breach for i < n_active.  Logits are
+ * not stored unless dev_dbg_logits (fp32 [B][V], row i = active_idx[i]) is given. */
+int ee_exit_head(const ee_model* m, int exit_idx, float threshold, int force_exit,
+                 ee_batch* b, float* dev_dbg_logits, void* stream);
+
+/* Order-preserving compaction of the active rows by head_exit: survivors stay in
+ * active_idx (ascending), leavers go to exited_idx; the leavers' token, layer,
+ * confidence and breach flag are scattered to out_*[row id]; n_active, n_exited,
+ * exit_counts[exit_idx] and breach_count are updated on the device. */
+int ee_compact_active(ee_batch* b, int exit_idx, int exit_layer, void* stream);
+
+/* K and V of layers (from_layer_excl, to_layer_incl] for the rows in exited_idx,
+ * from their hidden state at the exit (Sec. 2.2: skipped layers still get their
+ * KV): x = RMSNorm(h_b; g_attn of that layer), K = RoPE(x W_k, pos_b), V = x W_v. */
+int ee_fill_skipped_kv(const ee_model* m, int from_layer_excl, int to_layer_incl,
+                       ee_kv* kv, ee_batch* b, void* stream);
+
+/* One whole early-exit decode step: embed tok_in; for l = 1..R run the layer on
+ * the active rows and, where l carries an exit, the exit head, the compaction
+ * and the fill of skipped layers; then pos += 1 and tok_in = out_tok for every
+ * row.  host_thresholds holds one value per resident exit; values <= 0 always
+ * exit, values > 1 never do (except at R).
+ * Errors: EE_ERR_EXIT_NOT_RESIDENT if layer R carries no (set) exit head,
+ * EE_ERR_INVALID_ARG if the resident layers are not exactly 1..R, if
+ * n_thresholds differs from the number of resident exits or a threshold is NaN,
+ * EE_ERR_CAPACITY if the cache was bound for fewer layers than R. */
+int ee_decode_step(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_thresholds,
+                   int n_thresholds, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -360,7 +360,7 @@ int orc_fill_skipped_kv(const orc_model* m, int from_excl, int to_incl, orc_kv* 
 int orc_decode_step(const orc_model* m, orc_kv* kv, const int32_t* tok_in, int32_t* pos,
                     const float* scale, const float* thresholds, int n_thresholds,
                     int32_t* out_tok, int32_t* out_layer, float* out_conf, uint8_t* out_breach,
-                    int32_t* counts, int64_t* layers_run, float* h_out) {
+                    int32_t* counts, int64_t* layers_run, float* h_out, float* conf_trace) {
     if (!m || !kv || !tok_in || !pos || !thresholds || !out_tok || !out_layer || !out_conf || !out_breach)
         return ORC_ERR_ARG;
     const orc_config& c = m->cfg;
@@ -397,6 +397,7 @@ int orc_decode_step(const orc_model* m, orc_kv* kv, const int32_t* tok_in, int32
             float s = scale ? scale[b] : 1.0f;
             rc = orc_exit_head(m, e, &h[(size_t)b * d], s, nullptr, &conf, &tok);
             if (rc != ORC_OK) return rc;
+            if (conf_trace) conf_trace[(size_t)b * c.n_exits + e] = conf;
             bool met = conf >= th;           // "meets" the threshold
             bool last = (l == R);            // nothing deeper is loaded
             if (!(met || last)) continue;

@@ -120,11 +120,13 @@ int orc_fill_skipped_kv(const orc_model* m, int from_excl, int to_incl, orc_kv* 
  *   pos is advanced by one for every row.  counts[e] += rows that left at
  *   resident exit e.  layers_run (nullable): number of (row, layer) pairs
  *   executed.  h_out (nullable, [B][d]): each row's hidden state at its exit.
+ *   conf_trace (nullable, [B][n_exits]): the confidence each row had at every
+ *   exit it reached; entries of exits it did not reach are left untouched.
  */
 int orc_decode_step(const orc_model* m, orc_kv* kv, const int32_t* tok_in, int32_t* pos,
                     const float* scale, const float* thresholds, int n_thresholds,
                     int32_t* out_tok, int32_t* out_layer, float* out_conf, uint8_t* out_breach,
-                    int32_t* counts, int64_t* layers_run, float* h_out);
+                    int32_t* counts, int64_t* layers_run, float* h_out, float* conf_trace);
 
 /* Full-depth decode with no exit logic at all: every row runs layers 1..R and
  * takes the token of the exit head at R.  Written separately from

@@ -72,9 +72,12 @@ class OracleModel:
         self.h = h
 
     def __del__(self):
-        if getattr(self, "h", None):
-            lib().orc_model_destroy(self.h)
-            self.h = None
+        try:
+            if getattr(self, "h", None):
+                lib().orc_model_destroy(self.h)
+                self.h = None
+        except Exception:   # interpreter shutdown
+            pass
 
     def _w(self, a):
         want = np.uint16 if self.dtype == ORC_BF16 else np.float32
@@ -226,12 +229,13 @@ def decode_step(model, kv, tok_in, pos, scale, thresholds, want_h=False):
     counts = np.zeros(16, np.int32)
     layers_run = C.c_int64(0)
     h_out = np.zeros((B, model.cfg.d_model), np.float32) if want_h else None
+    trace = np.full((B, model.cfg.n_exits), np.nan, np.float32)
     s = kv.struct()
     rc = lib().orc_decode_step(model.h, C.byref(s), _p(tok_in), _p(pos), _p(sc), _p(th), th.size,
                                _p(out_tok), _p(out_layer), _p(out_conf), _p(out_breach), _p(counts),
-                               C.byref(layers_run), _p(h_out))
+                               C.byref(layers_run), _p(h_out), _p(trace))
     return dict(rc=rc, tok=out_tok, layer=out_layer, conf=out_conf, breach=out_breach,
-                counts=counts, layers_run=layers_run.value, h=h_out)
+                counts=counts, layers_run=layers_run.value, h=h_out, conf_trace=trace)
 
 
 def vanilla_step(model, kv, tok_in, pos, scale, want_h=False):

@@ -1,0 +1,450 @@
+// ee_api.cpp -- the C ABI of libee: argument checks, handle bookkeeping and the
+// sequencing of one early-exit decode step.  All arithmetic is in the kernels.
+#include "ee_internal.h"
+
+#include <cmath>
+#include <cstring>
+#include <new>
+
+static thread_local std::string g_last_error;
+
+void ee_set_error(const std::string& msg) { g_last_error = msg; }
+int ee_fail(int code, const std::string& msg) {
+    g_last_error = msg;
+    return code;
+}
+
+static hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+extern "C" {
+
+const char* ee_last_error(void) { return g_last_error.c_str(); }
+
+int ee_device_count(void) {
+    int n = 0;
+    hipError_t e = hipGetDeviceCount(&n);
+    if (e != hipSuccess) return ee_fail(EE_ERR_HIP, std::string("hipGetDeviceCount: ") + hipGetErrorString(e));
+    return n;
+}
+
+// ------------------------------------------------------------------ weights
+size_t ee_packed_bytes(int n_out, int n_in) {
+    if (n_out <= 0 || n_in <= 0) return 0;
+    return (size_t)n_out * (size_t)n_in * 2;
+}
+
+int ee_pack_weight(const void* dev_src, int n_out, int n_in, void* dev_dst, int tile_offset,
+                   int tile_stride, void* stream) {
+    if (!dev_src || !dev_dst) return ee_fail(EE_ERR_INVALID_ARG, "ee_pack_weight: null pointer");
+    if (n_out <= 0 || n_in <= 0 || n_out % 32 != 0 || n_in % 16 != 0)
+        return ee_fail(EE_ERR_SHAPE, "ee_pack_weight: n_out must be a multiple of 32 and n_in of 16");
+    if (tile_offset < 0 || tile_stride < 1) return ee_fail(EE_ERR_INVALID_ARG, "ee_pack_weight: bad tile placement");
+    return launch_pack_weight(dev_src, n_out, n_in, dev_dst, tile_offset, tile_stride, as_stream(stream));
+}
+
+// ------------------------------------------------------------------ model
+static int check_config(const ee_model_config* c) {
+    if (c->n_layers < 1 || c->d_model < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->d_ffn < 1 ||
+        c->vocab < 1 || c->max_pos < 1)
+        return ee_fail(EE_ERR_SHAPE, "ee_model_create: non-positive dimension");
+    if (c->n_q_heads % c->n_kv_heads != 0 || c->n_q_heads / c->n_kv_heads > 16)
+        return ee_fail(EE_ERR_SHAPE, "ee_model_create: H_q must be a multiple of H_kv with ratio <= 16");
+    if (c->head_dim < 2 || c->head_dim % 2 != 0) return ee_fail(EE_ERR_SHAPE, "ee_model_create: head_dim must be even");
+    if (c->dtype != EE_F32 && c->dtype != EE_BF16) return ee_fail(EE_ERR_DTYPE, "ee_model_create: unknown dtype");
+    if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 1.f))
+        return ee_fail(EE_ERR_INVALID_ARG, "ee_model_create: rms_eps must be >= 0 and rope_theta > 1");
+    if (c->n_exits < 1 || c->n_exits > EE_MAX_EXITS) return ee_fail(EE_ERR_INVALID_ARG, "ee_model_create: n_exits out of range");
+    for (int e = 0; e < c->n_exits; ++e) {
+        if (c->exit_layers[e] < 1 || c->exit_layers[e] > c->n_layers ||
+            (e > 0 && c->exit_layers[e] <= c->exit_layers[e - 1]))
+            return ee_fail(EE_ERR_INVALID_ARG, "ee_model_create: exit_layers must be ascending layers of the model");
+    }
+    if (c->dtype == EE_BF16) {
+        int qd = c->n_q_heads * c->head_dim, qkv = (c->n_q_heads + 2 * c->n_kv_heads) * c->head_dim;
+        if (c->head_dim != 128) return ee_fail(EE_ERR_SHAPE, "ee_model_create: bf16 models need head_dim 128");
+        if (c->d_model % 64 || c->d_ffn % 64 || qd % 64 || qkv % 32 || c->vocab % 32)
+            return ee_fail(EE_ERR_SHAPE, "ee_model_create: bf16 models need d, F, H_q*hd multiples of 64 and "
+                                         "(H_q+2H_kv)*hd, V multiples of 32");
+    } else {
+        if (c->head_dim > 256) return ee_fail(EE_ERR_SHAPE, "ee_model_create: fp32 models need head_dim <= 256");
+        if (c->max_pos > 8192) return ee_fail(EE_ERR_SHAPE, "ee_model_create: fp32 models need max_pos <= 8192");
+    }
+    return EE_OK;
+}
+
+int ee_model_create(const ee_model_config* cfg, ee_model** out) {
+    if (!cfg || !out) return ee_fail(EE_ERR_INVALID_ARG, "ee_model_create: null pointer");
+    int rc = check_config(cfg);
+    if (rc != EE_OK) return rc;
+    ee_model* m = new (std::nothrow) ee_model();
+    if (!m) return ee_fail(EE_ERR_INVALID_ARG, "ee_model_create: out of host memory");
+    m->cfg = *cfg;
+    m->layers.resize(cfg->n_layers);
+    m->resident.assign(cfg->n_layers, 0);
+    hipError_t e = hipGetDevice(&m->device);
+    if (e == hipSuccess)
+        e = hipMalloc((void**)&m->d_rope, (size_t)cfg->max_pos * (cfg->head_dim / 2) * 2 * sizeof(float));
+    if (e != hipSuccess) {
+        delete m;
+        return ee_fail(EE_ERR_HIP, std::string("ee_model_create: ") + hipGetErrorString(e));
+    }
+    rc = launch_rope_table(m->d_rope, cfg->max_pos, cfg->head_dim, (double)cfg->rope_theta, nullptr);
+    if (rc == EE_OK && hipStreamSynchronize(nullptr) != hipSuccess) rc = ee_fail(EE_ERR_HIP, "ee_model_create: rotary table kernel failed");
+    if (rc != EE_OK) {
+        (void)hipFree(m->d_rope);
+        delete m;
+        return rc;
+    }
+    *out = m;
+    return EE_OK;
+}
+
+int ee_model_destroy(ee_model* m) {
+    if (!m) return EE_OK;
+    if (m->d_rope) (void)hipFree(m->d_rope);
+    delete m;
+    return EE_OK;
+}
+
+int ee_model_set_layer(ee_model* m, int layer, const ee_layer_weights* w) {
+    if (!m || !w) return ee_fail(EE_ERR_INVALID_ARG, "ee_model_set_layer: null pointer");
+    if (layer < 1 || layer > m->cfg.n_layers) return ee_fail(EE_ERR_INVALID_ARG, "ee_model_set_layer: layer out of range");
+    if (!w->g_attn || !w->w_qkv || !w->w_o || !w->g_ffn || !w->w_gate_up || !w->w_down)
+        return ee_fail(EE_ERR_INVALID_ARG, "ee_model_set_layer: null weight pointer");
+    m->layers[layer - 1] = *w;
+    m->resident[layer - 1] = 1;
+    return EE_OK;
+}
+
+int ee_model_set_exit(ee_model* m, int exit_idx, const float* gain, const void* w) {
+    if (!m || !gain || !w) return ee_fail(EE_ERR_INVALID_ARG, "ee_model_set_exit: null pointer");
+    if (exit_idx < 0 || exit_idx >= m->cfg.n_exits) return ee_fail(EE_ERR_INVALID_ARG, "ee_model_set_exit: exit index out of range");
+    m->exits[exit_idx].gain = gain;
+    m->exits[exit_idx].w = w;
+    m->exits[exit_idx].set = true;
+    return EE_OK;
+}
+
+int ee_model_set_embed(ee_model* m, const void* emb) {
+    if (!m || !emb) return ee_fail(EE_ERR_INVALID_ARG, "ee_model_set_embed: null pointer");
+    m->emb = emb;
+    return EE_OK;
+}
+
+int ee_model_resident_depth(const ee_model* m) {
+    if (!m) return ee_fail(EE_ERR_INVALID_ARG, "ee_model_resident_depth: null model");
+    int R = 0;
+    while (R < m->cfg.n_layers && m->resident[R]) ++R;
+    for (int l = R; l < m->cfg.n_layers; ++l)
+        if (m->resident[l]) return ee_fail(EE_ERR_INVALID_ARG, "resident layers are not a prefix 1..R");
+    return R;
+}
+
+// ------------------------------------------------------------------ key/value pool
+static size_t elem_size(const ee_model* m) { return m->cfg.dtype == EE_BF16 ? 2 : 4; }
+
+static int check_capacity(const ee_model* m, const int32_t* cap, int B, int64_t* total) {
+    if (!m || !cap || B < 1) return ee_fail(EE_ERR_INVALID_ARG, "key/value pool: null pointer or empty batch");
+    int64_t T = 0;
+    for (int b = 0; b < B; ++b) {
+        if (cap[b] < 1 || cap[b] > m->cfg.max_pos)
+            return ee_fail(EE_ERR_CAPACITY, "key/value pool: row capacity must be in 1..max_pos");
+        if (m->cfg.dtype == EE_BF16 && cap[b] % 32 != 0)
+            return ee_fail(EE_ERR_SHAPE, "key/value pool: bf16 row capacity must be a multiple of 32");
+        T += cap[b];
+    }
+    *total = T;
+    return EE_OK;
+}
+
+size_t ee_kv_pool_bytes(const ee_model* m, int n_resident_layers, const int32_t* host_capacity, int B) {
+    int64_t T = 0;
+    if (n_resident_layers < 1 || check_capacity(m, host_capacity, B, &T) != EE_OK) return 0;
+    return (size_t)n_resident_layers * (size_t)T * 2 * m->cfg.n_kv_heads * m->cfg.head_dim * elem_size(m);
+}
+
+int ee_kv_bind(const ee_model* m, void* dev_pool, size_t pool_bytes, int n_resident_layers,
+               const int32_t* host_capacity, int B, ee_kv** out) {
+    if (!m || !dev_pool || !out) return ee_fail(EE_ERR_INVALID_ARG, "ee_kv_bind: null pointer");
+    if (n_resident_layers < 1 || n_resident_layers > m->cfg.n_layers)
+        return ee_fail(EE_ERR_INVALID_ARG, "ee_kv_bind: layer count out of range");
+    int64_t T = 0;
+    int rc = check_capacity(m, host_capacity, B, &T);
+    if (rc != EE_OK) return rc;
+    size_t need = ee_kv_pool_bytes(m, n_resident_layers, host_capacity, B);
+    if (pool_bytes < need) return ee_fail(EE_ERR_CAPACITY, "ee_kv_bind: pool smaller than ee_kv_pool_bytes");
+    if ((uintptr_t)dev_pool % 256 != 0) return ee_fail(EE_ERR_INVALID_ARG, "ee_kv_bind: pool must be 256-byte aligned");
+    ee_kv* kv = new (std::nothrow) ee_kv();
+    if (!kv) return ee_fail(EE_ERR_INVALID_ARG, "ee_kv_bind: out of host memory");
+    kv->pool = (char*)dev_pool;
+    kv->bytes = pool_bytes;
+    kv->n_layers = n_resident_layers;
+    kv->B = B;
+    kv->T = T;
+    kv->h_cap.assign(host_capacity, host_capacity + B);
+    kv->h_off.resize(B);
+    int64_t acc = 0;
+    for (int b = 0; b < B; ++b) { kv->h_off[b] = acc; acc += host_capacity[b]; }
+    hipError_t e = hipMalloc((void**)&kv->d_cap, sizeof(int32_t) * B);
+    if (e == hipSuccess) e = hipMalloc((void**)&kv->d_off, sizeof(int64_t) * B);
+    if (e == hipSuccess) e = hipMemcpy(kv->d_cap, kv->h_cap.data(), sizeof(int32_t) * B, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(kv->d_off, kv->h_off.data(), sizeof(int64_t) * B, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        ee_kv_destroy(kv);
+        return ee_fail(EE_ERR_HIP, std::string("ee_kv_bind: ") + hipGetErrorString(e));
+    }
+    *out = kv;
+    return EE_OK;
+}
+
+int ee_kv_destroy(ee_kv* kv) {
+    if (!kv) return EE_OK;
+    if (kv->d_cap) (void)hipFree(kv->d_cap);
+    if (kv->d_off) (void)hipFree(kv->d_off);
+    delete kv;
+    return EE_OK;
+}
+
+static int check_context_args(const ee_model* m, const ee_kv* kv, int layer, int row, int pos0, int n_pos,
+                              const void* k, const void* v) {
+    if (!m || !kv || !k || !v) return ee_fail(EE_ERR_INVALID_ARG, "key/value context copy: null pointer");
+    if (layer < 1 || layer > kv->n_layers) return ee_fail(EE_ERR_CAPACITY, "key/value context copy: layer not in the pool");
+    if (row < 0 || row >= kv->B) return ee_fail(EE_ERR_CAPACITY, "key/value context copy: row out of range");
+    if (pos0 < 0 || n_pos < 0 || (int64_t)pos0 + n_pos > kv->h_cap[row])
+        return ee_fail(EE_ERR_CAPACITY, "key/value context copy: positions exceed the row capacity");
+    return EE_OK;
+}
+
+int ee_kv_write_context(const ee_model* m, ee_kv* kv, int layer, int row, int pos0, int n_pos,
+                        const void* dev_k, const void* dev_v, void* stream) {
+    int rc = check_context_args(m, kv, layer, row, pos0, n_pos, dev_k, dev_v);
+    if (rc != EE_OK) return rc;
+    return launch_kv_copy_context(m, kv, layer, row, pos0, n_pos, const_cast<void*>(dev_k),
+                                  const_cast<void*>(dev_v), true, as_stream(stream));
+}
+
+int ee_kv_read_context(const ee_model* m, const ee_kv* kv, int layer, int row, int pos0, int n_pos,
+                       void* dev_k, void* dev_v, void* stream) {
+    int rc = check_context_args(m, kv, layer, row, pos0, n_pos, dev_k, dev_v);
+    if (rc != EE_OK) return rc;
+    return launch_kv_copy_context(m, kv, layer, row, pos0, n_pos, dev_k, dev_v, false, as_stream(stream));
+}
+
+// ------------------------------------------------------------------ batch
+static void lay_state(const ee_model* m, int B, ee_batch_layout* L, size_t* total) {
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    L->h = take((size_t)B * m->cfg.d_model * 4);
+    L->tok_in = take((size_t)B * 4);
+    L->pos = take((size_t)B * 4);
+    L->row_scale = take((size_t)B * 4);
+    L->active_idx = take((size_t)B * 4);
+    L->n_active = take(4);
+    L->exited_idx = take((size_t)B * 4);
+    L->n_exited = take(4);
+    L->head_conf = take((size_t)B * 4);
+    L->head_tok = take((size_t)B * 4);
+    L->head_exit = take((size_t)B);
+    L->head_breach = take((size_t)B);
+    L->out_tok = take((size_t)B * 4);
+    L->out_layer = take((size_t)B * 4);
+    L->out_conf = take((size_t)B * 4);
+    L->out_breach = take((size_t)B);
+    L->exit_counts = take(EE_MAX_EXITS * 4);
+    L->breach_count = take(4);
+    L->status = take(4);
+    *total = o;
+}
+
+static void lay_workspace(const ee_model* m, int B, WsLayout* W) {
+    const ee_model_config& c = m->cfg;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    size_t Mpad = align_up((size_t)B, 32);
+    size_t qd = (size_t)c.n_q_heads * c.head_dim, qkv = qd + 2 * (size_t)c.n_kv_heads * c.head_dim;
+    size_t kvn = 2 * (size_t)c.n_kv_heads * c.head_dim;
+    if (c.dtype == EE_BF16) {
+        size_t n_part = (size_t)c.vocab / 32;
+        W->x = take(Mpad * c.d_model * 2);
+        W->qkv = take(Mpad * qkv * 4);
+        W->q_hi = take(Mpad * qd * 2);
+        W->q_lo = take(Mpad * qd * 2);
+        W->ao = take(Mpad * qd * 2);
+        W->act = take(Mpad * c.d_ffn * 2);
+        W->part_max = take(Mpad * n_part * 4);
+        W->part_sum = take(Mpad * n_part * 4);
+        W->part_arg = take(Mpad * n_part * 4);
+        W->logits = take(0);
+        W->fill_x = take(Mpad * c.d_model * 2);
+        W->fill_kv = take(Mpad * kvn * 4);
+    } else {
+        size_t wide = (size_t)c.vocab > 2 * (size_t)c.d_ffn ? (size_t)c.vocab : 2 * (size_t)c.d_ffn;
+        W->x = take(Mpad * c.d_model * 4);
+        W->qkv = take(Mpad * qkv * 4);
+        W->q_hi = take(0);
+        W->q_lo = take(0);
+        W->ao = take(Mpad * qd * 4);
+        W->act = take(Mpad * c.d_ffn * 4);
+        W->part_max = take(Mpad * 4);
+        W->part_sum = take(Mpad * 4);
+        W->part_arg = take(Mpad * 4);
+        W->logits = take(Mpad * wide * 4);
+        W->fill_x = take(Mpad * c.d_model * 4);
+        W->fill_kv = take(Mpad * kvn * 4);
+    }
+    W->total = o;
+}
+
+size_t ee_batch_state_bytes(const ee_model* m, int B) {
+    if (!m || B < 1) return 0;
+    ee_batch_layout L;
+    size_t t = 0;
+    lay_state(m, B, &L, &t);
+    return t;
+}
+
+size_t ee_workspace_bytes(const ee_model* m, int B) {
+    if (!m || B < 1) return 0;
+    WsLayout W;
+    lay_workspace(m, B, &W);
+    return W.total;
+}
+
+int ee_batch_get_layout(const ee_model* m, int B, ee_batch_layout* out) {
+    if (!m || !out || B < 1) return ee_fail(EE_ERR_INVALID_ARG, "ee_batch_get_layout: bad argument");
+    size_t t = 0;
+    lay_state(m, B, out, &t);
+    return EE_OK;
+}
+
+int ee_batch_bind(const ee_model* m, int B, void* dev_state, size_t state_bytes, void* dev_workspace,
+                  size_t workspace_bytes, ee_batch** out) {
+    if (!m || !dev_state || !dev_workspace || !out) return ee_fail(EE_ERR_INVALID_ARG, "ee_batch_bind: null pointer");
+    if (B < 1 || B > 65535) return ee_fail(EE_ERR_CAPACITY, "ee_batch_bind: batch must be in 1..65535");
+    if ((uintptr_t)dev_state % 256 != 0 || (uintptr_t)dev_workspace % 256 != 0)
+        return ee_fail(EE_ERR_INVALID_ARG, "ee_batch_bind: buffers must be 256-byte aligned");
+    if (state_bytes < ee_batch_state_bytes(m, B) || workspace_bytes < ee_workspace_bytes(m, B))
+        return ee_fail(EE_ERR_CAPACITY, "ee_batch_bind: state or workspace buffer too small");
+    ee_batch* b = new (std::nothrow) ee_batch();
+    if (!b) return ee_fail(EE_ERR_INVALID_ARG, "ee_batch_bind: out of host memory");
+    b->m = m;
+    b->B = B;
+    b->Mpad = (int)align_up((size_t)B, 32);
+    b->state = (char*)dev_state;
+    b->ws = (char*)dev_workspace;
+    size_t t = 0;
+    lay_state(m, B, &b->L, &t);
+    lay_workspace(m, B, &b->W);
+    *out = b;
+    return EE_OK;
+}
+
+int ee_batch_destroy(ee_batch* b) {
+    delete b;
+    return EE_OK;
+}
+
+int ee_batch_reset(ee_batch* b, const int32_t* dev_tok_in, const int32_t* dev_pos, const float* dev_row_scale,
+                   void* stream) {
+    if (!b || !dev_tok_in || !dev_pos) return ee_fail(EE_ERR_INVALID_ARG, "ee_batch_reset: null pointer");
+    return launch_reset(b, dev_tok_in, dev_pos, dev_row_scale, as_stream(stream));
+}
+
+int ee_batch_set_row_scale(ee_batch* b, const float* dev_row_scale, void* stream) {
+    if (!b || !dev_row_scale) return ee_fail(EE_ERR_INVALID_ARG, "ee_batch_set_row_scale: null pointer");
+    return launch_set_scale(b, dev_row_scale, as_stream(stream));
+}
+
+int ee_batch_begin_step(const ee_model* m, ee_batch* b, void* stream) {
+    if (!m || !b || b->m != m) return ee_fail(EE_ERR_INVALID_ARG, "ee_batch_begin_step: batch not bound to this model");
+    if (!m->emb) return ee_fail(EE_ERR_INVALID_ARG, "ee_batch_begin_step: embedding not set");
+    return launch_begin_step(m, b, as_stream(stream));
+}
+
+// ------------------------------------------------------------------ hot path
+static int check_pair(const char* who, const ee_model* m, const ee_kv* kv, const ee_batch* b) {
+    if (!m || !b || (kv == nullptr)) return ee_fail(EE_ERR_INVALID_ARG, std::string(who) + ": null handle");
+    if (b->m != m) return ee_fail(EE_ERR_INVALID_ARG, std::string(who) + ": batch not bound to this model");
+    if (kv->B != b->B) return ee_fail(EE_ERR_CAPACITY, std::string(who) + ": cache and batch have different row counts");
+    return EE_OK;
+}
+
+int ee_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, void* stream) {
+    int rc = check_pair("ee_layer_forward", m, kv, b);
+    if (rc != EE_OK) return rc;
+    if (layer < 1 || layer > m->cfg.n_layers) return ee_fail(EE_ERR_INVALID_ARG, "ee_layer_forward: layer out of range");
+    if (!m->resident[layer - 1]) return ee_fail(EE_ERR_LAYER_NOT_RESIDENT, "ee_layer_forward: layer is not resident");
+    if (layer > kv->n_layers) return ee_fail(EE_ERR_CAPACITY, "ee_layer_forward: cache holds fewer layers");
+    return m->cfg.dtype == EE_BF16 ? bf16_layer_forward(m, layer, kv, b, as_stream(stream))
+                                   : f32_layer_forward(m, layer, kv, b, as_stream(stream));
+}
+
+int ee_exit_head(const ee_model* m, int exit_idx, float threshold, int force_exit, ee_batch* b,
+                 float* dev_dbg_logits, void* stream) {
+    if (!m || !b || b->m != m) return ee_fail(EE_ERR_INVALID_ARG, "ee_exit_head: batch not bound to this model");
+    if (exit_idx < 0 || exit_idx >= m->cfg.n_exits) return ee_fail(EE_ERR_INVALID_ARG, "ee_exit_head: exit index out of range");
+    if (!m->exits[exit_idx].set) return ee_fail(EE_ERR_EXIT_NOT_RESIDENT, "ee_exit_head: exit head not set");
+    if (std::isnan(threshold)) return ee_fail(EE_ERR_INVALID_ARG, "ee_exit_head: threshold is NaN");
+    return m->cfg.dtype == EE_BF16
+               ? bf16_exit_head(m, exit_idx, threshold, force_exit ? 1 : 0, b, dev_dbg_logits, as_stream(stream))
+               : f32_exit_head(m, exit_idx, threshold, force_exit ? 1 : 0, b, dev_dbg_logits, as_stream(stream));
+}
+
+int ee_compact_active(ee_batch* b, int exit_idx, int exit_layer, void* stream) {
+    if (!b) return ee_fail(EE_ERR_INVALID_ARG, "ee_compact_active: null batch");
+    if (exit_idx < 0 || exit_idx >= EE_MAX_EXITS) return ee_fail(EE_ERR_INVALID_ARG, "ee_compact_active: exit index out of range");
+    return launch_compact(b, exit_idx, exit_layer, as_stream(stream));
+}
+
+int ee_fill_skipped_kv(const ee_model* m, int from_layer_excl, int to_layer_incl, ee_kv* kv, ee_batch* b,
+                       void* stream) {
+    int rc = check_pair("ee_fill_skipped_kv", m, kv, b);
+    if (rc != EE_OK) return rc;
+    if (from_layer_excl < 0 || to_layer_incl > m->cfg.n_layers)
+        return ee_fail(EE_ERR_INVALID_ARG, "ee_fill_skipped_kv: layer range out of the model");
+    for (int l = from_layer_excl + 1; l <= to_layer_incl; ++l)
+        if (!m->resident[l - 1]) return ee_fail(EE_ERR_LAYER_NOT_RESIDENT, "ee_fill_skipped_kv: layer is not resident");
+    if (to_layer_incl > kv->n_layers) return ee_fail(EE_ERR_CAPACITY, "ee_fill_skipped_kv: cache holds fewer layers");
+    if (from_layer_excl >= to_layer_incl) return EE_OK;
+    return m->cfg.dtype == EE_BF16 ? bf16_fill_kv(m, from_layer_excl, to_layer_incl, kv, b, as_stream(stream))
+                                   : f32_fill_kv(m, from_layer_excl, to_layer_incl, kv, b, as_stream(stream));
+}
+
+int ee_decode_step(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_thresholds, int n_thresholds,
+                   void* stream) {
+    int rc = check_pair("ee_decode_step", m, kv, b);
+    if (rc != EE_OK) return rc;
+    if (!host_thresholds) return ee_fail(EE_ERR_INVALID_ARG, "ee_decode_step: null thresholds");
+    int R = ee_model_resident_depth(m);
+    if (R < 0) return R;
+    if (R == 0) return ee_fail(EE_ERR_LAYER_NOT_RESIDENT, "ee_decode_step: no layer is resident");
+    const ee_model_config& c = m->cfg;
+    int n_res = 0;
+    for (int e = 0; e < c.n_exits; ++e)
+        if (c.exit_layers[e] <= R) ++n_res;
+    if (n_res == 0 || c.exit_layers[n_res - 1] != R)
+        return ee_fail(EE_ERR_EXIT_NOT_RESIDENT, "ee_decode_step: the deepest resident layer carries no exit head");
+    for (int e = 0; e < n_res; ++e)
+        if (!m->exits[e].set) return ee_fail(EE_ERR_EXIT_NOT_RESIDENT, "ee_decode_step: a resident exit head was never set");
+    if (n_thresholds != n_res) return ee_fail(EE_ERR_INVALID_ARG, "ee_decode_step: one threshold per resident exit is required");
+    for (int e = 0; e < n_res; ++e)
+        if (std::isnan(host_thresholds[e])) return ee_fail(EE_ERR_INVALID_ARG, "ee_decode_step: threshold is NaN");
+    if (kv->n_layers < R) return ee_fail(EE_ERR_CAPACITY, "ee_decode_step: cache was bound for fewer layers than are resident");
+    if (!m->emb) return ee_fail(EE_ERR_INVALID_ARG, "ee_decode_step: embedding not set");
+
+    void* s = stream;
+    rc = ee_batch_begin_step(m, b, s);
+    int next_exit = 0;
+    for (int l = 1; l <= R && rc == EE_OK; ++l) {
+        rc = ee_layer_forward(m, l, kv, b, s);
+        if (rc != EE_OK || c.exit_layers[next_exit] != l) continue;
+        int e = next_exit++;
+        rc = ee_exit_head(m, e, host_thresholds[e], l == R, b, nullptr, s);
+        if (rc == EE_OK) rc = ee_compact_active(b, e, l, s);
+        if (rc == EE_OK) rc = ee_fill_skipped_kv(m, l, R, kv, b, s);
+    }
+    if (rc == EE_OK) rc = launch_end_step(b, as_stream(s));
+    return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,67 @@
+// ee_device.h -- small device-side helpers shared by the kernels of libee.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ee_internal.h"
+
+typedef uint16_t bf16_t;   // storage: upper 16 bits of the fp32 pattern
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) {
+    return __uint_as_float(((uint32_t)b) << 16);
+}
+
+// round to nearest even; inf/nan pass through
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7f800000u) == 0x7f800000u) return (bf16_t)(u >> 16);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+// element offset (in elements of the model dtype) of the (layer, row, kv-head) block
+__device__ __forceinline__ int64_t kv_block(const KvView& kv, int b, int g, int cap_b) {
+    return ((int64_t)kv.layer0 * kv.T + kv.off[b]) * (2LL * kv.n_kv_heads * kv.head_dim) +
+           (int64_t)g * 2LL * cap_b * kv.head_dim;
+}
+
+// offset of V(p, i) relative to the start of the V part, bf16 grouped layout
+__device__ __forceinline__ int64_t v_bf16_offset(int p, int i, int hd) {
+    int q = p >> 5, r = p & 31;
+    return ((int64_t)(q * 4 + ((r & 15) >> 2)) * hd + i) * 8 + ((r >> 4) << 2) + (r & 3);
+}
+
+// index (in 8-element chunks) of the chunk holding row `row`, columns [c, c+8) (c % 8 == 0)
+// of an activation matrix with K columns stored in 32x16 tile order
+__device__ __forceinline__ int64_t afrag_chunk(int row, int c, int KB /* K/16 */) {
+    int mb = row >> 5, kb = c >> 4;
+    int lane = (row & 31) + (((c & 15) >> 3) << 5);
+    return ((int64_t)mb * KB + kb) * 64 + lane;
+}
+
+template <int THREADS>
+__device__ __forceinline__ float block_sum(float v, float* smem /* THREADS/64 floats */) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) smem[w] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < THREADS / 64; ++i) t += smem[i];
+    __syncthreads();
+    return t;
+}
+
+// Partial softmax statistics of a range of logits: maximum, sum of exp(z - max),
+// lowest index attaining the maximum.  Merging is associative up to rounding.
+struct Stat { float m; float s; int a; };
+
+__device__ __forceinline__ Stat stat_merge(Stat x, Stat y) {
+    Stat r;
+    r.m = fmaxf(x.m, y.m);
+    r.s = x.s * expf(x.m - r.m) + y.s * expf(y.m - r.m);
+    r.a = (x.m > y.m) ? x.a : ((y.m > x.m) ? y.a : min(x.a, y.a));
+    return r;
+}

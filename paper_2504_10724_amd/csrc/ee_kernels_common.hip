@@ -1,0 +1,315 @@
+// ee_kernels_common.hip -- kernels of the early-exit decode step that do not
+// depend on the weight format: step begin/end, exit decision, order-preserving
+// compaction, weight repacking, key/value pool import/export, rotary table.
+#include "ee_device.h"
+
+#include <float.h>
+
+// ------------------------------------------------------------------ rotary table
+// table[pos][i] = (cos, sin)(pos * theta^(-2i/hd)), evaluated in fp64, stored fp32
+__global__ void k_rope_table(float* __restrict__ table, int max_pos, int half, int hd, double theta) {
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)max_pos * half) return;
+    int pos = (int)(idx / half), i = (int)(idx % half);
+    double angle = (double)pos * pow(theta, -2.0 * (double)i / (double)hd);
+    table[2 * idx]     = (float)cos(angle);
+    table[2 * idx + 1] = (float)sin(angle);
+}
+
+int launch_rope_table(float* d_table, int max_pos, int hd, double theta, hipStream_t s) {
+    int64_t n = (int64_t)max_pos * (hd / 2);
+    hipLaunchKernelGGL(k_rope_table, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, d_table, max_pos,
+                       hd / 2, hd, theta);
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
+// ------------------------------------------------------------------ step begin / end
+// One block per row: every row becomes active again and its residual stream is
+// the embedding of its input token.
+__global__ void __launch_bounds__(256)
+k_begin_step(const int32_t* __restrict__ tok_in, const void* __restrict__ emb, int is_bf16, int d, int V,
+             float* __restrict__ h, int32_t* __restrict__ active_idx, int32_t* __restrict__ n_active,
+             int32_t* __restrict__ n_exited, int32_t* __restrict__ out_layer, int32_t* __restrict__ status, int B) {
+    int b = blockIdx.x;
+    int tok = tok_in[b];
+    if (tok < 0 || tok >= V) {
+        if (threadIdx.x == 0) atomicOr(status, 2);
+        tok = 0;
+    }
+    if (threadIdx.x == 0) {
+        active_idx[b] = b;
+        out_layer[b] = 0;
+        if (b == 0) { *n_active = B; *n_exited = 0; }
+    }
+    float* hr = h + (int64_t)b * d;
+    if (is_bf16) {
+        const bf16_t* e = (const bf16_t*)emb + (int64_t)tok * d;
+        for (int i = threadIdx.x; i < d; i += blockDim.x) hr[i] = bf16_to_f32(e[i]);
+    } else {
+        const float* e = (const float*)emb + (int64_t)tok * d;
+        for (int i = threadIdx.x; i < d; i += blockDim.x) hr[i] = e[i];
+    }
+}
+
+int launch_begin_step(const ee_model* m, ee_batch* b, hipStream_t s) {
+    const ee_batch_layout& L = b->L;
+    hipLaunchKernelGGL(k_begin_step, dim3(b->B), dim3(256), 0, s, b->st<int32_t>(L.tok_in), m->emb,
+                       m->cfg.dtype == EE_BF16 ? 1 : 0, m->cfg.d_model, m->cfg.vocab, b->st<float>(L.h),
+                       b->st<int32_t>(L.active_idx), b->st<int32_t>(L.n_active), b->st<int32_t>(L.n_exited),
+                       b->st<int32_t>(L.out_layer), b->st<int32_t>(L.status), b->B);
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
+// every row advances one position, whatever layer it left at, and the token it
+// emitted is the input of the next step
+__global__ void k_end_step(int32_t* __restrict__ pos, int32_t* __restrict__ tok_in,
+                           const int32_t* __restrict__ out_tok, int B) {
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    pos[b] += 1;
+    tok_in[b] = out_tok[b];
+}
+
+int launch_end_step(ee_batch* b, hipStream_t s) {
+    const ee_batch_layout& L = b->L;
+    hipLaunchKernelGGL(k_end_step, dim3((b->B + 255) / 256), dim3(256), 0, s, b->st<int32_t>(L.pos),
+                       b->st<int32_t>(L.tok_in), b->st<int32_t>(L.out_tok), b->B);
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
+__global__ void k_reset(const int32_t* __restrict__ tok, const int32_t* __restrict__ pos,
+                        const float* __restrict__ scale, int B, int32_t* s_tok, int32_t* s_pos, float* s_scale,
+                        int32_t* active_idx, int32_t* n_active, int32_t* n_exited, int32_t* out_tok,
+                        int32_t* out_layer, float* out_conf, uint8_t* out_breach, int32_t* exit_counts,
+                        int32_t* breach_count, int32_t* status) {
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) {
+        s_tok[b] = tok[b];
+        s_pos[b] = pos[b];
+        s_scale[b] = scale ? scale[b] : 1.0f;
+        active_idx[b] = b;
+        out_tok[b] = -1;
+        out_layer[b] = 0;
+        out_conf[b] = 0.f;
+        out_breach[b] = 0;
+    }
+    if (b < EE_MAX_EXITS) exit_counts[b] = 0;
+    if (b == 0) { *n_active = B; *n_exited = 0; *breach_count = 0; *status = 0; }
+}
+
+int launch_reset(ee_batch* b, const int32_t* tok, const int32_t* pos, const float* scale, hipStream_t s) {
+    const ee_batch_layout& L = b->L;
+    int n = b->B > EE_MAX_EXITS ? b->B : EE_MAX_EXITS;
+    hipLaunchKernelGGL(k_reset, dim3((n + 255) / 256), dim3(256), 0, s, tok, pos, scale, b->B,
+                       b->st<int32_t>(L.tok_in), b->st<int32_t>(L.pos), b->st<float>(L.row_scale),
+                       b->st<int32_t>(L.active_idx), b->st<int32_t>(L.n_active), b->st<int32_t>(L.n_exited),
+                       b->st<int32_t>(L.out_tok), b->st<int32_t>(L.out_layer), b->st<float>(L.out_conf),
+                       b->st<uint8_t>(L.out_breach), b->st<int32_t>(L.exit_counts),
+                       b->st<int32_t>(L.breach_count), b->st<int32_t>(L.status));
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
+__global__ void k_set_scale(const float* __restrict__ scale, float* __restrict__ s_scale, int B) {
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) s_scale[b] = scale[b];
+}
+
+int launch_set_scale(ee_batch* b, const float* scale, hipStream_t s) {
+    hipLaunchKernelGGL(k_set_scale, dim3((b->B + 255) / 256), dim3(256), 0, s, scale,
+                       b->st<float>(b->L.row_scale), b->B);
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
+// ------------------------------------------------------------------ compaction
+// Order-preserving split of the active list by head_exit.  One workgroup; each
+// wave turns its 64 flags into a ballot mask, a lane's rank among the kept (or
+// leaving) rows of its wave is the population count of the mask below the
+// lane, and the wave totals are combined through LDS.  Lists longer than the
+// workgroup are processed in consecutive chunks with running offsets.
+#define COMPACT_THREADS 512
+__global__ void __launch_bounds__(COMPACT_THREADS)
+k_compact(int32_t* __restrict__ active_idx, int32_t* __restrict__ n_active, int32_t* __restrict__ exited_idx,
+          int32_t* __restrict__ n_exited, const float* __restrict__ head_conf,
+          const int32_t* __restrict__ head_tok, const uint8_t* __restrict__ head_exit,
+          const uint8_t* __restrict__ head_breach, int32_t* __restrict__ out_tok,
+          int32_t* __restrict__ out_layer, float* __restrict__ out_conf, uint8_t* __restrict__ out_breach,
+          int32_t* __restrict__ exit_counts, int32_t* __restrict__ breach_count, int exit_idx, int exit_layer,
+          int B) {
+    __shared__ int s_keep[COMPACT_THREADS / 64];
+    __shared__ int s_gone[COMPACT_THREADS / 64];
+    __shared__ int s_brch[COMPACT_THREADS / 64];
+    int n = *n_active;
+    if (n > B) n = B;
+    int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int keep_base = 0, gone_base = 0, breaches = 0;
+    for (int base = 0; base < n; base += COMPACT_THREADS) {
+        int i = base + threadIdx.x;
+        bool valid = i < n;
+        int row = valid ? active_idx[i] : 0;
+        bool leaves = valid && head_exit[i] != 0;
+        bool stays = valid && !leaves;
+        bool br = leaves && head_breach[i] != 0;
+        unsigned long long mk = __ballot(stays), mg = __ballot(leaves), mb = __ballot(br);
+        unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+        int rk = __popcll(mk & below), rg = __popcll(mg & below);
+        if (lane == 0) { s_keep[w] = __popcll(mk); s_gone[w] = __popcll(mg); s_brch[w] = __popcll(mb); }
+        __syncthreads();   // all reads of active_idx[base ..] are done, wave totals visible
+        int ko = keep_base, go = gone_base, tk = 0, tg = 0, tb = 0;
+        for (int j = 0; j < COMPACT_THREADS / 64; ++j) {
+            if (j < w) { ko += s_keep[j]; go += s_gone[j]; }
+            tk += s_keep[j]; tg += s_gone[j]; tb += s_brch[j];
+        }
+        if (stays) active_idx[ko + rk] = row;          // ko + rk <= i: never overtakes a later read
+        if (leaves) {
+            exited_idx[go + rg] = row;
+            out_tok[row] = head_tok[i];
+            out_layer[row] = exit_layer;
+            out_conf[row] = head_conf[i];
+            out_breach[row] = br ? 1 : 0;
+        }
+        keep_base += tk; gone_base += tg; breaches += tb;
+        __syncthreads();   // wave totals are consumed before the next chunk overwrites them
+    }
+    if (threadIdx.x == 0) {
+        *n_active = keep_base;
+        *n_exited = gone_base;
+        exit_counts[exit_idx] += gone_base;
+        *breach_count += breaches;
+    }
+}
+
+int launch_compact(ee_batch* b, int exit_idx, int exit_layer, hipStream_t s) {
+    const ee_batch_layout& L = b->L;
+    hipLaunchKernelGGL(k_compact, dim3(1), dim3(COMPACT_THREADS), 0, s, b->st<int32_t>(L.active_idx),
+                       b->st<int32_t>(L.n_active), b->st<int32_t>(L.exited_idx), b->st<int32_t>(L.n_exited),
+                       b->st<float>(L.head_conf), b->st<int32_t>(L.head_tok), b->st<uint8_t>(L.head_exit),
+                       b->st<uint8_t>(L.head_breach), b->st<int32_t>(L.out_tok), b->st<int32_t>(L.out_layer),
+                       b->st<float>(L.out_conf), b->st<uint8_t>(L.out_breach), b->st<int32_t>(L.exit_counts),
+                       b->st<int32_t>(L.breach_count), exit_idx, exit_layer, b->B);
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
+// ------------------------------------------------------------------ weight repacking
+// one thread per 8-value chunk of the packed matrix
+__global__ void k_pack_weight(const bf16_t* __restrict__ src, int n_out, int n_in, bf16_t* __restrict__ dst,
+                              int tile_off, int tile_stride) {
+    int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int KB = n_in >> 4;
+    int64_t total = (int64_t)(n_out >> 5) * KB * 64;
+    if (c >= total) return;
+    int lane = (int)(c & 63);
+    int64_t t = c >> 6;
+    int kb = (int)(t % KB);
+    int rb = (int)(t / KB);
+    int row = rb * 32 + (lane & 31);
+    int col = kb * 16 + (lane >> 5) * 8;
+    const uint4 v = *reinterpret_cast<const uint4*>(src + (int64_t)row * n_in + col);
+    int64_t dst_tile_row = (int64_t)tile_off + (int64_t)rb * tile_stride;
+    *reinterpret_cast<uint4*>(dst + ((dst_tile_row * KB + kb) * 64 + lane) * 8) = v;
+}
+
+int launch_pack_weight(const void* src, int n_out, int n_in, void* dst, int tile_off, int tile_stride,
+                       hipStream_t s) {
+    int64_t total = (int64_t)(n_out / 32) * (n_in / 16) * 64;
+    hipLaunchKernelGGL(k_pack_weight, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                       (const bf16_t*)src, n_out, n_in, (bf16_t*)dst, tile_off, tile_stride);
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
+// ------------------------------------------------------------------ pool import / export
+// plain [H_kv][n_pos][hd] context <-> pool layout of one (layer, row)
+template <typename T, bool BF16_LAYOUT>
+__global__ void k_kv_copy(KvView kv, int row, int pos0, int n_pos, T* __restrict__ k, T* __restrict__ v,
+                          int to_pool) {
+    int hd = kv.head_dim;
+    int64_t total = (int64_t)kv.n_kv_heads * n_pos * hd;
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    int i = (int)(idx % hd);
+    int p = (int)((idx / hd) % n_pos);
+    int g = (int)(idx / ((int64_t)hd * n_pos));
+    int cap = kv.cap[row];
+    if (pos0 + p >= cap) return;
+    T* base = reinterpret_cast<T*>(kv.pool) + kv_block(kv, row, g, cap);
+    T* kp = base + (int64_t)(pos0 + p) * hd + i;
+    T* vp = base + (int64_t)cap * hd +
+            (BF16_LAYOUT ? v_bf16_offset(pos0 + p, i, hd) : ((int64_t)(pos0 + p) * hd + i));
+    if (to_pool) { *kp = k[idx]; *vp = v[idx]; }
+    else         { k[idx] = *kp; v[idx] = *vp; }
+}
+
+int launch_kv_copy_context(const ee_model* m, const ee_kv* kv, int layer, int row, int pos0, int n_pos,
+                           void* k, void* v, bool to_pool, hipStream_t s) {
+    KvView view{kv->pool, kv->d_cap, kv->d_off, kv->T, m->cfg.n_kv_heads, m->cfg.head_dim, layer - 1};
+    int64_t total = (int64_t)m->cfg.n_kv_heads * n_pos * m->cfg.head_dim;
+    if (total == 0) return EE_OK;
+    dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    if (m->cfg.dtype == EE_BF16)
+        hipLaunchKernelGGL((k_kv_copy<bf16_t, true>), grid, block, 0, s, view, row, pos0, n_pos, (bf16_t*)k,
+                           (bf16_t*)v, to_pool ? 1 : 0);
+    else
+        hipLaunchKernelGGL((k_kv_copy<float, false>), grid, block, 0, s, view, row, pos0, n_pos, (float*)k,
+                           (float*)v, to_pool ? 1 : 0);
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
+// ------------------------------------------------------------------ exit decision
+// Each active row has n_part partial softmax statistics over disjoint column
+// ranges of the (scaled) logits: the range's maximum, the sum of exp(z - max)
+// over the range, and the lowest column attaining the maximum.  This kernel
+// merges them, in a fixed order, into the row's confidence (largest softmax
+// probability = 1 / sum_j exp(z_j - max)) and token, and takes the exit decision:
+// a row leaves when its confidence meets the threshold, or when nothing deeper
+// is resident; leaving below the threshold is a breach.
+__global__ void __launch_bounds__(256)
+k_exit_decide(const float* __restrict__ part_max, const float* __restrict__ part_sum,
+              const int32_t* __restrict__ part_arg, int n_part, const int32_t* __restrict__ n_active, int B,
+              float threshold, int force_exit, float* __restrict__ head_conf, int32_t* __restrict__ head_tok,
+              uint8_t* __restrict__ head_exit, uint8_t* __restrict__ head_breach) {
+    __shared__ Stat sw[4];
+    int i = blockIdx.x;
+    int n = *n_active;
+    if (n > B) n = B;
+    if (i >= n) return;
+    Stat st{-FLT_MAX, 0.f, 0x7fffffff};
+    int64_t base = (int64_t)i * n_part;
+    for (int t = threadIdx.x; t < n_part; t += 256) {
+        Stat p{part_max[base + t], part_sum[base + t], part_arg[base + t]};
+        st = stat_merge(st, p);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        Stat y{__shfl_xor(st.m, o, 64), __shfl_xor(st.s, o, 64), __shfl_xor(st.a, o, 64)};
+        st = stat_merge(st, y);
+    }
+    if ((threadIdx.x & 63) == 0) sw[threadIdx.x >> 6] = st;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        Stat r = sw[0];
+        for (int w = 1; w < 4; ++w) r = stat_merge(r, sw[w]);
+        float conf = 1.0f / r.s;
+        bool met = conf >= threshold;
+        head_conf[i] = conf;
+        head_tok[i] = r.a;
+        head_exit[i] = (met || force_exit) ? 1 : 0;
+        head_breach[i] = (force_exit && !met) ? 1 : 0;
+    }
+}
+
+int launch_exit_decide(ee_batch* b, int n_part, float th, int force, hipStream_t s) {
+    const ee_batch_layout& L = b->L;
+    hipLaunchKernelGGL(k_exit_decide, dim3(b->B), dim3(256), 0, s, b->wsp<float>(b->W.part_max),
+                       b->wsp<float>(b->W.part_sum), b->wsp<int32_t>(b->W.part_arg), n_part,
+                       b->st<int32_t>(L.n_active), b->B, th, force, b->st<float>(L.head_conf),
+                       b->st<int32_t>(L.head_tok), b->st<uint8_t>(L.head_exit), b->st<uint8_t>(L.head_breach));
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}

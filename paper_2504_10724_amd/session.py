@@ -1,0 +1,243 @@
+"""Device-memory plumbing around libee: PyTorch allocates the buffers and
+provides the stream, libee does all the work.  Nothing here computes anything
+on the decode path."""
+import ctypes as C
+
+import numpy as np
+import torch
+
+from . import capi as ee
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _to_device(a, dtype):
+    """numpy (float32, or uint16 bf16 bit patterns) or torch tensor -> device tensor in the model dtype"""
+    if isinstance(a, torch.Tensor):
+        t = a
+    else:
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint16:
+            t = torch.from_numpy(a.view(np.int16)).view(torch.bfloat16)
+        else:
+            t = torch.from_numpy(a)
+    t = t.to("cuda", non_blocking=False).contiguous()
+    assert t.dtype == dtype, (t.dtype, dtype)
+    return t
+
+
+class Model:
+    """An early-exit decoder description plus the device tensors its resident layers use."""
+
+    def __init__(self, *, n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, dtype,
+                 exit_layers, max_pos, rms_eps=1e-5, rope_theta=10000.0):
+        if not torch.cuda.is_available():
+            raise RuntimeError("libee needs a HIP device; there is no CPU path")
+        self.lib = ee.load()
+        cfg = ee.ee_model_config()
+        cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads = n_layers, d_model, n_q_heads, n_kv_heads
+        cfg.head_dim, cfg.d_ffn, cfg.vocab = head_dim, d_ffn, vocab
+        cfg.dtype = ee.EE_BF16 if dtype == "bf16" else ee.EE_F32
+        cfg.rms_eps, cfg.rope_theta, cfg.max_pos = rms_eps, rope_theta, max_pos
+        cfg.n_exits = len(exit_layers)
+        for i, l in enumerate(exit_layers):
+            cfg.exit_layers[i] = l
+        self.cfg = cfg
+        self.bf16 = cfg.dtype == ee.EE_BF16
+        self.tdtype = torch.bfloat16 if self.bf16 else torch.float32
+        self.exit_layers = list(exit_layers)
+        self.h = C.c_void_p()
+        ee.check(self.lib.ee_model_create(C.byref(cfg), C.byref(self.h)))
+        self._keep = {}
+
+    @classmethod
+    def from_shape(cls, s, max_pos):
+        return cls(n_layers=s.n_layers, d_model=s.d_model, n_q_heads=s.n_q_heads, n_kv_heads=s.n_kv_heads,
+                   head_dim=s.head_dim, d_ffn=s.d_ffn, vocab=s.vocab, dtype=s.dtype,
+                   exit_layers=s.exit_layers, max_pos=max_pos, rms_eps=s.rms_eps, rope_theta=s.rope_theta)
+
+    def close(self):
+        if self.h:
+            self.lib.ee_model_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- weights --------------------------------------------------------------
+    def _matrix(self, W):
+        """row-major [out][in] -> device tensor in the form the kernels read"""
+        t = _to_device(W, self.tdtype)
+        if not self.bf16:
+            return t
+        out = torch.empty_like(t)
+        ee.check(self.lib.ee_pack_weight(_ptr(t), t.shape[0], t.shape[1], _ptr(out), 0, 1, _stream()))
+        torch.cuda.current_stream().synchronize()
+        return out
+
+    def _gate_up(self, Wg, Wu):
+        g, u = _to_device(Wg, self.tdtype), _to_device(Wu, self.tdtype)
+        if not self.bf16:
+            return torch.cat([g, u], dim=0).contiguous()
+        out = torch.empty((2 * g.shape[0], g.shape[1]), dtype=self.tdtype, device="cuda")
+        ee.check(self.lib.ee_pack_weight(_ptr(g), g.shape[0], g.shape[1], _ptr(out), 0, 2, _stream()))
+        ee.check(self.lib.ee_pack_weight(_ptr(u), u.shape[0], u.shape[1], _ptr(out), 1, 2, _stream()))
+        torch.cuda.current_stream().synchronize()
+        return out
+
+    def set_layer(self, layer, *, g_attn, W_qkv, W_o, g_ffn, W_gate, W_up, W_down):
+        t = dict(g_attn=_to_device(g_attn, torch.float32), w_qkv=self._matrix(W_qkv), w_o=self._matrix(W_o),
+                 g_ffn=_to_device(g_ffn, torch.float32), w_gate_up=self._gate_up(W_gate, W_up),
+                 w_down=self._matrix(W_down))
+        self.set_layer_device(layer, **t)
+
+    def set_layer_device(self, layer, *, g_attn, w_qkv, w_o, g_ffn, w_gate_up, w_down):
+        """device tensors already in the kernels' format"""
+        w = ee.ee_layer_weights(_ptr(g_attn), _ptr(w_qkv), _ptr(w_o), _ptr(g_ffn), _ptr(w_gate_up), _ptr(w_down))
+        ee.check(self.lib.ee_model_set_layer(self.h, layer, C.byref(w)))
+        self._keep[("layer", layer)] = (g_attn, w_qkv, w_o, g_ffn, w_gate_up, w_down)
+
+    def set_exit(self, e, *, g, W):
+        gt, wt = _to_device(g, torch.float32), self._matrix(W)
+        self.set_exit_device(e, gt, wt)
+
+    def set_exit_device(self, e, g, w):
+        ee.check(self.lib.ee_model_set_exit(self.h, e, _ptr(g), _ptr(w)))
+        self._keep[("exit", e)] = (g, w)
+
+    def set_embed(self, emb):
+        t = _to_device(emb, self.tdtype)
+        ee.check(self.lib.ee_model_set_embed(self.h, _ptr(t)))
+        self._keep["embed"] = t
+
+    def resident_depth(self):
+        return self.lib.ee_model_resident_depth(self.h)
+
+
+class KVCache:
+    def __init__(self, model, n_layers, capacity):
+        self.model = model
+        cap = np.ascontiguousarray(capacity, dtype=np.int32)
+        self.capacity = cap
+        self.B = int(cap.size)
+        self.n_layers = n_layers
+        capp = cap.ctypes.data_as(C.POINTER(C.c_int32))
+        nbytes = model.lib.ee_kv_pool_bytes(model.h, n_layers, capp, self.B)
+        if nbytes == 0:
+            raise ee.EEError(ee.EE_ERR_CAPACITY, "invalid key/value pool description")
+        self.pool = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        self.h = C.c_void_p()
+        ee.check(model.lib.ee_kv_bind(model.h, _ptr(self.pool), nbytes, n_layers, capp, self.B, C.byref(self.h)))
+
+    def close(self):
+        if self.h:
+            self.model.lib.ee_kv_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def write_context(self, layer, row, K, V, pos0=0):
+        """K, V: [H_kv][n_pos][hd] in the model dtype (numpy or torch)"""
+        k, v = _to_device(K, self.model.tdtype), _to_device(V, self.model.tdtype)
+        ee.check(self.model.lib.ee_kv_write_context(self.model.h, self.h, layer, row, pos0, k.shape[1],
+                                                    _ptr(k), _ptr(v), _stream()))
+        torch.cuda.current_stream().synchronize()
+
+    def read_context(self, layer, row, n_pos, pos0=0):
+        c = self.model.cfg
+        k = torch.empty((c.n_kv_heads, n_pos, c.head_dim), dtype=self.model.tdtype, device="cuda")
+        v = torch.empty_like(k)
+        ee.check(self.model.lib.ee_kv_read_context(self.model.h, self.h, layer, row, pos0, n_pos, _ptr(k), _ptr(v),
+                                                   _stream()))
+        torch.cuda.current_stream().synchronize()
+        return k.float().cpu().numpy(), v.float().cpu().numpy()
+
+
+_FIELD_TYPES = dict(h=torch.float32, tok_in=torch.int32, pos=torch.int32, row_scale=torch.float32,
+                    active_idx=torch.int32, n_active=torch.int32, exited_idx=torch.int32, n_exited=torch.int32,
+                    head_conf=torch.float32, head_tok=torch.int32, head_exit=torch.uint8, head_breach=torch.uint8,
+                    out_tok=torch.int32, out_layer=torch.int32, out_conf=torch.float32, out_breach=torch.uint8,
+                    exit_counts=torch.int32, breach_count=torch.int32, status=torch.int32)
+
+
+class Batch:
+    def __init__(self, model, B):
+        self.model, self.B = model, B
+        lib = model.lib
+        sb, wb = lib.ee_batch_state_bytes(model.h, B), lib.ee_workspace_bytes(model.h, B)
+        self.state = torch.zeros(sb, dtype=torch.uint8, device="cuda")
+        self.workspace = torch.empty(wb, dtype=torch.uint8, device="cuda")
+        self.h = C.c_void_p()
+        ee.check(lib.ee_batch_bind(model.h, B, _ptr(self.state), sb, _ptr(self.workspace), wb, C.byref(self.h)))
+        self.layout = ee.ee_batch_layout()
+        ee.check(lib.ee_batch_get_layout(model.h, B, C.byref(self.layout)))
+
+    def close(self):
+        if self.h:
+            self.model.lib.ee_batch_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def field(self, name):
+        """torch view of a field of the batch state (see ee_batch_layout)"""
+        off = getattr(self.layout, name)
+        dt = _FIELD_TYPES[name]
+        count = {"h": self.B * self.model.cfg.d_model, "n_active": 1, "n_exited": 1, "breach_count": 1,
+                 "status": 1, "exit_counts": ee.EE_MAX_EXITS}.get(name, self.B)
+        nbytes = count * torch.empty(0, dtype=dt).element_size()
+        v = self.state[off:off + nbytes].view(dt)
+        return v.view(self.B, -1) if name == "h" else v
+
+    def reset(self, tok, pos, scale=None):
+        t = torch.as_tensor(np.asarray(tok, dtype=np.int32)).cuda()
+        p = torch.as_tensor(np.asarray(pos, dtype=np.int32)).cuda()
+        s = None if scale is None else torch.as_tensor(np.asarray(scale, dtype=np.float32)).cuda()
+        ee.check(self.model.lib.ee_batch_reset(self.h, _ptr(t), _ptr(p), _ptr(s), _stream()))
+        torch.cuda.current_stream().synchronize()
+
+    def set_row_scale(self, scale):
+        s = scale if isinstance(scale, torch.Tensor) else torch.as_tensor(np.asarray(scale, dtype=np.float32)).cuda()
+        ee.check(self.model.lib.ee_batch_set_row_scale(self.h, _ptr(s), _stream()))
+        self._scale_keep = s
+
+    def begin_step(self):
+        ee.check(self.model.lib.ee_batch_begin_step(self.model.h, self.h, _stream()))
+
+
+def layer_forward(model, layer, kv, batch):
+    return model.lib.ee_layer_forward(model.h, layer, kv.h, batch.h, _stream())
+
+
+def exit_head(model, exit_idx, threshold, force_exit, batch, dbg_logits=None):
+    return model.lib.ee_exit_head(model.h, exit_idx, threshold, int(force_exit), batch.h, _ptr(dbg_logits), _stream())
+
+
+def compact_active(batch, exit_idx, exit_layer):
+    return batch.model.lib.ee_compact_active(batch.h, exit_idx, exit_layer, _stream())
+
+
+def fill_skipped_kv(model, from_excl, to_incl, kv, batch):
+    return model.lib.ee_fill_skipped_kv(model.h, from_excl, to_incl, kv.h, batch.h, _stream())
+
+
+def decode_step(model, kv, batch, thresholds):
+    th = (C.c_float * len(thresholds))(*thresholds)
+    return model.lib.ee_decode_step(model.h, kv.h, batch.h, th, len(thresholds), _stream())

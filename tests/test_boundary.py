@@ -1,0 +1,89 @@
+"""The C-ABI boundary without a GPU: the library loads, exports every symbol the
+header declares, the binding covers them, and argument checks that come before
+any device work return the documented codes."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2504_10724_amd import capi as ee
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "ee.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ee_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = C.CDLL(ee.LIB_PATH)
+    names = _declared()
+    assert len(names) >= 25
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in ee.h but not exported"
+
+
+def test_binding_covers_the_header():
+    assert sorted(ee.exported_names()) == _declared()
+    for hot in ("ee_layer_forward", "ee_exit_head", "ee_compact_active", "ee_fill_skipped_kv", "ee_decode_step"):
+        assert hot in ee.exported_names()
+
+
+def _cfg(**kw):
+    c = ee.ee_model_config()
+    base = dict(n_layers=4, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, d_ffn=688, vocab=2048,
+                dtype=ee.EE_F32, rms_eps=1e-5, rope_theta=10000.0, max_pos=128, n_exits=2)
+    base.update(kw)
+    for k, v in base.items():
+        setattr(c, k, v)
+    for i, l in enumerate(kw.get("exits", (2, 4))):
+        c.exit_layers[i] = l
+    return c
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(n_kv_heads=3), ee.EE_ERR_SHAPE),                      # H_q not a multiple of H_kv
+    (dict(head_dim=63), ee.EE_ERR_SHAPE),
+    (dict(dtype=7), ee.EE_ERR_DTYPE),
+    (dict(n_exits=0), ee.EE_ERR_INVALID_ARG),
+    (dict(exits=(4, 2)), ee.EE_ERR_INVALID_ARG),                # not ascending
+    (dict(exits=(2, 9)), ee.EE_ERR_INVALID_ARG),                # beyond the model
+    (dict(dtype=ee.EE_BF16), ee.EE_ERR_SHAPE),                  # bf16 needs head_dim 128
+    (dict(dtype=ee.EE_BF16, head_dim=128, d_model=200), ee.EE_ERR_SHAPE),
+    (dict(rope_theta=0.5), ee.EE_ERR_INVALID_ARG),
+])
+def test_model_create_rejects_bad_configs_before_touching_the_device(kw, code):
+    lib = ee.load()
+    h = C.c_void_p()
+    assert lib.ee_model_create(C.byref(_cfg(**kw)), C.byref(h)) == code
+    assert lib.ee_last_error() not in (None, b"")
+    assert not h.value
+
+
+def test_null_and_shape_checks_without_device():
+    lib = ee.load()
+    assert lib.ee_model_create(None, None) == ee.EE_ERR_INVALID_ARG
+    assert lib.ee_pack_weight(None, 32, 16, None, 0, 1, None) == ee.EE_ERR_INVALID_ARG
+    dummy = C.c_void_p(256)
+    assert lib.ee_pack_weight(dummy, 33, 16, dummy, 0, 1, None) == ee.EE_ERR_SHAPE
+    assert lib.ee_pack_weight(dummy, 32, 24, dummy, 0, 1, None) == ee.EE_ERR_SHAPE
+    assert lib.ee_packed_bytes(64, 32) == 64 * 32 * 2
+    assert lib.ee_layer_forward(None, 1, None, None, None) == ee.EE_ERR_INVALID_ARG
+    assert lib.ee_decode_step(None, None, None, None, 0, None) == ee.EE_ERR_INVALID_ARG
+    assert lib.ee_compact_active(None, 0, 1, None) == ee.EE_ERR_INVALID_ARG
+    assert lib.ee_exit_head(None, 0, 0.5, 0, None, None, None) == ee.EE_ERR_INVALID_ARG
+    assert lib.ee_fill_skipped_kv(None, 0, 1, None, None, None) == ee.EE_ERR_INVALID_ARG
+    assert lib.ee_batch_state_bytes(None, 4) == 0 and lib.ee_workspace_bytes(None, 4) == 0
+
+
+def test_product_package_does_not_reach_for_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2504_10724_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f"{f} mentions the oracle"
