@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched early-exit decode step on one MI355X.
+
+Workload (default): the Llama2-70B-shaped early-exit decoder, 80 resident
+layers, exit heads after layers 20/40/60/80 with thresholds 0.9/0.85/0.8/0,
+batch 256, per-request context uniform in [512, 2048], 16 decode steps.  All
+inputs are seeded and synthetic (random-init weights of that architecture,
+random cached context) and already resident in HBM when the timed region
+starts.  One "step" is one whole decode step over the batch.
+
+Prints ONE JSON line with the decoded tokens/s, the roofline figures of the
+dominant kernel (measured with HIP events on the launch stream) and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def build_device_model(s, S, torch, max_pos, seed):
+    """random-init weights generated on the device: N(0, 0.02^2) row-major bf16, then
+    repacked by the library into the order its kernels stream"""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    model = S.Model.from_shape(s, max_pos=max_pos)
+
+    def mat(n_out, n_in):
+        return (torch.randn((n_out, n_in), generator=gen, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+
+    d, F, qd = s.d_model, s.d_ffn, s.n_q_heads * s.head_dim
+    ones = torch.ones(d, dtype=torch.float32, device="cuda")
+    t0 = time.time()
+    for l in range(1, s.resident + 1):
+        model.set_layer(l, g_attn=ones, W_qkv=mat(s.qkv_rows, d), W_o=mat(d, qd), g_ffn=ones,
+                        W_gate=mat(F, d), W_up=mat(F, d), W_down=mat(d, F))
+        if l % 20 == 0:
+            print(f"[bench] layers 1..{l} resident ({time.time() - t0:.1f} s)", file=sys.stderr, flush=True)
+    for e, l in enumerate(s.exit_layers):
+        if l <= s.resident:
+            model.set_exit(e, g=ones, W=mat(s.vocab, d))
+    model.set_embed(mat(s.vocab, d))
+    return model
+
+
+def fill_cache(kv, s, torch):
+    """cached context: i.i.d. N(0, (0.02 sqrt(d))^2) in bf16 over the whole pool"""
+    std = 0.02 * float(np.sqrt(s.d_model))
+    pool = kv.pool.view(torch.bfloat16)
+    chunk = 1 << 30
+    for i in range(0, pool.numel(), chunk):
+        pool[i:i + chunk].normal_(0.0, std)
+
+
+def cpu_baseline(s, exit_hist, n_rows=8):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: one
+    70B-shaped layer and one exit head for n_rows rows (contexts drawn like the
+    workload's), scaled to tokens/s with the exit histogram the GPU run measured."""
+    import synth
+    from oracle import ee_oracle as orc
+    one = s.with_(n_layers=1, resident=1, exit_layers=(1,), thresholds=(0.0,), batch=n_rows, steps=1)
+    W = synth.layer_weights(one, 1)
+    E = synth.exit_weights(one, 0)
+    om = orc.OracleModel(n_layers=1, d_model=s.d_model, n_q_heads=s.n_q_heads, n_kv_heads=s.n_kv_heads,
+                         head_dim=s.head_dim, d_ffn=s.d_ffn, vocab=s.vocab, dtype=s.dtype, exit_layers=(1,))
+    om.set_layer(1, W["g_attn"], W["W_qkv"], W["W_o"], W["g_ffn"], W["W_gate"], W["W_up"], W["W_down"])
+    om.set_exit(0, E["g"], E["W"])
+    ctx = synth.context_lengths(one)
+    cap = int(ctx.max()) + 1
+    om.set_rope(s.rope_theta, cap)
+    kv = orc.OracleKV(1, n_rows, s.n_kv_heads, cap, s.head_dim)
+    for b in range(n_rows):
+        K, V = synth.kv_rows(one, 1, b, int(ctx[b]))
+        kv.K[0, b, :, :ctx[b]] = synth.bf16_bits_to_f32(K)
+        kv.V[0, b, :, :ctx[b]] = synth.bf16_bits_to_f32(V)
+    h = (np.random.default_rng(0).standard_normal((n_rows, s.d_model)) * 0.02).astype(np.float32)
+    t0 = time.perf_counter()
+    orc.layer_forward(om, 1, kv, np.ones(n_rows, np.uint8), ctx.astype(np.int32), h)
+    t_layer = (time.perf_counter() - t0) / n_rows
+    t0 = time.perf_counter()
+    for b in range(n_rows):
+        orc.exit_head(om, 0, h[b], 1.0)
+    t_exit = (time.perf_counter() - t0) / n_rows
+    t0 = time.perf_counter()
+    for b in range(n_rows):
+        orc.fill_skipped_kv(om, 0, 1, kv, b, int(ctx[b]), h[b])
+    t_fill = (time.perf_counter() - t0) / n_rows
+    # expected time per token under the measured exit histogram
+    exits = s.resident_exits
+    frac = np.asarray(exit_hist, np.float64)
+    frac = frac / frac.sum()
+    t_tok = 0.0
+    for e, l in enumerate(exits):
+        t_tok += frac[e] * (l * t_layer + (e + 1) * t_exit + (s.resident - l) * t_fill)
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return dict(value=1.0 / t_tok, unit="tokens/s", cores=cores, kind="oracle",
+                sample=f"{n_rows} rows x (1 layer + 1 exit head + 1 skipped-layer KV fill) at the "
+                       f"workload's shape; per-row costs {t_layer:.3f}/{t_exit:.3f}/{t_fill:.4f} s combined "
+                       f"with the measured exit histogram over {s.resident} layers")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=16)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="llama2_70b")
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--layers", type=int, default=None, help="debug: fewer resident layers (not a valid result)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; nothing shards across GPUs (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth
+    from paper_2504_10724_amd import capi as ee
+    from paper_2504_10724_amd import session as S
+    import ctypes as C
+
+    assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    torch.cuda.set_device(0)
+    s = synth.CONFIGS[args.workload]
+    if args.batch:
+        s = s.with_(batch=args.batch)
+    valid = True
+    if args.layers:
+        keep = tuple(l for l in s.exit_layers if l <= args.layers)
+        s = s.with_(resident=args.layers, thresholds=s.thresholds[:len(keep)])
+        valid = False
+    total_steps = args.steps + args.warmup
+    ctx = synth.context_lengths(s)
+    cap = synth.capacity_for(ctx, max(total_steps, s.steps), 32)
+    model = build_device_model(s, S, torch, int(cap.max()), s.seed)
+    kv = S.KVCache(model, s.resident, cap)
+    fill_cache(kv, s, torch)
+    batch = S.Batch(model, s.batch)
+    tok0 = synth.first_tokens(s)
+    scales = [torch.as_tensor(synth.row_scale(s, t)).cuda() for t in range(total_steps)]
+    th = list(s.thresholds)
+    lib = model.lib
+    torch.cuda.synchronize()
+    free, total = torch.cuda.mem_get_info()
+    print(f"[bench] {s.name}: B={s.batch} R={s.resident} HBM used {(total - free) / 2**30:.1f} GiB of {total / 2**30:.1f}",
+          file=sys.stderr, flush=True)
+
+    def run(n_steps, first_step):
+        for t in range(n_steps):
+            batch.set_row_scale(scales[first_step + t])
+            rc = S.decode_step(model, kv, batch, th)
+            if rc != 0:
+                raise ee.EEError(rc, lib.ee_last_error().decode())
+
+    # warmup from the start state, then rewind and time exactly `steps` steps
+    batch.reset(tok0, ctx.astype(np.int32), None)
+    run(args.warmup, 0)
+    torch.cuda.synchronize()
+    batch.reset(tok0, ctx.astype(np.int32), None)
+    lib.ee_timing_reset()
+    lib.ee_timing_enable(1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps, 0)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    lib.ee_timing_enable(0)
+
+    f = batch.field
+    assert int(f("status").cpu()[0]) == 0, "device status flag set"
+    counts = f("exit_counts").cpu().numpy()[:len(s.resident_exits)].astype(np.int64)
+    tokens = s.batch * args.steps
+    assert counts.sum() == tokens, (counts, tokens)
+    kern = {}
+    for k, name in enumerate(ee.KERNEL_CLASSES):
+        n, ms = C.c_int(), C.c_float()
+        lib.ee_timing_read(k, C.byref(n), C.byref(ms))
+        kern[name] = dict(launches=n.value, total_ms=round(ms.value, 3))
+
+    # rows that ran each layer, from the exit histogram (average per step)
+    exits = s.resident_exits
+    left_before = np.concatenate([[0], np.cumsum(counts)[:-1]]) / args.steps   # rows gone before segment e
+    seg_layers = np.diff(np.concatenate([[0], exits]))
+    rows_per_launch = np.repeat(s.batch - left_before, seg_layers)              # avg active rows per layer
+    d, F = s.d_model, s.d_ffn
+    # dominant GEMM: gate/up projection with the SwiGLU epilogue
+    gu = kern["gemm_gate_up"]
+    gu_bytes = 2 * F * d * 2                                                     # weights streamed once per launch
+    gu_flops = 2.0 * rows_per_launch.mean() * d * 2 * F                          # per launch, average active rows
+    gu_t = gu["total_ms"] / max(1, gu["launches"]) * 1e-3
+    at = kern["attention"]
+    kv_bytes_token = 2 * s.n_kv_heads * s.head_dim * 2
+    mean_pos = float(ctx.mean()) + (args.steps + 1) / 2.0
+    at_bytes = rows_per_launch.mean() * mean_pos * kv_bytes_token
+    at_t = at["total_ms"] / max(1, at["launches"]) * 1e-3
+    layer_kernels = ["norm", "gemm_qkv", "rope_append", "attention", "gemm_o", "gemm_gate_up", "gemm_down"]
+    dominant = max(layer_kernels, key=lambda k: kern[k]["total_ms"])
+    if dominant == "attention":
+        roof = dict(kernel="k_bf16_attn", bound="hbm", achieved=at_bytes / at_t / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
+                    traffic=None)
+    else:
+        roof = dict(kernel="k_bf16_gemm<gate_up,swiglu>", bound="hbm", achieved=gu_bytes / gu_t / 1e9,
+                    peak=HBM_PEAK_GBS, unit="GB/s", traffic=None)
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    extra = dict(
+        gate_up_gemm=dict(avg_us=gu_t * 1e6, hbm_gbs=gu_bytes / gu_t / 1e9, hbm_frac=gu_bytes / gu_t / 1e9 / HBM_PEAK_GBS,
+                          tflops=gu_flops / gu_t / 1e12, mfma_frac=gu_flops / gu_t / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                          avg_rows=float(rows_per_launch.mean())),
+        attention=dict(avg_us=at_t * 1e6, hbm_gbs=at_bytes / at_t / 1e9, hbm_frac=at_bytes / at_t / 1e9 / HBM_PEAK_GBS),
+        exit_head_plus_compaction_us_per_step=(kern["norm"]["total_ms"] * 0 + kern["exit_gemm"]["total_ms"] +
+                                               kern["exit_decide"]["total_ms"] + kern["compact"]["total_ms"]) * 1e3 / args.steps,
+        kernels_ms=kern,
+    )
+    out = dict(metric="decoded tokens/s/GPU at Llama2-70B shape", value=tokens / dt, unit="tokens/s", n_gpus=1,
+               steps=args.steps, warmup=args.warmup, ms_per_step=dt / args.steps * 1e3, higher_is_better=True,
+               scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
+               config=dict(workload=f"{s.name}: L={s.n_layers} R={s.resident} d={s.d_model} Hq/Hkv={s.n_q_heads}/{s.n_kv_heads} "
+                                    f"F={s.d_ffn} V={s.vocab} exits={list(exits)} th={th}",
+                           batch=s.batch, ctx=[s.ctx_lo, s.ctx_hi], valid_config=valid),
+               exit_fractions={str(l): float(c) / tokens for l, c in zip(exits, counts)},
+               roofline=roof, detail=extra)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(s, counts)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

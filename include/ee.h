@@ -250,6 +250,34 @@ int ee_fill_skipped_kv(const ee_model* m, int from_layer_excl, int to_layer_incl
 int ee_decode_step(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_thresholds,
                    int n_thresholds, void* stream);
 
+/* ------------------------------------------------------------------ measurement aid */
+
+/* Kernel classes of the decode step, for ee_timing_read. */
+typedef enum {
+    EE_K_EMBED = 0,     /* step begin: embedding gather                               */
+    EE_K_NORM = 1,      /* RMSNorm -> matrix-product operand                          */
+    EE_K_GEMM_QKV = 2,
+    EE_K_ROPE_APPEND = 3,
+    EE_K_ATTENTION = 4,
+    EE_K_GEMM_O = 5,
+    EE_K_GEMM_GATE_UP = 6,  /* with the SwiGLU epilogue                               */
+    EE_K_GEMM_DOWN = 7,
+    EE_K_EXIT_GEMM = 8,     /* vocabulary product with the fused softmax statistics   */
+    EE_K_EXIT_DECIDE = 9,
+    EE_K_COMPACT = 10,
+    EE_K_FILL_KV = 11,      /* all kernels of ee_fill_skipped_kv                      */
+    EE_K_COUNT = 12
+} ee_kernel_class;
+
+/* With timing on, every launch of a kernel class is bracketed by a pair of HIP
+ * events recorded on the launch stream (this creates events: not for code under
+ * graph capture).  ee_timing_read waits for the recorded events, returns the
+ * number of launches and their summed duration in milliseconds, and keeps
+ * accumulating until ee_timing_reset. */
+int ee_timing_enable(int on);
+int ee_timing_reset(void);
+int ee_timing_read(int kernel_class, int* launches, float* total_ms);
+
 #ifdef __cplusplus
 }
 #endif

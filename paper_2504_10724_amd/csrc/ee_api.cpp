@@ -16,6 +16,52 @@ int ee_fail(int code, const std::string& msg) {
 
 static hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
+// ------------------------------------------------------------------ kernel timing
+bool g_ee_timing_on = false;
+namespace {
+struct TimingPair { int kind; hipEvent_t a, b; bool closed; };
+std::vector<TimingPair> g_pairs;
+std::vector<hipEvent_t> g_free_events;
+int   g_launches[EE_K_COUNT];
+float g_total_ms[EE_K_COUNT];
+
+hipEvent_t take_event() {
+    if (!g_free_events.empty()) { hipEvent_t e = g_free_events.back(); g_free_events.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    (void)hipEventCreate(&e);
+    return e;
+}
+
+void drain_pairs() {
+    for (TimingPair& p : g_pairs) {
+        if (p.closed && p.a && p.b && hipEventSynchronize(p.b) == hipSuccess) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) { g_total_ms[p.kind] += ms; g_launches[p.kind] += 1; }
+        }
+        if (p.a) g_free_events.push_back(p.a);
+        if (p.b) g_free_events.push_back(p.b);
+    }
+    g_pairs.clear();
+}
+}  // namespace
+
+void ee_timing_mark(int kind, hipStream_t s, bool begin) {
+    if (kind < 0 || kind >= EE_K_COUNT) return;
+    if (begin) {
+        TimingPair p{kind, take_event(), take_event(), false};
+        if (p.a) (void)hipEventRecord(p.a, s);
+        g_pairs.push_back(p);
+    } else {
+        for (size_t i = g_pairs.size(); i-- > 0;) {
+            if (g_pairs[i].kind == kind && !g_pairs[i].closed) {
+                if (g_pairs[i].b) (void)hipEventRecord(g_pairs[i].b, s);
+                g_pairs[i].closed = true;
+                break;
+            }
+        }
+    }
+}
+
 extern "C" {
 
 const char* ee_last_error(void) { return g_last_error.c_str(); }
@@ -25,6 +71,26 @@ int ee_device_count(void) {
     hipError_t e = hipGetDeviceCount(&n);
     if (e != hipSuccess) return ee_fail(EE_ERR_HIP, std::string("hipGetDeviceCount: ") + hipGetErrorString(e));
     return n;
+}
+
+int ee_timing_enable(int on) {
+    g_ee_timing_on = on != 0;
+    return EE_OK;
+}
+
+int ee_timing_reset(void) {
+    drain_pairs();
+    for (int k = 0; k < EE_K_COUNT; ++k) { g_launches[k] = 0; g_total_ms[k] = 0.f; }
+    return EE_OK;
+}
+
+int ee_timing_read(int kernel_class, int* launches, float* total_ms) {
+    if (kernel_class < 0 || kernel_class >= EE_K_COUNT || !launches || !total_ms)
+        return ee_fail(EE_ERR_INVALID_ARG, "ee_timing_read: bad argument");
+    drain_pairs();
+    *launches = g_launches[kernel_class];
+    *total_ms = g_total_ms[kernel_class];
+    return EE_OK;
 }
 
 // ------------------------------------------------------------------ weights

@@ -69,6 +69,17 @@ int  ee_fail(int code, const std::string& msg);
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// ----------------------------------------------------------------- kernel timing (opt-in)
+// When enabled, every launch of a kernel class is bracketed by a pair of HIP
+// events on the launch stream; ee_timing_read adds up the elapsed times.
+void ee_timing_mark(int kind, hipStream_t s, bool begin);
+extern bool g_ee_timing_on;
+struct TimedScope {
+    int kind; hipStream_t s;
+    TimedScope(int k, hipStream_t st) : kind(k), s(st) { if (g_ee_timing_on) ee_timing_mark(kind, s, true); }
+    ~TimedScope() { if (g_ee_timing_on) ee_timing_mark(kind, s, false); }
+};
+
 // Per-(layer,row,head) addressing of the key/value pool, passed by value to kernels.
 struct KvView {
     char*          pool;

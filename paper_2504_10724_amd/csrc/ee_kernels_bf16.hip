@@ -452,24 +452,48 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
     bf16_t* act = b->wsp<bf16_t>(b->W.act);
     KvView view = make_view(m, kv, layer);
 
-    hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, h, idx, n_ptr, B, w.g_attn, c.rms_eps, d, x);
+    {
+        TimedScope t(EE_K_NORM, s);
+        hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, h, idx, n_ptr, B, w.g_attn, c.rms_eps, d, x);
+    }
     EpiArgs e1{};
     e1.out = qkv; e1.ldo = qkv_n; e1.idx = idx;
-    gemm<1, EPI_STORE>(x, w.w_qkv, qkv_n, d, n_ptr, B, e1, s);
-    hipLaunchKernelGGL(k_bf16_rope_append, dim3(B), dim3(256), 0, s, qkv, qkv_n, c.n_q_heads, idx, n_ptr, B,
-                       b->st<int32_t>(L.pos), m->d_rope, c.max_pos, view, b->wsp<bf16_t>(b->W.q_hi),
-                       b->wsp<bf16_t>(b->W.q_lo), b->st<int32_t>(L.status));
-    hipLaunchKernelGGL(k_bf16_attn, dim3(c.n_kv_heads, B), dim3(256), 0, s, b->wsp<bf16_t>(b->W.q_hi),
-                       b->wsp<bf16_t>(b->W.q_lo), c.n_q_heads, idx, n_ptr, B, b->st<int32_t>(L.pos), view, ao,
-                       qd / 16);
+    {
+        TimedScope t(EE_K_GEMM_QKV, s);
+        gemm<1, EPI_STORE>(x, w.w_qkv, qkv_n, d, n_ptr, B, e1, s);
+    }
+    {
+        TimedScope t(EE_K_ROPE_APPEND, s);
+        hipLaunchKernelGGL(k_bf16_rope_append, dim3(B), dim3(256), 0, s, qkv, qkv_n, c.n_q_heads, idx, n_ptr, B,
+                           b->st<int32_t>(L.pos), m->d_rope, c.max_pos, view, b->wsp<bf16_t>(b->W.q_hi),
+                           b->wsp<bf16_t>(b->W.q_lo), b->st<int32_t>(L.status));
+    }
+    {
+        TimedScope t(EE_K_ATTENTION, s);
+        hipLaunchKernelGGL(k_bf16_attn, dim3(c.n_kv_heads, B), dim3(256), 0, s, b->wsp<bf16_t>(b->W.q_hi),
+                           b->wsp<bf16_t>(b->W.q_lo), c.n_q_heads, idx, n_ptr, B, b->st<int32_t>(L.pos), view, ao,
+                           qd / 16);
+    }
     EpiArgs e2{};
     e2.out = h; e2.ldo = d; e2.idx = idx;
-    gemm<1, EPI_RESID>(ao, w.w_o, d, qd, n_ptr, B, e2, s);
-    hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, h, idx, n_ptr, B, w.g_ffn, c.rms_eps, d, x);
+    {
+        TimedScope t(EE_K_GEMM_O, s);
+        gemm<1, EPI_RESID>(ao, w.w_o, d, qd, n_ptr, B, e2, s);
+    }
+    {
+        TimedScope t(EE_K_NORM, s);
+        hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, h, idx, n_ptr, B, w.g_ffn, c.rms_eps, d, x);
+    }
     EpiArgs e3{};
     e3.act = act; e3.KB_act = F / 16; e3.idx = idx;
-    gemm<2, EPI_SWIGLU>(x, w.w_gate_up, 2 * F, d, n_ptr, B, e3, s);
-    gemm<1, EPI_RESID>(act, w.w_down, d, F, n_ptr, B, e2, s);
+    {
+        TimedScope t(EE_K_GEMM_GATE_UP, s);
+        gemm<2, EPI_SWIGLU>(x, w.w_gate_up, 2 * F, d, n_ptr, B, e3, s);
+    }
+    {
+        TimedScope t(EE_K_GEMM_DOWN, s);
+        gemm<1, EPI_RESID>(act, w.w_down, d, F, n_ptr, B, e2, s);
+    }
     EE_LAUNCH_CHECK();
     return EE_OK;
 }
@@ -481,14 +505,20 @@ int bf16_exit_head(const ee_model* m, int e, float th, int force, ee_batch* b, f
     const int32_t* idx = b->st<int32_t>(L.active_idx);
     const int32_t* n_ptr = b->st<int32_t>(L.n_active);
     uint4* x = b->wsp<uint4>(b->W.x);
-    hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, b->st<float>(L.h), idx, n_ptr, B,
-                       m->exits[e].gain, c.rms_eps, d, x);
+    {
+        TimedScope t(EE_K_NORM, s);
+        hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, b->st<float>(L.h), idx, n_ptr, B,
+                           m->exits[e].gain, c.rms_eps, d, x);
+    }
     EpiArgs ep{};
     ep.idx = idx; ep.row_scale = b->st<float>(L.row_scale);
     ep.part_max = b->wsp<float>(b->W.part_max); ep.part_sum = b->wsp<float>(b->W.part_sum);
     ep.part_arg = b->wsp<int32_t>(b->W.part_arg); ep.n_part = V / 32;
     ep.dbg_logits = dbg; ep.ldo = V;
-    gemm<1, EPI_EXIT>(x, m->exits[e].w, V, d, n_ptr, B, ep, s);
+    {
+        TimedScope t(EE_K_EXIT_GEMM, s);
+        gemm<1, EPI_EXIT>(x, m->exits[e].w, V, d, n_ptr, B, ep, s);
+    }
     EE_LAUNCH_CHECK();
     return launch_exit_decide(b, V / 32, th, force, s);
 }
@@ -502,6 +532,7 @@ int bf16_fill_kv(const ee_model* m, int from_excl, int to_incl, ee_kv* kv, ee_ba
     const int32_t* n_ptr = b->st<int32_t>(L.n_exited);
     uint4* x = b->wsp<uint4>(b->W.fill_x);
     float* kvb = b->wsp<float>(b->W.fill_kv);
+    TimedScope t(EE_K_FILL_KV, s);
     for (int l = from_excl + 1; l <= to_incl; ++l) {
         const ee_layer_weights& w = m->layers[l - 1];
         hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, b->st<float>(L.h), idx, n_ptr, B, w.g_attn,

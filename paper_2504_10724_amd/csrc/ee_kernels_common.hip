@@ -54,6 +54,7 @@ k_begin_step(const int32_t* __restrict__ tok_in, const void* __restrict__ emb, i
 
 int launch_begin_step(const ee_model* m, ee_batch* b, hipStream_t s) {
     const ee_batch_layout& L = b->L;
+    TimedScope t(EE_K_EMBED, s);
     hipLaunchKernelGGL(k_begin_step, dim3(b->B), dim3(256), 0, s, b->st<int32_t>(L.tok_in), m->emb,
                        m->cfg.dtype == EE_BF16 ? 1 : 0, m->cfg.d_model, m->cfg.vocab, b->st<float>(L.h),
                        b->st<int32_t>(L.active_idx), b->st<int32_t>(L.n_active), b->st<int32_t>(L.n_exited),
@@ -185,6 +186,7 @@ k_compact(int32_t* __restrict__ active_idx, int32_t* __restrict__ n_active, int3
 
 int launch_compact(ee_batch* b, int exit_idx, int exit_layer, hipStream_t s) {
     const ee_batch_layout& L = b->L;
+    TimedScope t(EE_K_COMPACT, s);
     hipLaunchKernelGGL(k_compact, dim3(1), dim3(COMPACT_THREADS), 0, s, b->st<int32_t>(L.active_idx),
                        b->st<int32_t>(L.n_active), b->st<int32_t>(L.exited_idx), b->st<int32_t>(L.n_exited),
                        b->st<float>(L.head_conf), b->st<int32_t>(L.head_tok), b->st<uint8_t>(L.head_exit),
@@ -306,6 +308,7 @@ k_exit_decide(const float* __restrict__ part_max, const float* __restrict__ part
 
 int launch_exit_decide(ee_batch* b, int n_part, float th, int force, hipStream_t s) {
     const ee_batch_layout& L = b->L;
+    TimedScope t(EE_K_EXIT_DECIDE, s);
     hipLaunchKernelGGL(k_exit_decide, dim3(b->B), dim3(256), 0, s, b->wsp<float>(b->W.part_max),
                        b->wsp<float>(b->W.part_sum), b->wsp<int32_t>(b->W.part_arg), n_part,
                        b->st<int32_t>(L.n_active), b->B, th, force, b->st<float>(L.head_conf),
