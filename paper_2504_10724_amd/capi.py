@@ -6,7 +6,7 @@ import ctypes as C
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libee.so")
+LIB_PATH = os.environ.get("EE_LIB_PATH", os.path.join(HERE, "libee.so"))
 
 EE_MAX_EXITS = 16
 EE_OK = 0

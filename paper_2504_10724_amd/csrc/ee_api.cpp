@@ -343,6 +343,10 @@ static void lay_workspace(const ee_model* m, int B, WsLayout* W) {
         W->logits = take(0);
         W->fill_x = take(Mpad * c.d_model * 2);
         W->fill_kv = take(Mpad * kvn * 4);
+        W->gemm_part_bytes = B > 64 ? ((size_t)64 << 20) : 0;
+        W->gemm_part = take(W->gemm_part_bytes);
+        W->gemm_cnt_ints = 4096;
+        W->gemm_cnt = take(W->gemm_cnt_ints * 4);
     } else {
         size_t wide = (size_t)c.vocab > 2 * (size_t)c.d_ffn ? (size_t)c.vocab : 2 * (size_t)c.d_ffn;
         W->x = take(Mpad * c.d_model * 4);
@@ -357,6 +361,8 @@ static void lay_workspace(const ee_model* m, int B, WsLayout* W) {
         W->logits = take(Mpad * wide * 4);
         W->fill_x = take(Mpad * c.d_model * 4);
         W->fill_kv = take(Mpad * kvn * 4);
+        W->gemm_part_bytes = 0; W->gemm_part = take(0);
+        W->gemm_cnt_ints = 0;   W->gemm_cnt = take(0);
     }
     W->total = o;
 }
@@ -401,6 +407,13 @@ int ee_batch_bind(const ee_model* m, int B, void* dev_state, size_t state_bytes,
     size_t t = 0;
     lay_state(m, B, &b->L, &t);
     lay_workspace(m, B, &b->W);
+    if (b->W.gemm_cnt_ints) {   // arrival counters start at zero and reset themselves after each use
+        hipError_t e = hipMemset(b->ws + b->W.gemm_cnt, 0, b->W.gemm_cnt_ints * 4);
+        if (e != hipSuccess) {
+            delete b;
+            return ee_fail(EE_ERR_HIP, std::string("ee_batch_bind: ") + hipGetErrorString(e));
+        }
+    }
     *out = b;
     return EE_OK;
 }

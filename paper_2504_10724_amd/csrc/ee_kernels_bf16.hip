@@ -216,6 +216,222 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
     }
 }
 
+// ------------------------------------------------------------------ large-batch MFMA GEMM
+// For 65..256 rows per row group.  A workgroup of 2 x 2 waves owns a 256-row x
+// 128-column tile and one slice of K; wave (wm, wn) owns rows 128 wm .. +127 and
+// columns 64 wn .. +63 of the tile (4 x 2 MFMA tiles of 32x32, 128 accumulator
+// registers).  W tiles go from HBM straight into B-operand registers; the X
+// tiles of a 32-wide K step (16 KiB) are staged in LDS, double buffered, and
+// both are fetched several steps ahead.  When K is sliced, every slice writes
+// an fp32 partial tile and k_splitk_finish adds the slices in order.
+#define BIG_THREADS 256
+struct Quad { uint4 a, b, c, d; };
+struct Oct { uint4 v[2][4]; };
+
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+template <int EPI>
+__device__ __forceinline__ void epilogue_tile(const EpiArgs& ep, const floatx16& v0, const floatx16& v1, int row0,
+                                              int n, int nb, int lane) {
+    // v0 / v1: the 32x32 results of tile-rows nb and nb+1 for rows row0 .. row0+31
+    const int cl = lane & 31;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int row = row0 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const bool live = row < n;
+        if (EPI == EPI_STORE) {
+            if (live) {
+                ep.out[(int64_t)row * ep.ldo + 32 * nb + cl] = v0[r];
+                ep.out[(int64_t)row * ep.ldo + 32 * (nb + 1) + cl] = v1[r];
+            }
+        } else if (EPI == EPI_RESID) {
+            if (live) {
+                float* hr = ep.out + (int64_t)ep.idx[row] * ep.ldo;
+                hr[32 * nb + cl] += v0[r];
+                hr[32 * (nb + 1) + cl] += v1[r];
+            }
+        } else if (EPI == EPI_SWIGLU) {
+            if (live) {
+                float gt = v0[r], up = v1[r];
+                float a = (gt / (1.0f + expf(-gt))) * up;
+                int col = 32 * (nb >> 1) + cl;
+                ep.act[afrag_chunk(row, col & ~7, ep.KB_act) * 8 + (col & 7)] = f32_to_bf16(a);
+            }
+        } else {
+            float sc = live ? ep.row_scale[ep.idx[row]] : 0.f;
+#pragma unroll
+            for (int ns = 0; ns < 2; ++ns) {
+                int col = 32 * (nb + ns) + cl;
+                float z = (ns == 0 ? v0[r] : v1[r]) * sc;
+                if (live && ep.dbg_logits) ep.dbg_logits[(int64_t)row * ep.ldo + col] = z;
+                Stat st{z, 1.0f, col};
+#pragma unroll
+                for (int o = 16; o > 0; o >>= 1) {
+                    Stat y{__shfl_xor(st.m, o, 64), __shfl_xor(st.s, o, 64), __shfl_xor(st.a, o, 64)};
+                    st = stat_merge(st, y);
+                }
+                if (live && cl == 0) {
+                    int64_t at = (int64_t)row * ep.n_part + nb + ns;
+                    ep.part_max[at] = st.m; ep.part_sum[at] = st.s; ep.part_arg[at] = st.a;
+                }
+            }
+        }
+    }
+}
+
+template <int EPI>
+__global__ void __launch_bounds__(BIG_THREADS, 1)
+k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int n_tiles, int splits,
+                const int32_t* __restrict__ n_ptr, int B, float* __restrict__ partial, int64_t part_plane,
+                int part_ld, EpiArgs ep) {
+    __shared__ uint4 xl[3][16][64];          // 3 stages x (8 row tiles x 2 k tiles) x 1 KiB
+    const int n = min(*n_ptr, B);
+    const int rg = blockIdx.y;
+    const int row_base = rg * 256;
+    if (row_base >= n) return;
+    const int mbs = min(8, (n - row_base + 31) >> 5);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, lives in an SGPR
+    const int wm = wave >> 1, wn = wave & 1;
+    const int cnt = max(0, min(4, mbs - 4 * wm));            // live 32-row tiles of this wave
+    const int tile = blockIdx.x / splits, sp = blockIdx.x % splits;
+    const int nbw = tile * 4 + 2 * wn;                       // first of this wave's two tile-rows of W
+    const int KS4 = KB >> 3;                                 // groups of four 32-wide K steps
+    const int ks_lo = 4 * (int)(((int64_t)KS4 * sp) / splits), ks_hi = 4 * (int)(((int64_t)KS4 * (sp + 1)) / splits);
+    const int T = ks_hi - ks_lo;                             // K steps of this slice: a positive multiple of 4
+    const uint4* xg = Xp + ((int64_t)rg * 8 * KB) * 64 + lane;
+    const uint4* wg = Wp + ((int64_t)nbw * KB) * 64 + lane;
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // Software pipeline over the 32-wide K steps ("stages").  Stage s uses the register sets
+    // xr(s % 4) (X tiles on their way to LDS; this wave stages tiles 4 wave .. 4 wave + 3),
+    // br(s % 4) (W tiles, kk * 2 + ns), ar(s % 2) (A operands read back from LDS) and the LDS
+    // buffer s % 3.  During step t the wave
+    //   issues the HBM/L2 loads of X(t+4) and W(t+3),
+    //   reads the A operands of stage t+1 from LDS,
+    //   runs the 16 MFMAs of stage t,
+    //   writes X(t+2) to LDS, and meets the other waves at the barrier.
+    // T is a multiple of 4 and the loop is unrolled by 4, so every register set is named
+    // statically and the steady state has no branch.  Loads past the end re-read the last stage.
+    Quad xr0, xr1, xr2, xr3, br0, br1, br2, br3;
+    Oct ar0, ar1;
+    auto load_x = [&](int t) -> Quad {
+        const int kb0 = 2 * (ks_lo + min(t, T - 1));
+        // dead row tiles re-read a live one: no branch, nothing out of range
+        const int m0 = min(2 * wave, mbs - 1), m1 = min(2 * wave + 1, mbs - 1);
+        Quad q;
+        q.a = xg[((int64_t)m0 * KB + kb0) * 64];
+        q.b = xg[((int64_t)m0 * KB + kb0 + 1) * 64];
+        q.c = xg[((int64_t)m1 * KB + kb0) * 64];
+        q.d = xg[((int64_t)m1 * KB + kb0 + 1) * 64];
+        return q;
+    };
+    auto load_w = [&](int t) -> Quad {
+        const int kb0 = 2 * (ks_lo + min(t, T - 1));
+        Quad q;
+        q.a = wg[((int64_t)kb0) * 64];
+        q.b = wg[((int64_t)KB + kb0) * 64];
+        q.c = wg[((int64_t)kb0 + 1) * 64];
+        q.d = wg[((int64_t)KB + kb0 + 1) * 64];
+        return q;
+    };
+    auto store_x = [&](int buf, const Quad& q) {
+        xl[buf][4 * wave + 0][lane] = q.a;
+        xl[buf][4 * wave + 1][lane] = q.b;
+        xl[buf][4 * wave + 2][lane] = q.c;
+        xl[buf][4 * wave + 3][lane] = q.d;
+    };
+    auto read_a = [&](int buf) -> Oct {
+        Oct o;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o.v[kk][i] = xl[buf][(4 * wm + i) * 2 + kk][lane];
+        return o;
+    };
+    auto compute_full = [&](const Oct& a, const Quad& bw) {
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const bf16x8 b0 = as_bf16x8(kk ? bw.c : bw.a), b1 = as_bf16x8(kk ? bw.d : bw.b);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[kk][i]), b0, acc[i][0], 0, 0, 0);
+                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[kk][i]), b1, acc[i][1], 0, 0, 0);
+            }
+        }
+    };
+    auto compute_some = [&](const Oct& a, const Quad& bw) {
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const bf16x8 b0 = as_bf16x8(kk ? bw.c : bw.a), b1 = as_bf16x8(kk ? bw.d : bw.b);
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                if (i < cnt) {
+                    acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[kk][i]), b0, acc[i][0], 0, 0, 0);
+                    acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[kk][i]), b1, acc[i][1], 0, 0, 0);
+                }
+            }
+        }
+    };
+#define BIG_STEP(COMPUTE, U, XNEW, BNEW, ANEXT, ACUR, BCUR, XOUT)   \
+    XNEW = load_x(t0 + (U) + 4);                                    \
+    BNEW = load_w(t0 + (U) + 3);                                    \
+    ANEXT = read_a((t0 + (U) + 1) % 3);                             \
+    __builtin_amdgcn_sched_barrier(0);   /* keep the loads above the MFMAs they overlap with */ \
+    COMPUTE(ACUR, BCUR);                                            \
+    __builtin_amdgcn_sched_barrier(0);                              \
+    store_x((t0 + (U) + 2) % 3, XOUT);                              \
+    lds_barrier();
+#define BIG_LOOP(COMPUTE)                                           \
+    for (int t0 = 0; t0 < T; t0 += 4) {                             \
+        BIG_STEP(COMPUTE, 0, xr0, br3, ar1, ar0, br0, xr2)          \
+        BIG_STEP(COMPUTE, 1, xr1, br0, ar0, ar1, br1, xr3)          \
+        BIG_STEP(COMPUTE, 2, xr2, br1, ar1, ar0, br2, xr0)          \
+        BIG_STEP(COMPUTE, 3, xr3, br2, ar0, ar1, br3, xr1)          \
+    }
+
+    xr0 = load_x(0); br0 = load_w(0);
+    xr1 = load_x(1); br1 = load_w(1);
+    xr2 = load_x(2); br2 = load_w(2);
+    xr3 = load_x(3);
+    store_x(0, xr0);
+    store_x(1, xr1);
+    lds_barrier();
+    ar0 = read_a(0);
+    if (cnt == 4) { BIG_LOOP(compute_full) } else { BIG_LOOP(compute_some) }
+#undef BIG_LOOP
+#undef BIG_STEP
+
+    // ---- K slices: each slice writes its fp32 partial tile row-major into its own plane of the
+    // workspace ([slice][row][N]); k_splitk_finish adds the planes in slice order and applies the
+    // epilogue, so the result does not depend on timing and no atomics or fences are needed.
+    if (splits > 1) {
+        EpiArgs pe = ep;
+        pe.out = partial + (int64_t)sp * part_plane;
+        pe.ldo = part_ld;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int mb = 4 * wm + i;
+            if (mb < mbs) epilogue_tile<EPI_STORE>(pe, acc[i][0], acc[i][1], row_base + 32 * mb, n, nbw, lane);
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int mb = 4 * wm + i;
+        if (mb < mbs) epilogue_tile<EPI>(ep, acc[i][0], acc[i][1], row_base + 32 * mb, n, nbw, lane);
+    }
+}
+
 // ------------------------------------------------------------------ RoPE + cache append
 // buf[i] = [q (n_q heads, may be 0) | k (Hkv heads) | v (Hkv heads)], fp32, hd = 128.
 // Queries are rotated and written as a bf16 pair (hi, lo) with hi + lo = q to 16
@@ -437,6 +653,58 @@ static void gemm(const void* X, const void* W, int N, int K, const int32_t* n_pt
     else                  gemm_launch<8, NS, 1, 4, EPI>(X, W, K, NB, n_ptr, B, (Mpad + 255) / 256, ep, s);
 }
 
+// Adds the K-slice planes in slice order and applies the epilogue: plain store, or
+// residual update h[row id] += sum.  One thread per 4 consecutive columns.
+template <int EPI>
+__global__ void __launch_bounds__(256)
+k_splitk_finish(const float* __restrict__ partial, int64_t plane, int ld, int splits, int N,
+                const int32_t* __restrict__ n_ptr, int B, EpiArgs ep) {
+    const int n = min(*n_ptr, B);
+    const int row = blockIdx.y;
+    if (row >= n) return;
+    const int col = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (col >= N) return;
+    const float* p = partial + (int64_t)row * ld + col;
+    float4 sum = *reinterpret_cast<const float4*>(p);
+    for (int q = 1; q < splits; ++q) {
+        float4 v = *reinterpret_cast<const float4*>(p + (int64_t)q * plane);
+        sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+    }
+    if (EPI == EPI_STORE) {
+        *reinterpret_cast<float4*>(ep.out + (int64_t)row * ep.ldo + col) = sum;
+    } else {
+        float4* h = reinterpret_cast<float4*>(ep.out + (int64_t)ep.idx[row] * ep.ldo + col);
+        float4 o = *h;
+        o.x += sum.x; o.y += sum.y; o.z += sum.z; o.w += sum.w;
+        *h = o;
+    }
+}
+
+// batches above 64 rows: the 256 x 128 tile kernel, K sliced so that about one workgroup per CU runs
+template <int EPI>
+static bool gemm_big(const ee_batch* b, const void* X, const void* W, int N, int K, const int32_t* n_ptr, int B,
+                     const EpiArgs& ep, hipStream_t s) {
+    if (B <= 64 || N % 128 != 0 || K % 128 != 0) return false;
+    int n_tiles = N / 128, row_groups = (B + 255) / 256;
+    int Mpad = (B + 31) / 32 * 32;
+    int KS = K / 32;
+    int splits = 1;
+    if ((EPI == EPI_STORE || EPI == EPI_RESID) && n_tiles * row_groups < 200) {
+        splits = (256 + n_tiles * row_groups / 2) / (n_tiles * row_groups);
+        while (splits > 1 && KS / splits < 16) --splits;   // every slice keeps at least 16 K steps (> 4)
+        while (splits > 1 && (size_t)splits * Mpad * N * sizeof(float) > b->W.gemm_part_bytes) --splits;
+    }
+    dim3 grid(n_tiles * splits, row_groups);
+    hipLaunchKernelGGL((k_bf16_gemm_big<EPI>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
+                       K / 16, n_tiles, splits, n_ptr, B, b->wsp<float>(b->W.gemm_part), (int64_t)Mpad * N, N, ep);
+    if (splits > 1) {
+        constexpr int FIN = (EPI == EPI_RESID) ? EPI_RESID : EPI_STORE;
+        hipLaunchKernelGGL((k_splitk_finish<FIN>), dim3((N / 4 + 255) / 256, B), dim3(256), 0, s,
+                           b->wsp<float>(b->W.gemm_part), (int64_t)Mpad * N, N, splits, N, n_ptr, B, ep);
+    }
+    return true;
+}
+
 int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hipStream_t s) {
     const ee_model_config& c = m->cfg;
     const ee_layer_weights& w = m->layers[layer - 1];
@@ -460,7 +728,7 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
     e1.out = qkv; e1.ldo = qkv_n; e1.idx = idx;
     {
         TimedScope t(EE_K_GEMM_QKV, s);
-        gemm<1, EPI_STORE>(x, w.w_qkv, qkv_n, d, n_ptr, B, e1, s);
+        if (!gemm_big<EPI_STORE>(b, x, w.w_qkv, qkv_n, d, n_ptr, B, e1, s)) gemm<1, EPI_STORE>(x, w.w_qkv, qkv_n, d, n_ptr, B, e1, s);
     }
     {
         TimedScope t(EE_K_ROPE_APPEND, s);
@@ -478,7 +746,7 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
     e2.out = h; e2.ldo = d; e2.idx = idx;
     {
         TimedScope t(EE_K_GEMM_O, s);
-        gemm<1, EPI_RESID>(ao, w.w_o, d, qd, n_ptr, B, e2, s);
+        if (!gemm_big<EPI_RESID>(b, ao, w.w_o, d, qd, n_ptr, B, e2, s)) gemm<1, EPI_RESID>(ao, w.w_o, d, qd, n_ptr, B, e2, s);
     }
     {
         TimedScope t(EE_K_NORM, s);
@@ -488,11 +756,11 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
     e3.act = act; e3.KB_act = F / 16; e3.idx = idx;
     {
         TimedScope t(EE_K_GEMM_GATE_UP, s);
-        gemm<2, EPI_SWIGLU>(x, w.w_gate_up, 2 * F, d, n_ptr, B, e3, s);
+        if (!gemm_big<EPI_SWIGLU>(b, x, w.w_gate_up, 2 * F, d, n_ptr, B, e3, s)) gemm<2, EPI_SWIGLU>(x, w.w_gate_up, 2 * F, d, n_ptr, B, e3, s);
     }
     {
         TimedScope t(EE_K_GEMM_DOWN, s);
-        gemm<1, EPI_RESID>(act, w.w_down, d, F, n_ptr, B, e2, s);
+        if (!gemm_big<EPI_RESID>(b, act, w.w_down, d, F, n_ptr, B, e2, s)) gemm<1, EPI_RESID>(act, w.w_down, d, F, n_ptr, B, e2, s);
     }
     EE_LAUNCH_CHECK();
     return EE_OK;
@@ -517,7 +785,7 @@ int bf16_exit_head(const ee_model* m, int e, float th, int force, ee_batch* b, f
     ep.dbg_logits = dbg; ep.ldo = V;
     {
         TimedScope t(EE_K_EXIT_GEMM, s);
-        gemm<1, EPI_EXIT>(x, m->exits[e].w, V, d, n_ptr, B, ep, s);
+        if (!gemm_big<EPI_EXIT>(b, x, m->exits[e].w, V, d, n_ptr, B, ep, s)) gemm<1, EPI_EXIT>(x, m->exits[e].w, V, d, n_ptr, B, ep, s);
     }
     EE_LAUNCH_CHECK();
     return launch_exit_decide(b, V / 32, th, force, s);
