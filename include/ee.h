@@ -117,14 +117,17 @@ size_t ee_packed_bytes(int n_out, int n_in);
 /* Repack a row-major bf16 matrix src[n_out][n_in] (dev) into the tile order the
  * MFMA kernels stream: the matrix is cut into tiles of 32 output rows x 16 input
  * columns; tile (r, c) is stored as 64 x 8 values where entry (l, j) is
- * src[32 r + l % 32][16 c + 8 (l / 32) + j]; the tiles of one tile-row are
- * contiguous and tile-row r goes to slot (tile_offset + r * tile_stride) of dst.
- * (tile_offset, tile_stride) = (0, 1) packs a matrix on its own; (0, 2) and
- * (1, 2) interleave the gate and up matrices into one w_gate_up buffer.
- * n_out % 32 == 0 and n_in % 16 == 0, else EE_ERR_SHAPE.  Runs on `stream`;
- * src may be freed after the stream is synchronised. */
+ * src[32 r + l % 32][16 c + 8 (l / 32) + j].  The destination holds
+ * dst_tile_rows tile-rows; source tile (r, c) goes to tile slot
+ * c * dst_tile_rows + (tile_offset + r * tile_stride), i.e. all tiles of one
+ * 16-column slice of K are contiguous.  (tile_offset, tile_stride,
+ * dst_tile_rows) = (0, 1, n_out/32) packs a matrix on its own; (0, 2, 2F/32)
+ * and (1, 2, 2F/32) interleave the gate and up matrices into one w_gate_up
+ * buffer.  n_out % 32 == 0 and n_in % 16 == 0, else EE_ERR_SHAPE; a placement
+ * outside the destination gives EE_ERR_INVALID_ARG.  Runs on `stream`; src may
+ * be freed after the stream is synchronised. */
 int ee_pack_weight(const void* dev_src, int n_out, int n_in, void* dev_dst,
-                   int tile_offset, int tile_stride, void* stream);
+                   int tile_offset, int tile_stride, int dst_tile_rows, void* stream);
 
 /* ------------------------------------------------------------------ handles */
 

@@ -40,7 +40,7 @@ _SIGS = {
     "ee_last_error": (C.c_char_p, []),
     "ee_device_count": (_i, []),
     "ee_packed_bytes": (_sz, [_i, _i]),
-    "ee_pack_weight": (_i, [_vp, _i, _i, _vp, _i, _i, _vp]),
+    "ee_pack_weight": (_i, [_vp, _i, _i, _vp, _i, _i, _i, _vp]),
     "ee_model_create": (_i, [C.POINTER(ee_model_config), C.POINTER(_vp)]),
     "ee_model_destroy": (_i, [_vp]),
     "ee_model_set_layer": (_i, [_vp, _i, C.POINTER(ee_layer_weights)]),

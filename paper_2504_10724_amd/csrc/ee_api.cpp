@@ -100,12 +100,13 @@ size_t ee_packed_bytes(int n_out, int n_in) {
 }
 
 int ee_pack_weight(const void* dev_src, int n_out, int n_in, void* dev_dst, int tile_offset,
-                   int tile_stride, void* stream) {
+                   int tile_stride, int dst_tile_rows, void* stream) {
     if (!dev_src || !dev_dst) return ee_fail(EE_ERR_INVALID_ARG, "ee_pack_weight: null pointer");
     if (n_out <= 0 || n_in <= 0 || n_out % 32 != 0 || n_in % 16 != 0)
         return ee_fail(EE_ERR_SHAPE, "ee_pack_weight: n_out must be a multiple of 32 and n_in of 16");
-    if (tile_offset < 0 || tile_stride < 1) return ee_fail(EE_ERR_INVALID_ARG, "ee_pack_weight: bad tile placement");
-    return launch_pack_weight(dev_src, n_out, n_in, dev_dst, tile_offset, tile_stride, as_stream(stream));
+    if (tile_offset < 0 || tile_stride < 1 || tile_offset + (n_out / 32 - 1) * tile_stride >= dst_tile_rows)
+        return ee_fail(EE_ERR_INVALID_ARG, "ee_pack_weight: tile placement outside the destination");
+    return launch_pack_weight(dev_src, n_out, n_in, dev_dst, tile_offset, tile_stride, dst_tile_rows, as_stream(stream));
 }
 
 // ------------------------------------------------------------------ model

@@ -5,7 +5,11 @@
 //     order ee_pack_weight produces: a 32(out) x 16(in) tile is 1 KiB and is the
 //     B operand of one v_mfma_f32_32x32x16_bf16 as it sits in memory (lane l
 //     holds output row l%32, inputs 8*(l/32)..+7), so a wave loads it with one
-//     fully coalesced 16-byte-per-lane read and no LDS transpose.
+//     fully coalesced 16-byte-per-lane read and no LDS transpose.  Tiles are
+//     ordered K-slice-major (tile (r, c) at slot c * R + r): the workgroups of a
+//     launch walk K more or less together, so what they fetch at any moment is
+//     one contiguous window of the matrix, spread evenly over the HBM channels,
+//     instead of addresses a power of two apart.
 //   * Activations that feed a matrix product (normalised rows, attention
 //     output, SwiGLU product) are written by their producers in the same tile
 //     order (32 rows x 16 columns per tile), i.e. as ready-made A operands.
@@ -80,7 +84,7 @@ struct EpiArgs {
 
 template <int MS, int NS, int WK, int WN, int EPI>
 __global__ void __launch_bounds__(64 * WK * WN)
-k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int NB_total,
+k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int NB_total, int NBs, int nb_off,
             const int32_t* __restrict__ n_ptr, int B, EpiArgs ep) {
     constexpr int IPW = 16 / WK;   // accumulator registers each wave finishes after the reduction
     __shared__ float red[(WK > 1) ? (WK * WN * NS * 16 * 64) : 1];
@@ -93,7 +97,7 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
     const int nb0 = (blockIdx.x * WN + wn) * NS;
     const int kb_lo = (int)(((int64_t)KB * wk) / WK), kb_hi = (int)(((int64_t)KB * (wk + 1)) / WK);
     const uint4* xw = Xp + ((int64_t)blockIdx.y * MS * KB) * 64 + lane;
-    const uint4* ww = Wp + ((int64_t)nb0 * KB) * 64 + lane;
+    const uint4* ww = Wp + (int64_t)(nb_off + nb0) * 64 + lane;   // tile (r, c) sits at slot c * NBs + r
     const bool has_cols = nb0 + NS <= NB_total;   // uniform per wave
 
     floatx16 acc[MS][NS];
@@ -111,7 +115,7 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
 #pragma unroll
             for (int u = 0; u < 4; ++u)
 #pragma unroll
-                for (int ns = 0; ns < NS; ++ns) bw[u][ns] = ww[((int64_t)ns * KB + kb + u) * 64];
+                for (int ns = 0; ns < NS; ++ns) bw[u][ns] = ww[((int64_t)(kb + u) * NBs + ns) * 64];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
 #pragma unroll
@@ -133,7 +137,7 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
                     uint4 a = xw[((int64_t)ms * KB + kb) * 64];
 #pragma unroll
                     for (int ns = 0; ns < NS; ++ns) {
-                        uint4 bwv = ww[((int64_t)ns * KB + kb) * 64];
+                        uint4 bwv = ww[((int64_t)kb * NBs + ns) * 64];
                         acc[ms][ns] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(bwv),
                                                                                acc[ms][ns], 0, 0, 0);
                     }
@@ -281,11 +285,13 @@ __device__ __forceinline__ void epilogue_tile(const EpiArgs& ep, const floatx16&
     }
 }
 
-template <int EPI>
+template <int NS> struct WFrag { uint4 v[2][NS]; };   // W tiles of one stage: [K half][column tile]
+
+template <int EPI, int NS>
 __global__ void __launch_bounds__(BIG_THREADS, 1)
-k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int n_tiles, int splits,
-                const int32_t* __restrict__ n_ptr, int B, float* __restrict__ partial, int64_t part_plane,
-                int part_ld, EpiArgs ep) {
+k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int NBs, int nb_off,
+                int n_tiles, int splits, const int32_t* __restrict__ n_ptr, int B, float* __restrict__ partial,
+                int64_t part_plane, int part_ld, EpiArgs ep) {
     __shared__ uint4 xl[3][16][64];          // 3 stages x (8 row tiles x 2 k tiles) x 1 KiB
     const int n = min(*n_ptr, B);
     const int rg = blockIdx.y;
@@ -297,32 +303,33 @@ k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
     const int wm = wave >> 1, wn = wave & 1;
     const int cnt = max(0, min(4, mbs - 4 * wm));            // live 32-row tiles of this wave
     const int tile = blockIdx.x / splits, sp = blockIdx.x % splits;
-    const int nbw = tile * 4 + 2 * wn;                       // first of this wave's two tile-rows of W
+    const int nbw = (tile * 2 + wn) * NS;                    // first of this wave's NS tile-rows of W
     const int KS4 = KB >> 3;                                 // groups of four 32-wide K steps
     const int ks_lo = 4 * (int)(((int64_t)KS4 * sp) / splits), ks_hi = 4 * (int)(((int64_t)KS4 * (sp + 1)) / splits);
     const int T = ks_hi - ks_lo;                             // K steps of this slice: a positive multiple of 4
     const uint4* xg = Xp + ((int64_t)rg * 8 * KB) * 64 + lane;
-    const uint4* wg = Wp + ((int64_t)nbw * KB) * 64 + lane;
+    const uint4* wg = Wp + (int64_t)(nb_off + nbw) * 64 + lane;   // tile (r, c) sits at slot c * NBs + r
 
-    floatx16 acc[4][2];
+    floatx16 acc[4][NS];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NS; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     // Software pipeline over the 32-wide K steps ("stages").  Stage s uses the register sets
-    // xr(s % 4) (X tiles on their way to LDS; this wave stages tiles 4 wave .. 4 wave + 3),
-    // br(s % 4) (W tiles, kk * 2 + ns), ar(s % 2) (A operands read back from LDS) and the LDS
-    // buffer s % 3.  During step t the wave
-    //   issues the HBM/L2 loads of X(t+4) and W(t+3),
-    //   reads the A operands of stage t+1 from LDS,
-    //   runs the 16 MFMAs of stage t,
-    //   writes X(t+2) to LDS, and meets the other waves at the barrier.
-    // T is a multiple of 4 and the loop is unrolled by 4, so every register set is named
-    // statically and the steady state has no branch.  Loads past the end re-read the last stage.
-    Quad xr0, xr1, xr2, xr3, br0, br1, br2, br3;
+    // xr(s % 2) (X tiles on their way to LDS; this wave stages tiles 4 wave .. 4 wave + 3),
+    // br(s % 4) (W tiles), ar(s % 2) (A operands read back from LDS) and the LDS buffer s % 3.
+    // During step t the wave runs the 8 NS MFMAs of stage t and, slotted between them so that
+    // they issue in the shadow of the matrix pipe,
+    //   writes X(t+2) to LDS, reads the A operands of stage t+1 from LDS,
+    //   and issues the HBM/L2 loads of X(t+3) and W(t+3);
+    // then it meets the other waves at the barrier.  T is a multiple of 4 and the loop is
+    // unrolled by 4, so every register set is named statically and the steady state has no
+    // branch.  Loads past the end re-read the last stage.
+    Quad xr0, xr1;
+    WFrag<NS> br0, br1, br2, br3;
     Oct ar0, ar1;
     auto load_x = [&](int t) -> Quad {
         const int kb0 = 2 * (ks_lo + min(t, T - 1));
@@ -335,81 +342,71 @@ k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
         q.d = xg[((int64_t)m1 * KB + kb0 + 1) * 64];
         return q;
     };
-    auto load_w = [&](int t) -> Quad {
+    auto load_w = [&](int t) -> WFrag<NS> {
         const int kb0 = 2 * (ks_lo + min(t, T - 1));
-        Quad q;
-        q.a = wg[((int64_t)kb0) * 64];
-        q.b = wg[((int64_t)KB + kb0) * 64];
-        q.c = wg[((int64_t)kb0 + 1) * 64];
-        q.d = wg[((int64_t)KB + kb0 + 1) * 64];
-        return q;
-    };
-    auto store_x = [&](int buf, const Quad& q) {
-        xl[buf][4 * wave + 0][lane] = q.a;
-        xl[buf][4 * wave + 1][lane] = q.b;
-        xl[buf][4 * wave + 2][lane] = q.c;
-        xl[buf][4 * wave + 3][lane] = q.d;
-    };
-    auto read_a = [&](int buf) -> Oct {
-        Oct o;
+        WFrag<NS> q;
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) o.v[kk][i] = xl[buf][(4 * wm + i) * 2 + kk][lane];
-        return o;
+            for (int ns = 0; ns < NS; ++ns) q.v[kk][ns] = wg[((int64_t)(kb0 + kk) * NBs + ns) * 64];
+        return q;
     };
-    auto compute_full = [&](const Oct& a, const Quad& bw) {
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            const bf16x8 b0 = as_bf16x8(kk ? bw.c : bw.a), b1 = as_bf16x8(kk ? bw.d : bw.b);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[kk][i]), b0, acc[i][0], 0, 0, 0);
-                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[kk][i]), b1, acc[i][1], 0, 0, 0);
-            }
-        }
+    auto store_x01 = [&](int buf, const Quad& q) {
+        xl[buf][4 * wave + 0][lane] = q.a;
+        xl[buf][4 * wave + 1][lane] = q.b;
     };
-    auto compute_some = [&](const Oct& a, const Quad& bw) {
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            const bf16x8 b0 = as_bf16x8(kk ? bw.c : bw.a), b1 = as_bf16x8(kk ? bw.d : bw.b);
-#pragma unroll
-            for (int i = 0; i < 3; ++i) {
-                if (i < cnt) {
-                    acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[kk][i]), b0, acc[i][0], 0, 0, 0);
-                    acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[kk][i]), b1, acc[i][1], 0, 0, 0);
-                }
-            }
-        }
+    auto store_x23 = [&](int buf, const Quad& q) {
+        xl[buf][4 * wave + 2][lane] = q.c;
+        xl[buf][4 * wave + 3][lane] = q.d;
     };
-#define BIG_STEP(COMPUTE, U, XNEW, BNEW, ANEXT, ACUR, BCUR, XOUT)   \
-    XNEW = load_x(t0 + (U) + 4);                                    \
-    BNEW = load_w(t0 + (U) + 3);                                    \
-    ANEXT = read_a((t0 + (U) + 1) % 3);                             \
-    __builtin_amdgcn_sched_barrier(0);   /* keep the loads above the MFMAs they overlap with */ \
-    COMPUTE(ACUR, BCUR);                                            \
-    __builtin_amdgcn_sched_barrier(0);                              \
-    store_x((t0 + (U) + 2) % 3, XOUT);                              \
+    // NS MFMAs: row tile i, K half kk, all column tiles
+    auto mf = [&](const Oct& a, const WFrag<NS>& bw, int kk, int i) {
+#pragma unroll
+        for (int ns = 0; ns < NS; ++ns)
+            acc[i][ns] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[kk][i]), as_bf16x8(bw.v[kk][ns]),
+                                                                 acc[i][ns], 0, 0, 0);
+    };
+    auto mf_some = [&](const Oct& a, const WFrag<NS>& bw, int kk, int i) {
+        if (i < cnt) mf(a, bw, kk, i);
+    };
+    auto read_a2 = [&](Oct& o, int buf, int kk, int i) {   // two A tiles of the next stage
+        o.v[kk][i] = xl[buf][(4 * wm + i) * 2 + kk][lane];
+        o.v[kk][i + 1] = xl[buf][(4 * wm + i + 1) * 2 + kk][lane];
+    };
+#define SB __builtin_amdgcn_sched_barrier(0);
+#define BIG_STEP(MF, U, XNEW, BNEW, ANEXT, ACUR, BCUR, XOUT)                                  \
+    MF(ACUR, BCUR, 0, 0); SB store_x01((t0 + (U) + 2) % 3, XOUT); SB                          \
+    MF(ACUR, BCUR, 0, 1); SB store_x23((t0 + (U) + 2) % 3, XOUT); SB                          \
+    MF(ACUR, BCUR, 0, 2); SB read_a2(ANEXT, (t0 + (U) + 1) % 3, 0, 0); SB                     \
+    MF(ACUR, BCUR, 0, 3); SB read_a2(ANEXT, (t0 + (U) + 1) % 3, 0, 2); SB                     \
+    MF(ACUR, BCUR, 1, 0); SB read_a2(ANEXT, (t0 + (U) + 1) % 3, 1, 0); SB                     \
+    MF(ACUR, BCUR, 1, 1); SB read_a2(ANEXT, (t0 + (U) + 1) % 3, 1, 2); SB                     \
+    MF(ACUR, BCUR, 1, 2); SB XNEW = load_x(t0 + (U) + 3); SB                                  \
+    MF(ACUR, BCUR, 1, 3); SB BNEW = load_w(t0 + (U) + 3); SB                                  \
     lds_barrier();
-#define BIG_LOOP(COMPUTE)                                           \
-    for (int t0 = 0; t0 < T; t0 += 4) {                             \
-        BIG_STEP(COMPUTE, 0, xr0, br3, ar1, ar0, br0, xr2)          \
-        BIG_STEP(COMPUTE, 1, xr1, br0, ar0, ar1, br1, xr3)          \
-        BIG_STEP(COMPUTE, 2, xr2, br1, ar1, ar0, br2, xr0)          \
-        BIG_STEP(COMPUTE, 3, xr3, br2, ar0, ar1, br3, xr1)          \
+    // step t stores X(t+2) from xr(t % 2) and loads X(t+3) into the other set, which held X(t+1)
+    // and was written to LDS during step t-1; W(t+3) replaces W(t-1), consumed during step t-1.
+#define BIG_LOOP(MF)                                           \
+    for (int t0 = 0; t0 < T; t0 += 4) {                        \
+        BIG_STEP(MF, 0, xr1, br3, ar1, ar0, br0, xr0)          \
+        BIG_STEP(MF, 1, xr0, br0, ar0, ar1, br1, xr1)          \
+        BIG_STEP(MF, 2, xr1, br1, ar1, ar0, br2, xr0)          \
+        BIG_STEP(MF, 3, xr0, br2, ar0, ar1, br3, xr1)          \
     }
 
     xr0 = load_x(0); br0 = load_w(0);
     xr1 = load_x(1); br1 = load_w(1);
-    xr2 = load_x(2); br2 = load_w(2);
-    xr3 = load_x(3);
-    store_x(0, xr0);
-    store_x(1, xr1);
+    store_x01(0, xr0); store_x23(0, xr0);
+    store_x01(1, xr1); store_x23(1, xr1);
+    xr0 = load_x(2); br2 = load_w(2);
+    br3 = br2;
     lds_barrier();
-    ar0 = read_a(0);
-    if (cnt == 4) { BIG_LOOP(compute_full) } else { BIG_LOOP(compute_some) }
+    ar1 = Oct{};
+    read_a2(ar0, 0, 0, 0); read_a2(ar0, 0, 0, 2); read_a2(ar0, 0, 1, 0); read_a2(ar0, 0, 1, 2);
+    if (cnt == 4) { BIG_LOOP(mf) } else { BIG_LOOP(mf_some) }
 #undef BIG_LOOP
 #undef BIG_STEP
+#undef SB
 
     // ---- K slices: each slice writes its fp32 partial tile row-major into its own plane of the
     // workspace ([slice][row][N]); k_splitk_finish adds the planes in slice order and applies the
@@ -421,14 +418,22 @@ k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int mb = 4 * wm + i;
-            if (mb < mbs) epilogue_tile<EPI_STORE>(pe, acc[i][0], acc[i][1], row_base + 32 * mb, n, nbw, lane);
+            if (mb < mbs) {
+#pragma unroll
+                for (int j = 0; j < NS; j += 2)
+                    epilogue_tile<EPI_STORE>(pe, acc[i][j], acc[i][j + 1], row_base + 32 * mb, n, nbw + j, lane);
+            }
         }
         return;
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int mb = 4 * wm + i;
-        if (mb < mbs) epilogue_tile<EPI>(ep, acc[i][0], acc[i][1], row_base + 32 * mb, n, nbw, lane);
+        if (mb < mbs) {
+#pragma unroll
+            for (int j = 0; j < NS; j += 2)
+                epilogue_tile<EPI>(ep, acc[i][j], acc[i][j + 1], row_base + 32 * mb, n, nbw + j, lane);
+        }
     }
 }
 
@@ -634,23 +639,23 @@ static KvView make_view(const ee_model* m, const ee_kv* kv, int layer) {
 }
 
 template <int MS, int NS, int WK, int WN, int EPI>
-static void gemm_launch(const void* X, const void* W, int K, int NB_total, const int32_t* n_ptr, int B,
-                        int row_groups, const EpiArgs& ep, hipStream_t s) {
+static void gemm_launch(const void* X, const void* W, int K, int NB_total, int NBs, int nb_off, const int32_t* n_ptr,
+                        int B, int row_groups, const EpiArgs& ep, hipStream_t s) {
     dim3 grid((NB_total + WN * NS - 1) / (WN * NS), row_groups);
     hipLaunchKernelGGL((k_bf16_gemm<MS, NS, WK, WN, EPI>), grid, dim3(64 * WK * WN), 0, s, (const uint4*)X,
-                       (const uint4*)W, K / 16, NB_total, n_ptr, B, ep);
+                       (const uint4*)W, K / 16, NB_total, NBs, nb_off, n_ptr, B, ep);
 }
 
 // picks the tile configuration from the row capacity of the batch
 template <int NS, int EPI>
-static void gemm(const void* X, const void* W, int N, int K, const int32_t* n_ptr, int B, const EpiArgs& ep,
-                 hipStream_t s) {
+static void gemm(const void* X, const void* W, int N, int K, int NBs, int nb_off, const int32_t* n_ptr, int B,
+                 const EpiArgs& ep, hipStream_t s) {
     int NB = N / 32;
     int Mpad = (B + 31) / 32 * 32;
-    if (Mpad <= 32)       gemm_launch<1, NS, 8, 1, EPI>(X, W, K, NB, n_ptr, B, 1, ep, s);
-    else if (Mpad <= 64)  gemm_launch<2, NS, 8, 1, EPI>(X, W, K, NB, n_ptr, B, 1, ep, s);
-    else if (Mpad <= 128) gemm_launch<4, NS, 2, 2, EPI>(X, W, K, NB, n_ptr, B, 1, ep, s);
-    else                  gemm_launch<8, NS, 1, 4, EPI>(X, W, K, NB, n_ptr, B, (Mpad + 255) / 256, ep, s);
+    if (Mpad <= 32)       gemm_launch<1, NS, 8, 1, EPI>(X, W, K, NB, NBs, nb_off, n_ptr, B, 1, ep, s);
+    else if (Mpad <= 64)  gemm_launch<2, NS, 8, 1, EPI>(X, W, K, NB, NBs, nb_off, n_ptr, B, 1, ep, s);
+    else if (Mpad <= 128) gemm_launch<4, NS, 2, 2, EPI>(X, W, K, NB, NBs, nb_off, n_ptr, B, 1, ep, s);
+    else                  gemm_launch<8, NS, 1, 4, EPI>(X, W, K, NB, NBs, nb_off, n_ptr, B, (Mpad + 255) / 256, ep, s);
 }
 
 // Adds the K-slice planes in slice order and applies the epilogue: plain store, or
@@ -680,14 +685,18 @@ k_splitk_finish(const float* __restrict__ partial, int64_t plane, int ld, int sp
     }
 }
 
-// batches above 64 rows: the 256 x 128 tile kernel, K sliced so that about one workgroup per CU runs
+// batches above 64 rows: the 256-row tile kernel, 128 or 256 columns wide, K sliced so that about
+// one workgroup per CU runs
 template <int EPI>
-static bool gemm_big(const ee_batch* b, const void* X, const void* W, int N, int K, const int32_t* n_ptr, int B,
-                     const EpiArgs& ep, hipStream_t s) {
+static bool gemm_big(const ee_batch* b, const void* X, const void* W, int N, int K, int NBs, int nb_off,
+                     const int32_t* n_ptr, int B, const EpiArgs& ep, hipStream_t s) {
     if (B <= 64 || N % 128 != 0 || K % 128 != 0) return false;
-    int n_tiles = N / 128, row_groups = (B + 255) / 256;
+    int row_groups = (B + 255) / 256;
     int Mpad = (B + 31) / 32 * 32;
     int KS = K / 32;
+    // wide tiles halve the LDS traffic per MFMA; worth it when they still give every CU a workgroup
+    bool wide = (N % 256 == 0) && (N / 256) * row_groups >= 200;
+    int n_tiles = wide ? N / 256 : N / 128;
     int splits = 1;
     if ((EPI == EPI_STORE || EPI == EPI_RESID) && n_tiles * row_groups < 200) {
         splits = (256 + n_tiles * row_groups / 2) / (n_tiles * row_groups);
@@ -695,8 +704,14 @@ static bool gemm_big(const ee_batch* b, const void* X, const void* W, int N, int
         while (splits > 1 && (size_t)splits * Mpad * N * sizeof(float) > b->W.gemm_part_bytes) --splits;
     }
     dim3 grid(n_tiles * splits, row_groups);
-    hipLaunchKernelGGL((k_bf16_gemm_big<EPI>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
-                       K / 16, n_tiles, splits, n_ptr, B, b->wsp<float>(b->W.gemm_part), (int64_t)Mpad * N, N, ep);
+    if (wide)
+        hipLaunchKernelGGL((k_bf16_gemm_big<EPI, 4>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
+                           K / 16, NBs, nb_off, n_tiles, splits, n_ptr, B, b->wsp<float>(b->W.gemm_part),
+                           (int64_t)Mpad * N, N, ep);
+    else
+        hipLaunchKernelGGL((k_bf16_gemm_big<EPI, 2>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
+                           K / 16, NBs, nb_off, n_tiles, splits, n_ptr, B, b->wsp<float>(b->W.gemm_part),
+                           (int64_t)Mpad * N, N, ep);
     if (splits > 1) {
         constexpr int FIN = (EPI == EPI_RESID) ? EPI_RESID : EPI_STORE;
         hipLaunchKernelGGL((k_splitk_finish<FIN>), dim3((N / 4 + 255) / 256, B), dim3(256), 0, s,
@@ -728,7 +743,8 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
     e1.out = qkv; e1.ldo = qkv_n; e1.idx = idx;
     {
         TimedScope t(EE_K_GEMM_QKV, s);
-        if (!gemm_big<EPI_STORE>(b, x, w.w_qkv, qkv_n, d, n_ptr, B, e1, s)) gemm<1, EPI_STORE>(x, w.w_qkv, qkv_n, d, n_ptr, B, e1, s);
+        if (!gemm_big<EPI_STORE>(b, x, w.w_qkv, qkv_n, d, qkv_n / 32, 0, n_ptr, B, e1, s))
+            gemm<1, EPI_STORE>(x, w.w_qkv, qkv_n, d, qkv_n / 32, 0, n_ptr, B, e1, s);
     }
     {
         TimedScope t(EE_K_ROPE_APPEND, s);
@@ -746,7 +762,8 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
     e2.out = h; e2.ldo = d; e2.idx = idx;
     {
         TimedScope t(EE_K_GEMM_O, s);
-        if (!gemm_big<EPI_RESID>(b, ao, w.w_o, d, qd, n_ptr, B, e2, s)) gemm<1, EPI_RESID>(ao, w.w_o, d, qd, n_ptr, B, e2, s);
+        if (!gemm_big<EPI_RESID>(b, ao, w.w_o, d, qd, d / 32, 0, n_ptr, B, e2, s))
+            gemm<1, EPI_RESID>(ao, w.w_o, d, qd, d / 32, 0, n_ptr, B, e2, s);
     }
     {
         TimedScope t(EE_K_NORM, s);
@@ -756,11 +773,13 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
     e3.act = act; e3.KB_act = F / 16; e3.idx = idx;
     {
         TimedScope t(EE_K_GEMM_GATE_UP, s);
-        if (!gemm_big<EPI_SWIGLU>(b, x, w.w_gate_up, 2 * F, d, n_ptr, B, e3, s)) gemm<2, EPI_SWIGLU>(x, w.w_gate_up, 2 * F, d, n_ptr, B, e3, s);
+        if (!gemm_big<EPI_SWIGLU>(b, x, w.w_gate_up, 2 * F, d, 2 * F / 32, 0, n_ptr, B, e3, s))
+            gemm<2, EPI_SWIGLU>(x, w.w_gate_up, 2 * F, d, 2 * F / 32, 0, n_ptr, B, e3, s);
     }
     {
         TimedScope t(EE_K_GEMM_DOWN, s);
-        if (!gemm_big<EPI_RESID>(b, act, w.w_down, d, F, n_ptr, B, e2, s)) gemm<1, EPI_RESID>(act, w.w_down, d, F, n_ptr, B, e2, s);
+        if (!gemm_big<EPI_RESID>(b, act, w.w_down, d, F, d / 32, 0, n_ptr, B, e2, s))
+            gemm<1, EPI_RESID>(act, w.w_down, d, F, d / 32, 0, n_ptr, B, e2, s);
     }
     EE_LAUNCH_CHECK();
     return EE_OK;
@@ -785,7 +804,8 @@ int bf16_exit_head(const ee_model* m, int e, float th, int force, ee_batch* b, f
     ep.dbg_logits = dbg; ep.ldo = V;
     {
         TimedScope t(EE_K_EXIT_GEMM, s);
-        if (!gemm_big<EPI_EXIT>(b, x, m->exits[e].w, V, d, n_ptr, B, ep, s)) gemm<1, EPI_EXIT>(x, m->exits[e].w, V, d, n_ptr, B, ep, s);
+        if (!gemm_big<EPI_EXIT>(b, x, m->exits[e].w, V, d, V / 32, 0, n_ptr, B, ep, s))
+            gemm<1, EPI_EXIT>(x, m->exits[e].w, V, d, V / 32, 0, n_ptr, B, ep, s);
     }
     EE_LAUNCH_CHECK();
     return launch_exit_decide(b, V / 32, th, force, s);
@@ -806,10 +826,10 @@ int bf16_fill_kv(const ee_model* m, int from_excl, int to_incl, ee_kv* kv, ee_ba
         hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, b->st<float>(L.h), idx, n_ptr, B, w.g_attn,
                            c.rms_eps, d, x);
         // key and value rows are the last 2*H_kv*hd rows of W_qkv: tile-rows H_q*hd/32 onwards
-        const char* Wkv = (const char*)w.w_qkv + (size_t)(c.n_q_heads * hd / 32) * (d / 16) * 1024;
         EpiArgs ep{};
         ep.out = kvb; ep.ldo = kv_n; ep.idx = idx;
-        gemm<1, EPI_STORE>(x, Wkv, kv_n, d, n_ptr, B, ep, s);
+        gemm<1, EPI_STORE>(x, w.w_qkv, kv_n, d, (c.n_q_heads + 2 * c.n_kv_heads) * hd / 32, c.n_q_heads * hd / 32,
+                           n_ptr, B, ep, s);
         hipLaunchKernelGGL(k_bf16_rope_append, dim3(B), dim3(256), 0, s, kvb, kv_n, 0, idx, n_ptr, B,
                            b->st<int32_t>(L.pos), m->d_rope, c.max_pos, make_view(m, kv, l), (bf16_t*)nullptr,
                            (bf16_t*)nullptr, b->st<int32_t>(L.status));

@@ -200,7 +200,7 @@ int launch_compact(ee_batch* b, int exit_idx, int exit_layer, hipStream_t s) {
 // ------------------------------------------------------------------ weight repacking
 // one thread per 8-value chunk of the packed matrix
 __global__ void k_pack_weight(const bf16_t* __restrict__ src, int n_out, int n_in, bf16_t* __restrict__ dst,
-                              int tile_off, int tile_stride) {
+                              int tile_off, int tile_stride, int dst_tile_rows) {
     int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int KB = n_in >> 4;
     int64_t total = (int64_t)(n_out >> 5) * KB * 64;
@@ -213,14 +213,14 @@ __global__ void k_pack_weight(const bf16_t* __restrict__ src, int n_out, int n_i
     int col = kb * 16 + (lane >> 5) * 8;
     const uint4 v = *reinterpret_cast<const uint4*>(src + (int64_t)row * n_in + col);
     int64_t dst_tile_row = (int64_t)tile_off + (int64_t)rb * tile_stride;
-    *reinterpret_cast<uint4*>(dst + ((dst_tile_row * KB + kb) * 64 + lane) * 8) = v;
+    *reinterpret_cast<uint4*>(dst + (((int64_t)kb * dst_tile_rows + dst_tile_row) * 64 + lane) * 8) = v;
 }
 
 int launch_pack_weight(const void* src, int n_out, int n_in, void* dst, int tile_off, int tile_stride,
-                       hipStream_t s) {
+                       int dst_tile_rows, hipStream_t s) {
     int64_t total = (int64_t)(n_out / 32) * (n_in / 16) * 64;
     hipLaunchKernelGGL(k_pack_weight, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                       (const bf16_t*)src, n_out, n_in, (bf16_t*)dst, tile_off, tile_stride);
+                       (const bf16_t*)src, n_out, n_in, (bf16_t*)dst, tile_off, tile_stride, dst_tile_rows);
     EE_LAUNCH_CHECK();
     return EE_OK;
 }

@@ -80,7 +80,7 @@ class Model:
         if not self.bf16:
             return t
         out = torch.empty_like(t)
-        ee.check(self.lib.ee_pack_weight(_ptr(t), t.shape[0], t.shape[1], _ptr(out), 0, 1, _stream()))
+        ee.check(self.lib.ee_pack_weight(_ptr(t), t.shape[0], t.shape[1], _ptr(out), 0, 1, t.shape[0] // 32, _stream()))
         torch.cuda.current_stream().synchronize()
         return out
 
@@ -89,8 +89,8 @@ class Model:
         if not self.bf16:
             return torch.cat([g, u], dim=0).contiguous()
         out = torch.empty((2 * g.shape[0], g.shape[1]), dtype=self.tdtype, device="cuda")
-        ee.check(self.lib.ee_pack_weight(_ptr(g), g.shape[0], g.shape[1], _ptr(out), 0, 2, _stream()))
-        ee.check(self.lib.ee_pack_weight(_ptr(u), u.shape[0], u.shape[1], _ptr(out), 1, 2, _stream()))
+        ee.check(self.lib.ee_pack_weight(_ptr(g), g.shape[0], g.shape[1], _ptr(out), 0, 2, 2 * g.shape[0] // 32, _stream()))
+        ee.check(self.lib.ee_pack_weight(_ptr(u), u.shape[0], u.shape[1], _ptr(out), 1, 2, 2 * g.shape[0] // 32, _stream()))
         torch.cuda.current_stream().synchronize()
         return out
 
