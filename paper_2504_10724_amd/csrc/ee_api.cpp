@@ -151,7 +151,14 @@ int ee_model_create(const ee_model_config* cfg, ee_model** out) {
     hipError_t e = hipGetDevice(&m->device);
     if (e == hipSuccess)
         e = hipMalloc((void**)&m->d_rope, (size_t)cfg->max_pos * (cfg->head_dim / 2) * 2 * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void**)&m->d_wqkv_tab, sizeof(void*) * cfg->n_layers);
+    if (e == hipSuccess) e = hipMalloc((void**)&m->d_gattn_tab, sizeof(void*) * cfg->n_layers);
+    if (e == hipSuccess) e = hipMemset(m->d_wqkv_tab, 0, sizeof(void*) * cfg->n_layers);
+    if (e == hipSuccess) e = hipMemset(m->d_gattn_tab, 0, sizeof(void*) * cfg->n_layers);
     if (e != hipSuccess) {
+        if (m->d_rope) (void)hipFree(m->d_rope);
+        if (m->d_wqkv_tab) (void)hipFree(m->d_wqkv_tab);
+        if (m->d_gattn_tab) (void)hipFree(m->d_gattn_tab);
         delete m;
         return ee_fail(EE_ERR_HIP, std::string("ee_model_create: ") + hipGetErrorString(e));
     }
@@ -159,6 +166,8 @@ int ee_model_create(const ee_model_config* cfg, ee_model** out) {
     if (rc == EE_OK && hipStreamSynchronize(nullptr) != hipSuccess) rc = ee_fail(EE_ERR_HIP, "ee_model_create: rotary table kernel failed");
     if (rc != EE_OK) {
         (void)hipFree(m->d_rope);
+        (void)hipFree(m->d_wqkv_tab);
+        (void)hipFree(m->d_gattn_tab);
         delete m;
         return rc;
     }
@@ -169,6 +178,8 @@ int ee_model_create(const ee_model_config* cfg, ee_model** out) {
 int ee_model_destroy(ee_model* m) {
     if (!m) return EE_OK;
     if (m->d_rope) (void)hipFree(m->d_rope);
+    if (m->d_wqkv_tab) (void)hipFree(m->d_wqkv_tab);
+    if (m->d_gattn_tab) (void)hipFree(m->d_gattn_tab);
     delete m;
     return EE_OK;
 }
@@ -178,6 +189,10 @@ int ee_model_set_layer(ee_model* m, int layer, const ee_layer_weights* w) {
     if (layer < 1 || layer > m->cfg.n_layers) return ee_fail(EE_ERR_INVALID_ARG, "ee_model_set_layer: layer out of range");
     if (!w->g_attn || !w->w_qkv || !w->w_o || !w->g_ffn || !w->w_gate_up || !w->w_down)
         return ee_fail(EE_ERR_INVALID_ARG, "ee_model_set_layer: null weight pointer");
+    // the per-layer device tables the multi-layer launches index
+    hipError_t e = hipMemcpy(m->d_wqkv_tab + (layer - 1), &w->w_qkv, sizeof(void*), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(m->d_gattn_tab + (layer - 1), &w->g_attn, sizeof(void*), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return ee_fail(EE_ERR_HIP, std::string("ee_model_set_layer: ") + hipGetErrorString(e));
     m->layers[layer - 1] = *w;
     m->resident[layer - 1] = 1;
     return EE_OK;
@@ -342,8 +357,9 @@ static void lay_workspace(const ee_model* m, int B, WsLayout* W) {
         W->part_sum = take(Mpad * n_part * 4);
         W->part_arg = take(Mpad * n_part * 4);
         W->logits = take(0);
-        W->fill_x = take(Mpad * c.d_model * 2);
-        W->fill_kv = take(Mpad * kvn * 4);
+        size_t fill_layers = c.n_layers > 1 ? (size_t)c.n_layers - 1 : 1;   // all skipped layers in one launch
+        W->fill_x = take(fill_layers * Mpad * c.d_model * 2);
+        W->fill_kv = take(fill_layers * Mpad * kvn * 4);
         W->gemm_part_bytes = B > 64 ? ((size_t)64 << 20) : 0;
         W->gemm_part = take(W->gemm_part_bytes);
         W->gemm_cnt_ints = 4096;

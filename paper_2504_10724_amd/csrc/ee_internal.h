@@ -24,6 +24,8 @@ struct ee_model {
     ExitWeights exits[EE_MAX_EXITS];
     const void* emb = nullptr;
     float* d_rope = nullptr;                // [max_pos][hd/2][2] (cos, sin), device
+    const void**  d_wqkv_tab = nullptr;     // device [n_layers]: w_qkv of each layer (null if not resident)
+    const float** d_gattn_tab = nullptr;    // device [n_layers]: g_attn of each layer
     int device = 0;
 };
 

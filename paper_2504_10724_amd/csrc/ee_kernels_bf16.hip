@@ -25,6 +25,16 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+// Several layers in one launch (blockIdx.z = layer - first layer): used to produce the keys and
+// values of all skipped layers at once.  Null tables / zero strides mean a single-layer launch.
+struct ZBatch {
+    const void* const*  w_tab;     // per layer: packed W_qkv           (device table, index layer - 1)
+    const float* const* g_tab;     // per layer: attention-norm gain
+    int     z0;                    // table index of blockIdx.z == 0
+    int64_t x_stride;              // uint4 units between the layers' activation matrices
+    int64_t out_stride;            // floats between the layers' output matrices
+};
+
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
     return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
 }
@@ -33,11 +43,13 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
 // one block per list entry i; out is the [Mpad][d] activation matrix in tile order
 __global__ void __launch_bounds__(256)
 k_bf16_rmsnorm(const float* __restrict__ h, const int32_t* __restrict__ idx, const int32_t* __restrict__ n_ptr,
-               int B, const float* __restrict__ gain, float eps, int d, uint4* __restrict__ out) {
+               int B, const float* __restrict__ gain, float eps, int d, uint4* __restrict__ out, ZBatch zb) {
     __shared__ float red[4];
     int i = blockIdx.x;
     int n = min(*n_ptr, B);
     if (i >= n) return;
+    if (zb.g_tab) gain = zb.g_tab[zb.z0 + blockIdx.z];
+    out += (int64_t)blockIdx.z * zb.x_stride;
     const float4* hr = reinterpret_cast<const float4*>(h + (int64_t)idx[i] * d);
     const float4* g4 = reinterpret_cast<const float4*>(gain);
     int n8 = d >> 3;
@@ -85,12 +97,15 @@ struct EpiArgs {
 template <int MS, int NS, int WK, int WN, int EPI>
 __global__ void __launch_bounds__(64 * WK * WN)
 k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int NB_total, int NBs, int nb_off,
-            const int32_t* __restrict__ n_ptr, int B, EpiArgs ep) {
+            const int32_t* __restrict__ n_ptr, int B, EpiArgs ep, ZBatch zb) {
     constexpr int IPW = 16 / WK;   // accumulator registers each wave finishes after the reduction
     __shared__ float red[(WK > 1) ? (WK * WN * NS * 16 * 64) : 1];
     const int n = min(*n_ptr, B);
     const int row_base = blockIdx.y * (32 * MS);
     if (row_base >= n) return;
+    if (zb.w_tab) Wp = reinterpret_cast<const uint4*>(zb.w_tab[zb.z0 + blockIdx.z]);
+    Xp += (int64_t)blockIdx.z * zb.x_stride;
+    ep.out += (int64_t)blockIdx.z * zb.out_stride;
     const int mbs = min(MS, (n - row_base + 31) >> 5);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wk = wave % WK, wn = wave / WK;
@@ -291,12 +306,15 @@ template <int EPI, int NS>
 __global__ void __launch_bounds__(BIG_THREADS, 1)
 k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int NBs, int nb_off,
                 int n_tiles, int splits, const int32_t* __restrict__ n_ptr, int B, float* __restrict__ partial,
-                int64_t part_plane, int part_ld, EpiArgs ep) {
+                int64_t part_plane, int part_ld, EpiArgs ep, ZBatch zb) {
     __shared__ uint4 xl[3][16][64];          // 3 stages x (8 row tiles x 2 k tiles) x 1 KiB
     const int n = min(*n_ptr, B);
     const int rg = blockIdx.y;
     const int row_base = rg * 256;
     if (row_base >= n) return;
+    if (zb.w_tab) Wp = reinterpret_cast<const uint4*>(zb.w_tab[zb.z0 + blockIdx.z]);
+    Xp += (int64_t)blockIdx.z * zb.x_stride;
+    ep.out += (int64_t)blockIdx.z * zb.out_stride;
     const int mbs = min(8, (n - row_base + 31) >> 5);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, lives in an SGPR
@@ -447,10 +465,12 @@ __global__ void __launch_bounds__(256)
 k_bf16_rope_append(const float* __restrict__ buf, int ld, int n_q, const int32_t* __restrict__ idx,
                    const int32_t* __restrict__ n_ptr, int B, const int32_t* __restrict__ pos,
                    const float* __restrict__ rope, int max_pos, KvView kv, bf16_t* __restrict__ q_hi,
-                   bf16_t* __restrict__ q_lo, int32_t* __restrict__ status) {
+                   bf16_t* __restrict__ q_lo, int32_t* __restrict__ status, int64_t z_stride) {
     int i = blockIdx.x;
     int n = min(*n_ptr, B);
     if (i >= n) return;
+    buf += (int64_t)blockIdx.z * z_stride;     // several layers in one launch: blockIdx.z = layer offset
+    kv.layer0 += blockIdx.z;
     int b = idx[i];
     int p = pos[b];
     const int hd = 128, half = 64;
@@ -640,22 +660,22 @@ static KvView make_view(const ee_model* m, const ee_kv* kv, int layer) {
 
 template <int MS, int NS, int WK, int WN, int EPI>
 static void gemm_launch(const void* X, const void* W, int K, int NB_total, int NBs, int nb_off, const int32_t* n_ptr,
-                        int B, int row_groups, const EpiArgs& ep, hipStream_t s) {
-    dim3 grid((NB_total + WN * NS - 1) / (WN * NS), row_groups);
+                        int B, int row_groups, const EpiArgs& ep, hipStream_t s, const ZBatch& zb, int nz) {
+    dim3 grid((NB_total + WN * NS - 1) / (WN * NS), row_groups, nz);
     hipLaunchKernelGGL((k_bf16_gemm<MS, NS, WK, WN, EPI>), grid, dim3(64 * WK * WN), 0, s, (const uint4*)X,
-                       (const uint4*)W, K / 16, NB_total, NBs, nb_off, n_ptr, B, ep);
+                       (const uint4*)W, K / 16, NB_total, NBs, nb_off, n_ptr, B, ep, zb);
 }
 
 // picks the tile configuration from the row capacity of the batch
 template <int NS, int EPI>
 static void gemm(const void* X, const void* W, int N, int K, int NBs, int nb_off, const int32_t* n_ptr, int B,
-                 const EpiArgs& ep, hipStream_t s) {
+                 const EpiArgs& ep, hipStream_t s, const ZBatch& zb = ZBatch{}, int nz = 1) {
     int NB = N / 32;
     int Mpad = (B + 31) / 32 * 32;
-    if (Mpad <= 32)       gemm_launch<1, NS, 8, 1, EPI>(X, W, K, NB, NBs, nb_off, n_ptr, B, 1, ep, s);
-    else if (Mpad <= 64)  gemm_launch<2, NS, 8, 1, EPI>(X, W, K, NB, NBs, nb_off, n_ptr, B, 1, ep, s);
-    else if (Mpad <= 128) gemm_launch<4, NS, 2, 2, EPI>(X, W, K, NB, NBs, nb_off, n_ptr, B, 1, ep, s);
-    else                  gemm_launch<8, NS, 1, 4, EPI>(X, W, K, NB, NBs, nb_off, n_ptr, B, (Mpad + 255) / 256, ep, s);
+    if (Mpad <= 32)       gemm_launch<1, NS, 8, 1, EPI>(X, W, K, NB, NBs, nb_off, n_ptr, B, 1, ep, s, zb, nz);
+    else if (Mpad <= 64)  gemm_launch<2, NS, 8, 1, EPI>(X, W, K, NB, NBs, nb_off, n_ptr, B, 1, ep, s, zb, nz);
+    else if (Mpad <= 128) gemm_launch<4, NS, 2, 2, EPI>(X, W, K, NB, NBs, nb_off, n_ptr, B, 1, ep, s, zb, nz);
+    else                  gemm_launch<8, NS, 1, 4, EPI>(X, W, K, NB, NBs, nb_off, n_ptr, B, (Mpad + 255) / 256, ep, s, zb, nz);
 }
 
 // Adds the K-slice planes in slice order and applies the epilogue: plain store, or
@@ -689,29 +709,30 @@ k_splitk_finish(const float* __restrict__ partial, int64_t plane, int ld, int sp
 // one workgroup per CU runs
 template <int EPI>
 static bool gemm_big(const ee_batch* b, const void* X, const void* W, int N, int K, int NBs, int nb_off,
-                     const int32_t* n_ptr, int B, const EpiArgs& ep, hipStream_t s) {
+                     const int32_t* n_ptr, int B, const EpiArgs& ep, hipStream_t s, const ZBatch& zb = ZBatch{},
+                     int nz = 1) {
     if (B <= 64 || N % 128 != 0 || K % 128 != 0) return false;
     int row_groups = (B + 255) / 256;
     int Mpad = (B + 31) / 32 * 32;
     int KS = K / 32;
     // wide tiles halve the LDS traffic per MFMA; worth it when they still give every CU a workgroup
-    bool wide = (N % 256 == 0) && (N / 256) * row_groups >= 200;
+    bool wide = (N % 256 == 0) && (N / 256) * row_groups * nz >= 200;
     int n_tiles = wide ? N / 256 : N / 128;
     int splits = 1;
-    if ((EPI == EPI_STORE || EPI == EPI_RESID) && n_tiles * row_groups < 200) {
+    if ((EPI == EPI_STORE || EPI == EPI_RESID) && nz == 1 && n_tiles * row_groups < 200) {
         splits = (256 + n_tiles * row_groups / 2) / (n_tiles * row_groups);
         while (splits > 1 && KS / splits < 16) --splits;   // every slice keeps at least 16 K steps (> 4)
         while (splits > 1 && (size_t)splits * Mpad * N * sizeof(float) > b->W.gemm_part_bytes) --splits;
     }
-    dim3 grid(n_tiles * splits, row_groups);
+    dim3 grid(n_tiles * splits, row_groups, nz);
     if (wide)
         hipLaunchKernelGGL((k_bf16_gemm_big<EPI, 4>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
                            K / 16, NBs, nb_off, n_tiles, splits, n_ptr, B, b->wsp<float>(b->W.gemm_part),
-                           (int64_t)Mpad * N, N, ep);
+                           (int64_t)Mpad * N, N, ep, zb);
     else
         hipLaunchKernelGGL((k_bf16_gemm_big<EPI, 2>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
                            K / 16, NBs, nb_off, n_tiles, splits, n_ptr, B, b->wsp<float>(b->W.gemm_part),
-                           (int64_t)Mpad * N, N, ep);
+                           (int64_t)Mpad * N, N, ep, zb);
     if (splits > 1) {
         constexpr int FIN = (EPI == EPI_RESID) ? EPI_RESID : EPI_STORE;
         hipLaunchKernelGGL((k_splitk_finish<FIN>), dim3((N / 4 + 255) / 256, B), dim3(256), 0, s,
@@ -737,7 +758,7 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
 
     {
         TimedScope t(EE_K_NORM, s);
-        hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, h, idx, n_ptr, B, w.g_attn, c.rms_eps, d, x);
+        hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, h, idx, n_ptr, B, w.g_attn, c.rms_eps, d, x, ZBatch{});
     }
     EpiArgs e1{};
     e1.out = qkv; e1.ldo = qkv_n; e1.idx = idx;
@@ -750,7 +771,7 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
         TimedScope t(EE_K_ROPE_APPEND, s);
         hipLaunchKernelGGL(k_bf16_rope_append, dim3(B), dim3(256), 0, s, qkv, qkv_n, c.n_q_heads, idx, n_ptr, B,
                            b->st<int32_t>(L.pos), m->d_rope, c.max_pos, view, b->wsp<bf16_t>(b->W.q_hi),
-                           b->wsp<bf16_t>(b->W.q_lo), b->st<int32_t>(L.status));
+                           b->wsp<bf16_t>(b->W.q_lo), b->st<int32_t>(L.status), (int64_t)0);
     }
     {
         TimedScope t(EE_K_ATTENTION, s);
@@ -767,7 +788,7 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
     }
     {
         TimedScope t(EE_K_NORM, s);
-        hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, h, idx, n_ptr, B, w.g_ffn, c.rms_eps, d, x);
+        hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, h, idx, n_ptr, B, w.g_ffn, c.rms_eps, d, x, ZBatch{});
     }
     EpiArgs e3{};
     e3.act = act; e3.KB_act = F / 16; e3.idx = idx;
@@ -795,7 +816,7 @@ int bf16_exit_head(const ee_model* m, int e, float th, int force, ee_batch* b, f
     {
         TimedScope t(EE_K_NORM, s);
         hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, b->st<float>(L.h), idx, n_ptr, B,
-                           m->exits[e].gain, c.rms_eps, d, x);
+                           m->exits[e].gain, c.rms_eps, d, x, ZBatch{});
     }
     EpiArgs ep{};
     ep.idx = idx; ep.row_scale = b->st<float>(L.row_scale);
@@ -816,24 +837,28 @@ int bf16_fill_kv(const ee_model* m, int from_excl, int to_incl, ee_kv* kv, ee_ba
     const ee_batch_layout& L = b->L;
     int B = b->B, d = c.d_model, hd = c.head_dim;
     int kv_n = 2 * c.n_kv_heads * hd;
+    int nl = to_incl - from_excl;                       // layers to fill: from_excl + 1 .. to_incl
     const int32_t* idx = b->st<int32_t>(L.exited_idx);
     const int32_t* n_ptr = b->st<int32_t>(L.n_exited);
-    uint4* x = b->wsp<uint4>(b->W.fill_x);
-    float* kvb = b->wsp<float>(b->W.fill_kv);
+    uint4* x = b->wsp<uint4>(b->W.fill_x);              // [layer][Mpad][d] normalised exit rows, tile order
+    float* kvb = b->wsp<float>(b->W.fill_kv);           // [layer][Mpad][2 H_kv hd]
     TimedScope t(EE_K_FILL_KV, s);
-    for (int l = from_excl + 1; l <= to_incl; ++l) {
-        const ee_layer_weights& w = m->layers[l - 1];
-        hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, b->st<float>(L.h), idx, n_ptr, B, w.g_attn,
-                           c.rms_eps, d, x);
-        // key and value rows are the last 2*H_kv*hd rows of W_qkv: tile-rows H_q*hd/32 onwards
-        EpiArgs ep{};
-        ep.out = kvb; ep.ldo = kv_n; ep.idx = idx;
-        gemm<1, EPI_STORE>(x, w.w_qkv, kv_n, d, (c.n_q_heads + 2 * c.n_kv_heads) * hd / 32, c.n_q_heads * hd / 32,
-                           n_ptr, B, ep, s);
-        hipLaunchKernelGGL(k_bf16_rope_append, dim3(B), dim3(256), 0, s, kvb, kv_n, 0, idx, n_ptr, B,
-                           b->st<int32_t>(L.pos), m->d_rope, c.max_pos, make_view(m, kv, l), (bf16_t*)nullptr,
-                           (bf16_t*)nullptr, b->st<int32_t>(L.status));
-    }
+    // all skipped layers in three launches (blockIdx.z = layer): the layers differ only in
+    // their norm gain and their W_k / W_v
+    ZBatch zb{};
+    zb.w_tab = m->d_wqkv_tab; zb.g_tab = m->d_gattn_tab; zb.z0 = from_excl;
+    zb.x_stride = (int64_t)b->Mpad * d / 8; zb.out_stride = (int64_t)b->Mpad * kv_n;
+    hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B, 1, nl), dim3(256), 0, s, b->st<float>(L.h), idx, n_ptr, B,
+                       (const float*)nullptr, c.rms_eps, d, x, zb);
+    // key and value rows are the last 2*H_kv*hd rows of W_qkv: tile-rows H_q*hd/32 onwards
+    EpiArgs ep{};
+    ep.out = kvb; ep.ldo = kv_n; ep.idx = idx;
+    int NBs = (c.n_q_heads + 2 * c.n_kv_heads) * hd / 32, nb_off = c.n_q_heads * hd / 32;
+    if (!gemm_big<EPI_STORE>(b, x, nullptr, kv_n, d, NBs, nb_off, n_ptr, B, ep, s, zb, nl))
+        gemm<1, EPI_STORE>(x, nullptr, kv_n, d, NBs, nb_off, n_ptr, B, ep, s, zb, nl);
+    hipLaunchKernelGGL(k_bf16_rope_append, dim3(B, 1, nl), dim3(256), 0, s, kvb, kv_n, 0, idx, n_ptr, B,
+                       b->st<int32_t>(L.pos), m->d_rope, c.max_pos, make_view(m, kv, from_excl + 1),
+                       (bf16_t*)nullptr, (bf16_t*)nullptr, b->st<int32_t>(L.status), zb.out_stride);
     EE_LAUNCH_CHECK();
     return EE_OK;
 }
