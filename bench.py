@@ -108,47 +108,18 @@ def cpu_baseline(s, exit_hist, n_rows=8):
                        f"with the measured exit histogram over {s.resident} layers")
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=16)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="llama2_70b")
-    ap.add_argument("--batch", type=int, default=None)
-    ap.add_argument("--layers", type=int, default=None, help="debug: fewer resident layers (not a valid result)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; nothing shards across GPUs (run with --gpus 1)", file=sys.stderr)
-        sys.exit(2)
-
-    import torch
-    import synth
-    from paper_2504_10724_amd import capi as ee
-    from paper_2504_10724_amd import session as S
-    import ctypes as C
-
-    assert torch.cuda.is_available(), "bench.py needs an MI355X"
-    torch.cuda.set_device(0)
-    s = synth.CONFIGS[args.workload]
-    if args.batch:
-        s = s.with_(batch=args.batch)
-    valid = True
-    if args.layers:
-        keep = tuple(l for l in s.exit_layers if l <= args.layers)
-        s = s.with_(resident=args.layers, thresholds=s.thresholds[:len(keep)])
-        valid = False
+def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
+    """One batch size: bind cache and batch state, warm up, rewind, time `steps` decode steps."""
+    lib = model.lib
     total_steps = args.steps + args.warmup
     ctx = synth.context_lengths(s)
     cap = synth.capacity_for(ctx, max(total_steps, s.steps), 32)
-    model = build_device_model(s, S, torch, int(cap.max()), s.seed)
     kv = S.KVCache(model, s.resident, cap)
     fill_cache(kv, s, torch)
     batch = S.Batch(model, s.batch)
     tok0 = synth.first_tokens(s)
     scales = [torch.as_tensor(synth.row_scale(s, t)).cuda() for t in range(total_steps)]
     th = list(s.thresholds)
-    lib = model.lib
     torch.cuda.synchronize()
     free, total = torch.cuda.mem_get_info()
     print(f"[bench] {s.name}: B={s.batch} R={s.resident} HBM used {(total - free) / 2**30:.1f} GiB of {total / 2**30:.1f}",
@@ -192,9 +163,9 @@ def main():
     seg_layers = np.diff(np.concatenate([[0], exits]))
     rows_per_launch = np.repeat(s.batch - left_before, seg_layers)              # avg active rows per layer
     d, F = s.d_model, s.d_ffn
-    # dominant GEMM: gate/up projection with the SwiGLU epilogue
+    # gate/up projection with the SwiGLU epilogue: weights streamed once per launch
     gu = kern["gemm_gate_up"]
-    gu_bytes = 2 * F * d * 2                                                     # weights streamed once per launch
+    gu_bytes = 2 * F * d * 2
     gu_flops = 2.0 * rows_per_launch.mean() * d * 2 * F                          # per launch, average active rows
     gu_t = gu["total_ms"] / max(1, gu["launches"]) * 1e-3
     at = kern["attention"]
@@ -208,28 +179,87 @@ def main():
         roof = dict(kernel="k_bf16_attn", bound="hbm", achieved=at_bytes / at_t / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
                     traffic=None)
     else:
-        roof = dict(kernel="k_bf16_gemm<gate_up,swiglu>", bound="hbm", achieved=gu_bytes / gu_t / 1e9,
+        roof = dict(kernel="k_bf16_gemm (gate/up + SwiGLU)", bound="hbm", achieved=gu_bytes / gu_t / 1e9,
                     peak=HBM_PEAK_GBS, unit="GB/s", traffic=None)
     roof["frac"] = roof["achieved"] / roof["peak"]
-    extra = dict(
+    weights_per_layer = s.layer_params() * 2
+    res = dict(
+        batch=s.batch, tokens_per_s=tokens / dt, ms_per_step=dt / args.steps * 1e3,
+        exit_fractions={str(l): float(c) / tokens for l, c in zip(exits, counts)},
+        avg_layers_per_token=float((np.asarray(exits) * counts).sum() / tokens),
+        avg_active_rows=float(rows_per_launch.mean()),
         gate_up_gemm=dict(avg_us=gu_t * 1e6, hbm_gbs=gu_bytes / gu_t / 1e9, hbm_frac=gu_bytes / gu_t / 1e9 / HBM_PEAK_GBS,
-                          tflops=gu_flops / gu_t / 1e12, mfma_frac=gu_flops / gu_t / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                          avg_rows=float(rows_per_launch.mean())),
+                          tflops=gu_flops / gu_t / 1e12, mfma_frac=gu_flops / gu_t / 1e12 / MFMA_BF16_PEAK_TFLOPS),
         attention=dict(avg_us=at_t * 1e6, hbm_gbs=at_bytes / at_t / 1e9, hbm_frac=at_bytes / at_t / 1e9 / HBM_PEAK_GBS),
-        exit_head_plus_compaction_us_per_step=(kern["norm"]["total_ms"] * 0 + kern["exit_gemm"]["total_ms"] +
-                                               kern["exit_decide"]["total_ms"] + kern["compact"]["total_ms"]) * 1e3 / args.steps,
-        kernels_ms=kern,
-    )
-    out = dict(metric="decoded tokens/s/GPU at Llama2-70B shape", value=tokens / dt, unit="tokens/s", n_gpus=1,
-               steps=args.steps, warmup=args.warmup, ms_per_step=dt / args.steps * 1e3, higher_is_better=True,
+        # all weights of a layer streamed once per launch over the four GEMMs of the layer
+        layer_gemms=dict(avg_us=sum(kern[k]["total_ms"] for k in ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down")) /
+                         max(1, gu["launches"]) * 1e3,
+                         hbm_gbs=weights_per_layer / (sum(kern[k]["total_ms"] for k in ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down")) /
+                                                      max(1, gu["launches"]) * 1e-3) / 1e9),
+        exit_head_plus_compaction_us_per_step=(kern["exit_gemm"]["total_ms"] + kern["exit_decide"]["total_ms"] +
+                                               kern["compact"]["total_ms"]) * 1e3 / args.steps,
+        kernels_ms=kern, roofline=roof, counts=counts.tolist())
+    res["layer_gemms"]["hbm_frac"] = res["layer_gemms"]["hbm_gbs"] / HBM_PEAK_GBS
+    del batch, kv
+    torch.cuda.empty_cache()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=16)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="llama2_70b")
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--layers", type=int, default=None, help="debug: fewer resident layers (not a valid result)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the smaller batch sizes of the sweep")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; nothing shards across GPUs (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth
+    from paper_2504_10724_amd import capi as ee
+    from paper_2504_10724_amd import session as S
+    import ctypes as C
+
+    assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    torch.cuda.set_device(0)
+    s = synth.CONFIGS[args.workload]
+    if args.batch:
+        s = s.with_(batch=args.batch)
+    valid = True
+    if args.layers:
+        keep = tuple(l for l in s.exit_layers if l <= args.layers)
+        s = s.with_(resident=args.layers, thresholds=s.thresholds[:len(keep)])
+        valid = False
+    total_steps = args.steps + args.warmup
+    max_cap = int(synth.capacity_for(np.array([s.ctx_hi]), max(total_steps, s.steps), 32)[0])
+    model = build_device_model(s, S, torch, max_cap, s.seed)
+    head = run_workload(s, model, args, torch, S, ee, synth, C)
+    sweep = {}
+    if not args.no_sweep and not args.batch:
+        for b in (64, 16, 1):
+            r = run_workload(s.with_(batch=b), model, args, torch, S, ee, synth, C)
+            sweep[str(b)] = {k: r[k] for k in ("tokens_per_s", "ms_per_step", "exit_fractions", "avg_layers_per_token",
+                                               "gate_up_gemm", "attention", "layer_gemms",
+                                               "exit_head_plus_compaction_us_per_step")}
+    exits = s.resident_exits
+    out = dict(metric="decoded tokens/s/GPU at Llama2-70B shape", value=head["tokens_per_s"], unit="tokens/s", n_gpus=1,
+               steps=args.steps, warmup=args.warmup, ms_per_step=head["ms_per_step"], higher_is_better=True,
                scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
                config=dict(workload=f"{s.name}: L={s.n_layers} R={s.resident} d={s.d_model} Hq/Hkv={s.n_q_heads}/{s.n_kv_heads} "
-                                    f"F={s.d_ffn} V={s.vocab} exits={list(exits)} th={th}",
+                                    f"F={s.d_ffn} V={s.vocab} exits={list(exits)} th={list(s.thresholds)}",
                            batch=s.batch, ctx=[s.ctx_lo, s.ctx_hi], valid_config=valid),
-               exit_fractions={str(l): float(c) / tokens for l, c in zip(exits, counts)},
-               roofline=roof, detail=extra)
+               exit_fractions=head["exit_fractions"], roofline=head["roofline"],
+               detail={k: head[k] for k in ("avg_layers_per_token", "avg_active_rows", "gate_up_gemm", "attention",
+                                            "layer_gemms", "exit_head_plus_compaction_us_per_step", "kernels_ms")},
+               batch_sweep=sweep)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(s, counts)
+        out["cpu_baseline"] = cpu_baseline(s, head["counts"])
     print(json.dumps(out))
 
 

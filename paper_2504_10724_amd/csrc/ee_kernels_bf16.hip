@@ -220,15 +220,20 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
                 int col = 32 * nb0 + cl;
                 float z = live ? v[0][ii] * ep.row_scale[ep.idx[row]] : 0.f;
                 if (live && ep.dbg_logits) ep.dbg_logits[(int64_t)row * ep.ldo + col] = z;
-                Stat st{z, 1.0f, col};
+                float mx = z;
+                int arg = col;
 #pragma unroll
                 for (int o = 16; o > 0; o >>= 1) {
-                    Stat y{__shfl_xor(st.m, o, 64), __shfl_xor(st.s, o, 64), __shfl_xor(st.a, o, 64)};
-                    st = stat_merge(st, y);
+                    float m2 = __shfl_xor(mx, o, 64);
+                    int a2 = __shfl_xor(arg, o, 64);
+                    if (m2 > mx || (m2 == mx && a2 < arg)) { mx = m2; arg = a2; }
                 }
+                float se = expf(z - mx);
+#pragma unroll
+                for (int o = 16; o > 0; o >>= 1) se += __shfl_xor(se, o, 64);
                 if (live && cl == 0) {
                     int64_t at = (int64_t)row * ep.n_part + nb0;
-                    ep.part_max[at] = st.m; ep.part_sum[at] = st.s; ep.part_arg[at] = st.a;
+                    ep.part_max[at] = mx; ep.part_sum[at] = se; ep.part_arg[at] = arg;
                 }
             }
         }
@@ -245,7 +250,7 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
 // an fp32 partial tile and k_splitk_finish adds the slices in order.
 #define BIG_THREADS 256
 struct Quad { uint4 a, b, c, d; };
-struct Oct { uint4 v[2][4]; };
+struct Half { uint4 v[4]; };   // A operands of one K half: 4 row tiles
 
 __device__ __forceinline__ void lds_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -285,15 +290,22 @@ __device__ __forceinline__ void epilogue_tile(const EpiArgs& ep, const floatx16&
                 int col = 32 * (nb + ns) + cl;
                 float z = (ns == 0 ? v0[r] : v1[r]) * sc;
                 if (live && ep.dbg_logits) ep.dbg_logits[(int64_t)row * ep.ldo + col] = z;
-                Stat st{z, 1.0f, col};
+                // the 32 lanes of a half-wave hold the 32 columns of this row: maximum and its
+                // lowest column first, then one exponential per logit
+                float mx = z;
+                int arg = col;
 #pragma unroll
                 for (int o = 16; o > 0; o >>= 1) {
-                    Stat y{__shfl_xor(st.m, o, 64), __shfl_xor(st.s, o, 64), __shfl_xor(st.a, o, 64)};
-                    st = stat_merge(st, y);
+                    float m2 = __shfl_xor(mx, o, 64);
+                    int a2 = __shfl_xor(arg, o, 64);
+                    if (m2 > mx || (m2 == mx && a2 < arg)) { mx = m2; arg = a2; }
                 }
+                float se = expf(z - mx);
+#pragma unroll
+                for (int o = 16; o > 0; o >>= 1) se += __shfl_xor(se, o, 64);
                 if (live && cl == 0) {
                     int64_t at = (int64_t)row * ep.n_part + nb + ns;
-                    ep.part_max[at] = st.m; ep.part_sum[at] = st.s; ep.part_arg[at] = st.a;
+                    ep.part_max[at] = mx; ep.part_sum[at] = se; ep.part_arg[at] = arg;
                 }
             }
         }
@@ -338,17 +350,19 @@ k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
 
     // Software pipeline over the 32-wide K steps ("stages").  Stage s uses the register sets
     // xr(s % 2) (X tiles on their way to LDS; this wave stages tiles 4 wave .. 4 wave + 3),
-    // br(s % 4) (W tiles), ar(s % 2) (A operands read back from LDS) and the LDS buffer s % 3.
+    // br(s % 4) (W tiles), the LDS buffer s % 3, and the A-operand registers a0 (first K half)
+    // and a1 (second K half), which are refilled from LDS half a step ahead of their use.
     // During step t the wave runs the 8 NS MFMAs of stage t and, slotted between them so that
     // they issue in the shadow of the matrix pipe,
-    //   writes X(t+2) to LDS, reads the A operands of stage t+1 from LDS,
-    //   and issues the HBM/L2 loads of X(t+3) and W(t+3);
+    //   writes X(t+2) to LDS,
+    //   reads a1 <- A(t, second half) and then a0 <- A(t+1, first half) from LDS,
+    //   issues the HBM/L2 loads of X(t+3) and W(t+3);
     // then it meets the other waves at the barrier.  T is a multiple of 4 and the loop is
     // unrolled by 4, so every register set is named statically and the steady state has no
     // branch.  Loads past the end re-read the last stage.
     Quad xr0, xr1;
     WFrag<NS> br0, br1, br2, br3;
-    Oct ar0, ar1;
+    Half a0, a1;
     auto load_x = [&](int t) -> Quad {
         const int kb0 = 2 * (ks_lo + min(t, T - 1));
         // dead row tiles re-read a live one: no branch, nothing out of range
@@ -378,38 +392,38 @@ k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
         xl[buf][4 * wave + 3][lane] = q.d;
     };
     // NS MFMAs: row tile i, K half kk, all column tiles
-    auto mf = [&](const Oct& a, const WFrag<NS>& bw, int kk, int i) {
+    auto mf = [&](const Half& a, const WFrag<NS>& bw, int kk, int i) {
 #pragma unroll
         for (int ns = 0; ns < NS; ++ns)
-            acc[i][ns] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[kk][i]), as_bf16x8(bw.v[kk][ns]),
-                                                                 acc[i][ns], 0, 0, 0);
+            acc[i][ns] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[i]), as_bf16x8(bw.v[kk][ns]), acc[i][ns],
+                                                                 0, 0, 0);
     };
-    auto mf_some = [&](const Oct& a, const WFrag<NS>& bw, int kk, int i) {
+    auto mf_some = [&](const Half& a, const WFrag<NS>& bw, int kk, int i) {
         if (i < cnt) mf(a, bw, kk, i);
     };
-    auto read_a2 = [&](Oct& o, int buf, int kk, int i) {   // two A tiles of the next stage
-        o.v[kk][i] = xl[buf][(4 * wm + i) * 2 + kk][lane];
-        o.v[kk][i + 1] = xl[buf][(4 * wm + i + 1) * 2 + kk][lane];
+    auto read_a2 = [&](Half& o, int buf, int kk, int i) {   // two A tiles
+        o.v[i] = xl[buf][(4 * wm + i) * 2 + kk][lane];
+        o.v[i + 1] = xl[buf][(4 * wm + i + 1) * 2 + kk][lane];
     };
 #define SB __builtin_amdgcn_sched_barrier(0);
-#define BIG_STEP(MF, U, XNEW, BNEW, ANEXT, ACUR, BCUR, XOUT)                                  \
-    MF(ACUR, BCUR, 0, 0); SB store_x01((t0 + (U) + 2) % 3, XOUT); SB                          \
-    MF(ACUR, BCUR, 0, 1); SB store_x23((t0 + (U) + 2) % 3, XOUT); SB                          \
-    MF(ACUR, BCUR, 0, 2); SB read_a2(ANEXT, (t0 + (U) + 1) % 3, 0, 0); SB                     \
-    MF(ACUR, BCUR, 0, 3); SB read_a2(ANEXT, (t0 + (U) + 1) % 3, 0, 2); SB                     \
-    MF(ACUR, BCUR, 1, 0); SB read_a2(ANEXT, (t0 + (U) + 1) % 3, 1, 0); SB                     \
-    MF(ACUR, BCUR, 1, 1); SB read_a2(ANEXT, (t0 + (U) + 1) % 3, 1, 2); SB                     \
-    MF(ACUR, BCUR, 1, 2); SB XNEW = load_x(t0 + (U) + 3); SB                                  \
-    MF(ACUR, BCUR, 1, 3); SB BNEW = load_w(t0 + (U) + 3); SB                                  \
+#define BIG_STEP(MF, U, XNEW, BNEW, BCUR, XOUT)                                               \
+    MF(a0, BCUR, 0, 0); SB store_x01((t0 + (U) + 2) % 3, XOUT); SB                            \
+    MF(a0, BCUR, 0, 1); SB store_x23((t0 + (U) + 2) % 3, XOUT); SB                            \
+    MF(a0, BCUR, 0, 2); SB read_a2(a1, (t0 + (U)) % 3, 1, 0); SB                              \
+    MF(a0, BCUR, 0, 3); SB read_a2(a1, (t0 + (U)) % 3, 1, 2); SB                              \
+    MF(a1, BCUR, 1, 0); SB read_a2(a0, (t0 + (U) + 1) % 3, 0, 0); SB                          \
+    MF(a1, BCUR, 1, 1); SB read_a2(a0, (t0 + (U) + 1) % 3, 0, 2); SB                          \
+    MF(a1, BCUR, 1, 2); SB XNEW = load_x(t0 + (U) + 3); SB                                    \
+    MF(a1, BCUR, 1, 3); SB BNEW = load_w(t0 + (U) + 3); SB                                    \
     lds_barrier();
     // step t stores X(t+2) from xr(t % 2) and loads X(t+3) into the other set, which held X(t+1)
     // and was written to LDS during step t-1; W(t+3) replaces W(t-1), consumed during step t-1.
-#define BIG_LOOP(MF)                                           \
-    for (int t0 = 0; t0 < T; t0 += 4) {                        \
-        BIG_STEP(MF, 0, xr1, br3, ar1, ar0, br0, xr0)          \
-        BIG_STEP(MF, 1, xr0, br0, ar0, ar1, br1, xr1)          \
-        BIG_STEP(MF, 2, xr1, br1, ar1, ar0, br2, xr0)          \
-        BIG_STEP(MF, 3, xr0, br2, ar0, ar1, br3, xr1)          \
+#define BIG_LOOP(MF)                                 \
+    for (int t0 = 0; t0 < T; t0 += 4) {              \
+        BIG_STEP(MF, 0, xr1, br3, br0, xr0)          \
+        BIG_STEP(MF, 1, xr0, br0, br1, xr1)          \
+        BIG_STEP(MF, 2, xr1, br1, br2, xr0)          \
+        BIG_STEP(MF, 3, xr0, br2, br3, xr1)          \
     }
 
     xr0 = load_x(0); br0 = load_w(0);
@@ -419,8 +433,8 @@ k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
     xr0 = load_x(2); br2 = load_w(2);
     br3 = br2;
     lds_barrier();
-    ar1 = Oct{};
-    read_a2(ar0, 0, 0, 0); read_a2(ar0, 0, 0, 2); read_a2(ar0, 0, 1, 0); read_a2(ar0, 0, 1, 2);
+    a1 = Half{};
+    read_a2(a0, 0, 0, 0); read_a2(a0, 0, 0, 2);
     if (cnt == 4) { BIG_LOOP(mf) } else { BIG_LOOP(mf_some) }
 #undef BIG_LOOP
 #undef BIG_STEP
@@ -429,30 +443,22 @@ k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
     // ---- K slices: each slice writes its fp32 partial tile row-major into its own plane of the
     // workspace ([slice][row][N]); k_splitk_finish adds the planes in slice order and applies the
     // epilogue, so the result does not depend on timing and no atomics or fences are needed.
+    // (written out per row tile: the accumulators must be named statically)
+#define EPI_ROW(E, ARGS, I)                                                                                   \
+    if (4 * wm + (I) < mbs) {                                                                                 \
+        epilogue_tile<E>(ARGS, acc[I][0], acc[I][1], row_base + 32 * (4 * wm + (I)), n, nbw, lane);           \
+        if constexpr (NS == 4)                                                                                \
+            epilogue_tile<E>(ARGS, acc[I][NS - 2], acc[I][NS - 1], row_base + 32 * (4 * wm + (I)), n, nbw + 2, lane); \
+    }
     if (splits > 1) {
         EpiArgs pe = ep;
         pe.out = partial + (int64_t)sp * part_plane;
         pe.ldo = part_ld;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int mb = 4 * wm + i;
-            if (mb < mbs) {
-#pragma unroll
-                for (int j = 0; j < NS; j += 2)
-                    epilogue_tile<EPI_STORE>(pe, acc[i][j], acc[i][j + 1], row_base + 32 * mb, n, nbw + j, lane);
-            }
-        }
+        EPI_ROW(EPI_STORE, pe, 0) EPI_ROW(EPI_STORE, pe, 1) EPI_ROW(EPI_STORE, pe, 2) EPI_ROW(EPI_STORE, pe, 3)
         return;
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int mb = 4 * wm + i;
-        if (mb < mbs) {
-#pragma unroll
-            for (int j = 0; j < NS; j += 2)
-                epilogue_tile<EPI>(ep, acc[i][j], acc[i][j + 1], row_base + 32 * mb, n, nbw + j, lane);
-        }
-    }
+    EPI_ROW(EPI, ep, 0) EPI_ROW(EPI, ep, 1) EPI_ROW(EPI, ep, 2) EPI_ROW(EPI, ep, 3)
+#undef EPI_ROW
 }
 
 // ------------------------------------------------------------------ RoPE + cache append

