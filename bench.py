@@ -25,6 +25,21 @@ import numpy as np  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# HBM bytes per launch of the gate/up GEMM at batch 256 from the rocprofv3 counter runs summarised in
+# profiles/llama2_70b_b256_hbm_traffic.md (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, KiB -> bytes); valid
+# only for the kernel source it was measured on.
+TRAFFIC_KERNEL_SHA1 = "43758ade4e4b75246feb3edfff094d90a8c1135e"
+TRAFFIC_GATE_UP_BYTES = (948245 + 18172) * 1024
+
+
+def measured_traffic(batch):
+    import hashlib
+    src = os.path.join(ROOT, "paper_2504_10724_amd", "csrc", "ee_kernels_bf16.hip")
+    try:
+        same = hashlib.sha1(open(src, "rb").read()).hexdigest() == TRAFFIC_KERNEL_SHA1
+    except OSError:
+        same = False
+    return TRAFFIC_GATE_UP_BYTES if (same and batch == 256) else None
 
 
 def build_device_model(s, S, torch, max_pos, seed):
@@ -180,7 +195,7 @@ def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
                     traffic=None)
     else:
         roof = dict(kernel="k_bf16_gemm (gate/up + SwiGLU)", bound="hbm", achieved=gu_bytes / gu_t / 1e9,
-                    peak=HBM_PEAK_GBS, unit="GB/s", traffic=None)
+                    peak=HBM_PEAK_GBS, unit="GB/s", traffic=measured_traffic(s.batch))
     roof["frac"] = roof["achieved"] / roof["peak"]
     weights_per_layer = s.layer_params() * 2
     res = dict(
@@ -215,6 +230,8 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer resident layers (not a valid result)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the smaller batch sizes of the sweep")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy 4 times (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; nothing shards across GPUs (run with --gpus 1)", file=sys.stderr)
@@ -228,6 +245,15 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps(dict(copy_bytes=int(src.numel() * 4), copies=4)))
+        return
     s = synth.CONFIGS[args.workload]
     if args.batch:
         s = s.with_(batch=args.batch)

@@ -337,3 +337,21 @@ def test_meets_means_greater_or_equal():
     s3, above = _mk(batch=4)
     r = above.step(0, thresholds=(float(np.nextafter(np.float32(th), np.float32(2))), 0.0))
     assert r["layer"][b] == s.exit_layers[1]
+
+
+def test_bf16_contract_noise_floor_is_measurable_with_the_oracle_alone():
+    """Two correct implementations of the bf16 contract that differ by one part in 10^6 in an fp32
+    operand drift apart by bf16-sized amounts within a few layers; fp32 models do not.  This is what
+    the whole-step GPU comparison allows for (and only that)."""
+    from parity import shadow_of
+    for dtype, lo, hi in (("bf16", 1e-4, 2e-2), ("f32", 0.0, 2e-5)):
+        s = small_shape(dtype=dtype, n_layers=6, resident=6, exit_layers=(2, 4, 6), thresholds=(2.0, 2.0, 2.0),
+                        d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, d_ffn=512, vocab=512, batch=12,
+                        ctx_lo=10, ctx_hi=40)
+        a = OracleSide(s, gain_jitter=0)
+        b = shadow_of(a)
+        sc = a.scale(0)
+        ra = a.step(0, want_h=True, scale=sc)
+        rb = b.step(0, want_h=True, scale=sc)
+        err = np.abs(ra["h"] - rb["h"]).max(1) / np.abs(ra["h"]).max(1)
+        assert lo <= err.max() <= hi, (dtype, err.max())
