@@ -41,7 +41,10 @@ def rows_close(got, want, tol):
 class GpuSide:
     """libee model + cache + batch state for the same synthetic workload the oracle sees."""
 
-    def __init__(self, s, weights=None, std=0.02, cap_multiple=32, max_pos=None):
+    def __init__(self, s, weights=None, std=0.02, cap_multiple=32, max_pos=None, synth_rows=None):
+        """synth_rows: if given, only these rows get their cached context from the seeded host
+        generator (the rows an oracle will recompute); the others are filled on the device from
+        the same distribution, which is much faster for large batches."""
         self.s = s
         if weights is None:
             weights = {
@@ -59,8 +62,13 @@ class GpuSide:
             self.model.set_exit(e, **w)
         self.model.set_embed(weights["embed"])
         self.kv = S.KVCache(self.model, s.resident, self.cap)
+        if synth_rows is not None:
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(s.seed + 1)
+            pool = self.kv.pool.view(torch.bfloat16 if s.dtype == "bf16" else torch.float32)
+            pool.normal_(0.0, 0.02 * float(np.sqrt(s.d_model)), generator=gen)
         for l in range(1, s.resident + 1):
-            for b in range(s.batch):
+            for b in (range(s.batch) if synth_rows is None else synth_rows):
                 K, V = synth.kv_rows(s, l, b, int(self.ctx[b]))
                 self.kv.write_context(l, b, K, V)
         self.batch = S.Batch(self.model, s.batch)
