@@ -241,3 +241,46 @@ def fill_skipped_kv(model, from_excl, to_incl, kv, batch):
 def decode_step(model, kv, batch, thresholds):
     th = (C.c_float * len(thresholds))(*thresholds)
     return model.lib.ee_decode_step(model.h, kv.h, batch.h, th, len(thresholds), _stream())
+
+
+class WindowSwitcher:
+    """Host-side routing of one batch between several resident (partially loaded) models in fixed
+    windows of decode steps: each model serves one window first, afterwards every window goes to
+    the model whose last window had the larger fraction of tokens that left by confidence (not
+    forced at its last resident layer); ties go to the earlier model.  Each model keeps its own
+    cache, positions and token stream and is frozen while idle.  Policy only: every decode step
+    is libee's."""
+
+    def __init__(self, lanes, window):
+        """lanes: list of (model, kv, batch, thresholds)"""
+        self.lanes = lanes
+        self.window = window
+        self.last_fraction = [None] * len(lanes)
+        self.steps_done = [0] * len(lanes)
+        self.history = []
+
+    def choose(self):
+        for i, f in enumerate(self.last_fraction):
+            if f is None:
+                return i
+        best = 0
+        for i, f in enumerate(self.last_fraction):
+            if f > self.last_fraction[best]:
+                best = i
+        return best
+
+    def run_window(self, scale_for):
+        """scale_for(lane index, that lane's step index) -> per-row logit scales"""
+        i = self.choose()
+        model, kv, batch, th = self.lanes[i]
+        before = int(batch.field("breach_count").cpu()[0])
+        for _ in range(self.window):
+            batch.set_row_scale(scale_for(i, self.steps_done[i]))
+            ee.check(decode_step(model, kv, batch, list(th)))
+            self.steps_done[i] += 1
+        torch.cuda.current_stream().synchronize()
+        breaches = int(batch.field("breach_count").cpu()[0]) - before
+        tokens = self.window * batch.B
+        self.last_fraction[i] = 1.0 - breaches / tokens
+        self.history.append((i, self.last_fraction[i]))
+        return i, self.last_fraction[i]

@@ -322,3 +322,59 @@ def test_full_size_shapes_sampled_rows(s, rows):
     assert gg["counts"][0] + gg["counts"][1] == s.batch
     assert np.all(gg["conf"][gg["layer"] == 1] >= th0)
     assert np.array_equal(gg["pos"], g.ctx + 1)
+
+
+# ---------------------------------------------------------------- two resident models, window routing
+def test_two_model_window_switching():
+    """Two partially loaded models (different seeds, logit-scale distributions shifted by +-0.5 in
+    log scale) share the GPU; each window of decode steps goes to the model with the higher
+    confident-exit fraction in its last window.  The same rule, written separately here, drives two
+    oracles; routing decisions and per-window fractions must agree."""
+    mk = lambda key, name: synth.CONFIGS[key].with_(name=name, n_layers=3, resident=2, d_model=512, n_q_heads=4,
+                                                    n_kv_heads=4, d_ffn=1024, vocab=2048, exit_layers=(1, 2, 3),
+                                                    thresholds=(0.8, 0.8), batch=48, ctx_lo=20, ctx_hi=90, steps=12)
+    shapes = [mk("switch_7b_a", "switch_a"), mk("switch_7b_b", "switch_b")]
+    window, n_windows = 3, 4
+    _say(f"[case] window switching B={shapes[0].batch} window={window} windows={n_windows}")
+    oracles = [OracleSide(s, gain_jitter=0.0) for s in shapes]
+    gpus = [GpuSide(s, weights=o.weights) for s, o in zip(shapes, oracles)]
+    shadows = [shadow_of(o) for o in oracles]
+    sw = S.WindowSwitcher([(g.model, g.kv, g.batch, s.thresholds) for g, s in zip(gpus, shapes)], window)
+    last = [None, None]
+    done = [0, 0]
+    sticky = [np.zeros(s.batch, bool) for s in shapes]
+    for w in range(n_windows):
+        # the rule, on the oracle side
+        if last[0] is None:
+            pick = 0
+        elif last[1] is None:
+            pick = 1
+        else:
+            pick = 0 if last[0] >= last[1] else 1
+        s, o, sh = shapes[pick], oracles[pick], shadows[pick]
+        breaches, slack = 0, 0
+        for k in range(window):
+            sc = synth.row_scale(s, done[pick] + k)
+            sh.tok = o.tok.copy()
+            r = o.step(done[pick] + k, scale=sc)
+            rs = sh.step(done[pick] + k, scale=sc)
+            breaches += int(r["breach"].sum())
+            # rows whose breach flag could legitimately differ on another correct implementation
+            band = max(NEAR, float(np.nanmax(np.abs(r["conf_trace"][:, 1] - rs["conf_trace"][:, 1]))))
+            c = r["conf_trace"][:, 1]
+            slack += int(np.sum(np.isfinite(c) & (np.abs(c - np.float32(s.thresholds[1])) <= band)))
+            slack += int(np.sum(r["layer"] != rs["layer"]))
+            sticky[pick] |= (r["layer"] != rs["layer"]) | (r["tok"] != rs["tok"])
+        frac_o = 1.0 - breaches / (window * s.batch)
+        gi, frac_g = sw.run_window(lambda lane, step: synth.row_scale(shapes[lane], step))
+        _say(f"  window {w}: oracle -> model {pick} fraction {frac_o:.4f}; gpu -> model {gi} fraction {frac_g:.4f} "
+             f"(slack {slack} rows)")
+        assert gi == pick
+        assert abs(frac_g - frac_o) <= (slack + sticky[pick].sum() * window) / (window * s.batch) + 1e-9
+        done[pick] += window
+        last[pick] = frac_o
+        if last[0] is not None and last[1] is not None and abs(last[0] - last[1]) <= 2 * (slack + 1) / (window * s.batch):
+            _say("  fractions too close for a robust routing comparison; stopping here")
+            break
+    assert np.array_equal(gpus[0].batch.field("pos").cpu().numpy(), oracles[0].pos)
+    assert np.array_equal(gpus[1].batch.field("pos").cpu().numpy(), oracles[1].pos)
