@@ -407,14 +407,14 @@ k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
     };
 #define SB __builtin_amdgcn_sched_barrier(0);
 #define BIG_STEP(MF, U, XNEW, BNEW, BCUR, XOUT)                                               \
-    MF(a0, BCUR, 0, 0); SB store_x01((t0 + (U) + 2) % 3, XOUT); SB                            \
-    MF(a0, BCUR, 0, 1); SB store_x23((t0 + (U) + 2) % 3, XOUT); SB                            \
-    MF(a0, BCUR, 0, 2); SB read_a2(a1, (t0 + (U)) % 3, 1, 0); SB                              \
-    MF(a0, BCUR, 0, 3); SB read_a2(a1, (t0 + (U)) % 3, 1, 2); SB                              \
+    MF(a0, BCUR, 0, 0); SB read_a2(a1, (t0 + (U)) % 3, 1, 0); SB                              \
+    MF(a0, BCUR, 0, 1); SB read_a2(a1, (t0 + (U)) % 3, 1, 2); SB                              \
+    MF(a0, BCUR, 0, 2); SB                                                                    \
+    MF(a0, BCUR, 0, 3); SB                                                                    \
     MF(a1, BCUR, 1, 0); SB read_a2(a0, (t0 + (U) + 1) % 3, 0, 0); SB                          \
     MF(a1, BCUR, 1, 1); SB read_a2(a0, (t0 + (U) + 1) % 3, 0, 2); SB                          \
-    MF(a1, BCUR, 1, 2); SB XNEW = load_x(t0 + (U) + 3); SB                                    \
-    MF(a1, BCUR, 1, 3); SB BNEW = load_w(t0 + (U) + 3); SB                                    \
+    MF(a1, BCUR, 1, 2); SB store_x01((t0 + (U) + 2) % 3, XOUT); store_x23((t0 + (U) + 2) % 3, XOUT); SB \
+    MF(a1, BCUR, 1, 3); SB XNEW = load_x(t0 + (U) + 3); BNEW = load_w(t0 + (U) + 3); SB       \
     lds_barrier();
     // step t stores X(t+2) from xr(t % 2) and loads X(t+3) into the other set, which held X(t+1)
     // and was written to LDS during step t-1; W(t+3) replaces W(t-1), consumed during step t-1.
@@ -458,6 +458,120 @@ k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
         return;
     }
     EPI_ROW(EPI, ep, 0) EPI_ROW(EPI, ep, 1) EPI_ROW(EPI, ep, 2) EPI_ROW(EPI, ep, 3)
+#undef EPI_ROW
+}
+
+// ------------------------------------------------------------------ wide-tile variant
+// 256 rows x 256 columns per workgroup with the four waves side by side along N: wave w owns
+// columns 64 w .. 64 w + 63 for all eight row tiles (8 x 2 MFMA tiles, 256 accumulator
+// registers).  Every W tile is fetched by exactly one wave, so the vector-memory path carries
+// the weights once per CU instead of once per row half; the price is that every wave reads all
+// A tiles from LDS (2 MFMAs per 1 KiB read).  Same stage pipeline as k_bf16_gemm_big.
+struct Oct { uint4 v[8]; };   // A operands of one K half: 8 row tiles
+
+template <int EPI>
+__global__ void __launch_bounds__(BIG_THREADS, 1)
+k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int NBs, int nb_off,
+                 int n_tiles, const int32_t* __restrict__ n_ptr, int B, EpiArgs ep, ZBatch zb) {
+    __shared__ uint4 xl[3][16][64];
+    const int n = min(*n_ptr, B);
+    const int rg = blockIdx.y;
+    const int row_base = rg * 256;
+    if (row_base >= n) return;
+    if (zb.w_tab) Wp = reinterpret_cast<const uint4*>(zb.w_tab[zb.z0 + blockIdx.z]);
+    Xp += (int64_t)blockIdx.z * zb.x_stride;
+    ep.out += (int64_t)blockIdx.z * zb.out_stride;
+    const int mbs = min(8, (n - row_base + 31) >> 5);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nbw = (blockIdx.x * 4 + wave) * 2;             // this wave's two tile-rows of W
+    const int T = KB >> 1;                                   // 32-wide K steps, a multiple of 4
+    const uint4* xg = Xp + ((int64_t)rg * 8 * KB) * 64 + lane;
+    const uint4* wg = Wp + (int64_t)(nb_off + nbw) * 64 + lane;
+
+    floatx16 acc[8][2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    Quad xr0, xr1;
+    WFrag<2> br0, br1, br2, br3;
+    Oct a0, a1;
+    auto load_x = [&](int t) -> Quad {
+        const int kb0 = 2 * min(t, T - 1);
+        const int m0 = min(2 * wave, mbs - 1), m1 = min(2 * wave + 1, mbs - 1);
+        Quad q;
+        q.a = xg[((int64_t)m0 * KB + kb0) * 64];
+        q.b = xg[((int64_t)m0 * KB + kb0 + 1) * 64];
+        q.c = xg[((int64_t)m1 * KB + kb0) * 64];
+        q.d = xg[((int64_t)m1 * KB + kb0 + 1) * 64];
+        return q;
+    };
+    auto load_w = [&](int t) -> WFrag<2> {
+        const int kb0 = 2 * min(t, T - 1);
+        WFrag<2> q;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int ns = 0; ns < 2; ++ns) q.v[kk][ns] = wg[((int64_t)(kb0 + kk) * NBs + ns) * 64];
+        return q;
+    };
+    auto store_x = [&](int buf, const Quad& q) {
+        xl[buf][4 * wave + 0][lane] = q.a;
+        xl[buf][4 * wave + 1][lane] = q.b;
+        xl[buf][4 * wave + 2][lane] = q.c;
+        xl[buf][4 * wave + 3][lane] = q.d;
+    };
+    auto mf = [&](const Oct& a, const WFrag<2>& bw, int kk, int i) {   // 4 MFMAs: row tiles i, i+1
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            if (i + r < mbs) {
+                acc[i + r][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[i + r]), as_bf16x8(bw.v[kk][0]),
+                                                                        acc[i + r][0], 0, 0, 0);
+                acc[i + r][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[i + r]), as_bf16x8(bw.v[kk][1]),
+                                                                        acc[i + r][1], 0, 0, 0);
+            }
+        }
+    };
+    auto read_a2 = [&](Oct& o, int buf, int kk, int i) {
+        o.v[i] = xl[buf][i * 2 + kk][lane];
+        o.v[i + 1] = xl[buf][(i + 1) * 2 + kk][lane];
+    };
+#define SB __builtin_amdgcn_sched_barrier(0);
+#define WIDE_STEP(U, XNEW, BNEW, BCUR, XOUT)                                                  \
+    mf(a0, BCUR, 0, 0); SB read_a2(a1, (t0 + (U)) % 3, 1, 0); read_a2(a1, (t0 + (U)) % 3, 1, 2); SB         \
+    mf(a0, BCUR, 0, 2); SB read_a2(a1, (t0 + (U)) % 3, 1, 4); read_a2(a1, (t0 + (U)) % 3, 1, 6); SB         \
+    mf(a0, BCUR, 0, 4); SB                                                                    \
+    mf(a0, BCUR, 0, 6); SB                                                                    \
+    mf(a1, BCUR, 1, 0); SB read_a2(a0, (t0 + (U) + 1) % 3, 0, 0); read_a2(a0, (t0 + (U) + 1) % 3, 0, 2); SB \
+    mf(a1, BCUR, 1, 2); SB read_a2(a0, (t0 + (U) + 1) % 3, 0, 4); read_a2(a0, (t0 + (U) + 1) % 3, 0, 6); SB \
+    mf(a1, BCUR, 1, 4); SB store_x((t0 + (U) + 2) % 3, XOUT); SB                              \
+    mf(a1, BCUR, 1, 6); SB XNEW = load_x(t0 + (U) + 3); BNEW = load_w(t0 + (U) + 3); SB       \
+    lds_barrier();
+
+    xr0 = load_x(0); br0 = load_w(0);
+    xr1 = load_x(1); br1 = load_w(1);
+    store_x(0, xr0);
+    store_x(1, xr1);
+    xr0 = load_x(2); br2 = load_w(2);
+    br3 = br2;
+    lds_barrier();
+    a1 = Oct{};
+    read_a2(a0, 0, 0, 0); read_a2(a0, 0, 0, 2); read_a2(a0, 0, 0, 4); read_a2(a0, 0, 0, 6);
+    for (int t0 = 0; t0 < T; t0 += 4) {
+        WIDE_STEP(0, xr1, br3, br0, xr0)
+        WIDE_STEP(1, xr0, br0, br1, xr1)
+        WIDE_STEP(2, xr1, br1, br2, xr0)
+        WIDE_STEP(3, xr0, br2, br3, xr1)
+    }
+#undef WIDE_STEP
+#undef SB
+#define EPI_ROW(I) \
+    if ((I) < mbs) epilogue_tile<EPI>(ep, acc[I][0], acc[I][1], row_base + 32 * (I), n, nbw, lane);
+    EPI_ROW(0) EPI_ROW(1) EPI_ROW(2) EPI_ROW(3) EPI_ROW(4) EPI_ROW(5) EPI_ROW(6) EPI_ROW(7)
 #undef EPI_ROW
 }
 
@@ -732,9 +846,8 @@ static bool gemm_big(const ee_batch* b, const void* X, const void* W, int N, int
     }
     dim3 grid(n_tiles * splits, row_groups, nz);
     if (wide)
-        hipLaunchKernelGGL((k_bf16_gemm_big<EPI, 4>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
-                           K / 16, NBs, nb_off, n_tiles, splits, n_ptr, B, b->wsp<float>(b->W.gemm_part),
-                           (int64_t)Mpad * N, N, ep, zb);
+        hipLaunchKernelGGL((k_bf16_gemm_wide<EPI>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
+                           K / 16, NBs, nb_off, n_tiles, n_ptr, B, ep, zb);
     else
         hipLaunchKernelGGL((k_bf16_gemm_big<EPI, 2>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
                            K / 16, NBs, nb_off, n_tiles, splits, n_ptr, B, b->wsp<float>(b->W.gemm_part),
