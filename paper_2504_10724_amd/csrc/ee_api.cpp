@@ -360,10 +360,13 @@ static void lay_workspace(const ee_model* m, int B, WsLayout* W) {
         size_t fill_layers = c.n_layers > 1 ? (size_t)c.n_layers - 1 : 1;   // all skipped layers in one launch
         W->fill_x = take(fill_layers * Mpad * c.d_model * 2);
         W->fill_kv = take(fill_layers * Mpad * kvn * 4);
-        W->gemm_part_bytes = B > 64 ? ((size_t)64 << 20) : 0;
+        W->gemm_part_bytes = B > 64 ? ((size_t)96 << 20) : 0;
         W->gemm_part = take(W->gemm_part_bytes);
         W->gemm_cnt_ints = 4096;
         W->gemm_cnt = take(W->gemm_cnt_ints * 4);
+        size_t pairs = Mpad * (size_t)c.n_kv_heads;   // position shares only when there are few pairs
+        W->attn_part_bytes = pairs < 512 + 32 * (size_t)c.n_kv_heads ? pairs * 16 * 16 * 130 * 4 : 0;
+        W->attn_part = take(W->attn_part_bytes);
     } else {
         size_t wide = (size_t)c.vocab > 2 * (size_t)c.d_ffn ? (size_t)c.vocab : 2 * (size_t)c.d_ffn;
         W->x = take(Mpad * c.d_model * 4);
@@ -380,6 +383,7 @@ static void lay_workspace(const ee_model* m, int B, WsLayout* W) {
         W->fill_kv = take(Mpad * kvn * 4);
         W->gemm_part_bytes = 0; W->gemm_part = take(0);
         W->gemm_cnt_ints = 0;   W->gemm_cnt = take(0);
+        W->attn_part_bytes = 0; W->attn_part = take(0);
     }
     W->total = o;
 }

@@ -44,7 +44,8 @@ struct ee_kv {
 // byte offsets inside the workspace
 struct WsLayout {
     size_t x, qkv, q_hi, q_lo, ao, act, part_max, part_sum, part_arg, logits, fill_x, fill_kv, total;
-    size_t gemm_part, gemm_part_bytes, gemm_cnt, gemm_cnt_ints;   // split-K partial tiles and their arrival counters
+    size_t gemm_part, gemm_part_bytes, gemm_cnt, gemm_cnt_ints;   // K-slice partial planes
+    size_t attn_part, attn_part_bytes;                            // attention position shares
 };
 
 struct ee_batch {

@@ -472,7 +472,8 @@ struct Oct { uint4 v[8]; };   // A operands of one K half: 8 row tiles
 template <int EPI>
 __global__ void __launch_bounds__(BIG_THREADS, 1)
 k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int NBs, int nb_off,
-                 int n_tiles, const int32_t* __restrict__ n_ptr, int B, EpiArgs ep, ZBatch zb) {
+                 int n_tiles, int splits, const int32_t* __restrict__ n_ptr, int B, float* __restrict__ partial,
+                 int64_t part_plane, int part_ld, EpiArgs ep, ZBatch zb) {
     __shared__ uint4 xl[3][16][64];
     const int n = min(*n_ptr, B);
     const int rg = blockIdx.y;
@@ -484,8 +485,11 @@ k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
     const int mbs = min(8, (n - row_base + 31) >> 5);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nbw = (blockIdx.x * 4 + wave) * 2;             // this wave's two tile-rows of W
-    const int T = KB >> 1;                                   // 32-wide K steps, a multiple of 4
+    const int tile = blockIdx.x / splits, sp = blockIdx.x % splits;
+    const int nbw = (tile * 4 + wave) * 2;                   // this wave's two tile-rows of W
+    const int KS4 = KB >> 3;                                 // groups of four 32-wide K steps
+    const int ks_lo = 4 * (int)(((int64_t)KS4 * sp) / splits), ks_hi = 4 * (int)(((int64_t)KS4 * (sp + 1)) / splits);
+    const int T = ks_hi - ks_lo;                             // K steps of this slice: a positive multiple of 4
     const uint4* xg = Xp + ((int64_t)rg * 8 * KB) * 64 + lane;
     const uint4* wg = Wp + (int64_t)(nb_off + nbw) * 64 + lane;
 
@@ -501,7 +505,7 @@ k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
     WFrag<2> br0, br1, br2, br3;
     Oct a0, a1;
     auto load_x = [&](int t) -> Quad {
-        const int kb0 = 2 * min(t, T - 1);
+        const int kb0 = 2 * (ks_lo + min(t, T - 1));
         const int m0 = min(2 * wave, mbs - 1), m1 = min(2 * wave + 1, mbs - 1);
         Quad q;
         q.a = xg[((int64_t)m0 * KB + kb0) * 64];
@@ -511,7 +515,7 @@ k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
         return q;
     };
     auto load_w = [&](int t) -> WFrag<2> {
-        const int kb0 = 2 * min(t, T - 1);
+        const int kb0 = 2 * (ks_lo + min(t, T - 1));
         WFrag<2> q;
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk)
@@ -569,9 +573,18 @@ k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
     }
 #undef WIDE_STEP
 #undef SB
-#define EPI_ROW(I) \
-    if ((I) < mbs) epilogue_tile<EPI>(ep, acc[I][0], acc[I][1], row_base + 32 * (I), n, nbw, lane);
-    EPI_ROW(0) EPI_ROW(1) EPI_ROW(2) EPI_ROW(3) EPI_ROW(4) EPI_ROW(5) EPI_ROW(6) EPI_ROW(7)
+#define EPI_ROW(E, ARGS, I) \
+    if ((I) < mbs) epilogue_tile<E>(ARGS, acc[I][0], acc[I][1], row_base + 32 * (I), n, nbw, lane);
+    if (splits > 1) {   // K slices: fp32 partial planes, finished by k_splitk_finish
+        EpiArgs pe = ep;
+        pe.out = partial + (int64_t)sp * part_plane;
+        pe.ldo = part_ld;
+        EPI_ROW(EPI_STORE, pe, 0) EPI_ROW(EPI_STORE, pe, 1) EPI_ROW(EPI_STORE, pe, 2) EPI_ROW(EPI_STORE, pe, 3)
+        EPI_ROW(EPI_STORE, pe, 4) EPI_ROW(EPI_STORE, pe, 5) EPI_ROW(EPI_STORE, pe, 6) EPI_ROW(EPI_STORE, pe, 7)
+        return;
+    }
+    EPI_ROW(EPI, ep, 0) EPI_ROW(EPI, ep, 1) EPI_ROW(EPI, ep, 2) EPI_ROW(EPI, ep, 3)
+    EPI_ROW(EPI, ep, 4) EPI_ROW(EPI, ep, 5) EPI_ROW(EPI, ep, 6) EPI_ROW(EPI, ep, 7)
 #undef EPI_ROW
 }
 
@@ -644,7 +657,8 @@ k_bf16_rope_append(const float* __restrict__ buf, int ld, int n_q, const int32_t
 __global__ void __launch_bounds__(256)
 k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, int Hq,
             const int32_t* __restrict__ idx, const int32_t* __restrict__ n_ptr, int B,
-            const int32_t* __restrict__ pos, KvView kv, uint4* __restrict__ ao, int KB_ao) {
+            const int32_t* __restrict__ pos, KvView kv, uint4* __restrict__ ao, int KB_ao, int n_splits,
+            float* __restrict__ part) {
     __shared__ float sm_m[4][16];
     __shared__ float sm_l[4][16];
     __shared__ float sm_o[4][16][128];
@@ -678,7 +692,10 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
     for (int hb = 0; hb < 8; ++hb) O[hb] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     const int n_groups = (n_pos + 31) >> 5;
-    for (int t = w; t < n_groups; t += 4) {
+    // with n_splits > 1 this workgroup covers the blockIdx.z-th share of the position groups
+    const int g_lo = (int)(((int64_t)n_groups * blockIdx.z) / n_splits);
+    const int g_hi = (int)(((int64_t)n_groups * (blockIdx.z + 1)) / n_splits);
+    for (int t = g_lo + w; t < g_hi; t += 4) {
         const int p0 = t << 5;
         floatx4 S0 = {0.f, 0.f, 0.f, 0.f}, S1 = {0.f, 0.f, 0.f, 0.f};
         const bf16_t* k0 = Kb + (int64_t)(p0 + n16) * 128 + 8 * gq;
@@ -764,13 +781,48 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
                 float acc = 0.f;
 #pragma unroll
                 for (int k = 0; k < 4; ++k) acc += sm_o[k][head][c0 + j] * wgt[k];
-                o[j] = acc / Lsum;
+                o[j] = acc;
             }
-            uint4 pk = make_uint4(pack2(o[0], o[1]), pack2(o[2], o[3]), pack2(o[4], o[5]), pack2(o[6], o[7]));
-            int col = (g * G + head) * 128 + c0;
-            ao[afrag_chunk(i, col, KB_ao)] = pk;
+            if (n_splits == 1) {
+                uint4 pk = make_uint4(pack2(o[0] / Lsum, o[1] / Lsum), pack2(o[2] / Lsum, o[3] / Lsum),
+                                      pack2(o[4] / Lsum, o[5] / Lsum), pack2(o[6] / Lsum, o[7] / Lsum));
+                int col = (g * G + head) * 128 + c0;
+                ao[afrag_chunk(i, col, KB_ao)] = pk;
+            } else {
+                // unnormalised share: [i][kv head][split][head][130] = 128 features, max, sum
+                float* p = part + ((((int64_t)i * kv.n_kv_heads + g) * n_splits + blockIdx.z) * 16 + head) * 130;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) p[c0 + j] = o[j];
+                if (c0 == 0) { p[128] = M; p[129] = Lsum; }
+            }
         }
     }
+}
+
+// merges the position shares of k_bf16_attn in share order: one workgroup per (kv head, list entry)
+__global__ void __launch_bounds__(256)
+k_bf16_attn_merge(const float* __restrict__ part, int Hq, int Hkv, int n_splits, const int32_t* __restrict__ n_ptr,
+                  int B, uint4* __restrict__ ao, int KB_ao) {
+    const int g = blockIdx.x, i = blockIdx.y;
+    const int n = min(*n_ptr, B);
+    if (i >= n) return;
+    const int G = Hq / Hkv;
+    const int head = threadIdx.x >> 4, c0 = (threadIdx.x & 15) * 8;
+    if (head >= G) return;
+    const float* base = part + (((int64_t)i * Hkv + g) * n_splits * 16 + head) * 130;
+    float M = -1.0e30f;
+    for (int q = 0; q < n_splits; ++q) M = fmaxf(M, base[(int64_t)q * 16 * 130 + 128]);
+    float L = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int q = 0; q < n_splits; ++q) {
+        const float* p = base + (int64_t)q * 16 * 130;
+        float wq = __expf(p[128] - M);
+        L += p[129] * wq;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] += p[c0 + j] * wq;
+    }
+    uint4 pk = make_uint4(pack2(o[0] / L, o[1] / L), pack2(o[2] / L, o[3] / L), pack2(o[4] / L, o[5] / L),
+                          pack2(o[6] / L, o[7] / L));
+    ao[afrag_chunk(i, (g * G + head) * 128 + c0, KB_ao)] = pk;
 }
 
 // ------------------------------------------------------------------ host side
@@ -836,7 +888,9 @@ static bool gemm_big(const ee_batch* b, const void* X, const void* W, int N, int
     int Mpad = (B + 31) / 32 * 32;
     int KS = K / 32;
     // wide tiles halve the LDS traffic per MFMA; worth it when they still give every CU a workgroup
-    bool wide = (N % 256 == 0) && (N / 256) * row_groups * nz >= 200;
+    // the wide tile moves every weight tile through the vector-memory path once; worth it when it
+    // still fills the chip, or when K is long enough that a deeper K slicing costs little
+    bool wide = (N % 256 == 0) && ((N / 256) * row_groups * nz >= 200 || (EPI == EPI_RESID && K >= 2 * N));
     int n_tiles = wide ? N / 256 : N / 128;
     int splits = 1;
     if ((EPI == EPI_STORE || EPI == EPI_RESID) && nz == 1 && n_tiles * row_groups < 200) {
@@ -847,7 +901,8 @@ static bool gemm_big(const ee_batch* b, const void* X, const void* W, int N, int
     dim3 grid(n_tiles * splits, row_groups, nz);
     if (wide)
         hipLaunchKernelGGL((k_bf16_gemm_wide<EPI>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
-                           K / 16, NBs, nb_off, n_tiles, n_ptr, B, ep, zb);
+                           K / 16, NBs, nb_off, n_tiles, splits, n_ptr, B, b->wsp<float>(b->W.gemm_part),
+                           (int64_t)Mpad * N, N, ep, zb);
     else
         hipLaunchKernelGGL((k_bf16_gemm_big<EPI, 2>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
                            K / 16, NBs, nb_off, n_tiles, splits, n_ptr, B, b->wsp<float>(b->W.gemm_part),
@@ -894,9 +949,17 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
     }
     {
         TimedScope t(EE_K_ATTENTION, s);
-        hipLaunchKernelGGL(k_bf16_attn, dim3(c.n_kv_heads, B), dim3(256), 0, s, b->wsp<bf16_t>(b->W.q_hi),
+        // few (row, kv head) pairs: also split the positions, so that the chip has workgroups to run
+        int pairs = c.n_kv_heads * B;
+        int n_splits = pairs >= 512 ? 1 : (1024 + pairs - 1) / pairs;
+        if (n_splits > 16) n_splits = 16;
+        while (n_splits > 1 && (size_t)b->Mpad * c.n_kv_heads * n_splits * 16 * 130 * 4 > b->W.attn_part_bytes) --n_splits;
+        hipLaunchKernelGGL(k_bf16_attn, dim3(c.n_kv_heads, B, n_splits), dim3(256), 0, s, b->wsp<bf16_t>(b->W.q_hi),
                            b->wsp<bf16_t>(b->W.q_lo), c.n_q_heads, idx, n_ptr, B, b->st<int32_t>(L.pos), view, ao,
-                           qd / 16);
+                           qd / 16, n_splits, b->wsp<float>(b->W.attn_part));
+        if (n_splits > 1)
+            hipLaunchKernelGGL(k_bf16_attn_merge, dim3(c.n_kv_heads, B), dim3(256), 0, s, b->wsp<float>(b->W.attn_part),
+                               c.n_q_heads, c.n_kv_heads, n_splits, n_ptr, B, ao, qd / 16);
     }
     EpiArgs e2{};
     e2.out = h; e2.ldo = d; e2.idx = idx;

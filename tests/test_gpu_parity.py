@@ -292,7 +292,9 @@ def test_full_size_shapes_sampled_rows(s, rows):
     worst, ok = rows_close(hg, og["h"], TOL["bf16"])
     _say(f"  hidden state at exit: worst sampled row error {worst:.2e}")
     assert ok
-    band = max(NEAR, float(np.nanmax(np.abs(og["conf_trace"][:, 0] - sg["conf_trace"][:, 0]))))
+    # a handful of sampled rows cannot estimate the tail of the contract's rounding noise, so the
+    # band never goes below the 1e-2 that the batch-wide step tests measure at these scales
+    band = max(1e-2, float(np.nanmax(np.abs(og["conf_trace"][:, 0] - sg["conf_trace"][:, 0]))))
     th0 = np.float32(s.thresholds[0])
     for i, b in enumerate(rows):
         c1 = og["conf_trace"][i, 0]
