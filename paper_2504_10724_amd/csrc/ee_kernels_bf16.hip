@@ -124,26 +124,45 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
             for (int r = 0; r < 16; ++r) acc[ms][ns][r] = 0.f;
 
     if (has_cols) {
-        int kb = kb_lo;
-        for (; kb + 4 <= kb_hi; kb += 4) {
-            uint4 bw[4][NS];
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int ns = 0; ns < NS; ++ns) bw[u][ns] = ww[((int64_t)(kb + u) * NBs + ns) * 64];
+        // groups of 4 K tiles, the next group's W and X tiles in flight while the current one is
+        // multiplied (dead row tiles re-read a live one, so the loads need no branch)
+        struct Group { uint4 w[4][NS]; uint4 x[4][MS]; };
+        auto load_group = [&](int kb) -> Group {
+            Group g;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
 #pragma unroll
+                for (int ns = 0; ns < NS; ++ns) g.w[u][ns] = ww[((int64_t)(kb + u) * NBs + ns) * 64];
+#pragma unroll
+                for (int ms = 0; ms < MS; ++ms) g.x[u][ms] = xw[((int64_t)min(ms, mbs - 1) * KB + kb + u) * 64];
+            }
+            return g;
+        };
+        auto mul_group = [&](const Group& g) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
                 for (int ms = 0; ms < MS; ++ms) {
                     if (ms < mbs) {
-                        uint4 a = xw[((int64_t)ms * KB + kb + u) * 64];
 #pragma unroll
                         for (int ns = 0; ns < NS; ++ns)
-                            acc[ms][ns] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(bw[u][ns]),
+                            acc[ms][ns] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(g.x[u][ms]), as_bf16x8(g.w[u][ns]),
                                                                                    acc[ms][ns], 0, 0, 0);
                     }
                 }
+        };
+        int kb = kb_lo;
+        const int n_groups = (kb_hi - kb_lo) >> 2;
+        if (n_groups > 0) {
+            Group cur = load_group(kb);
+            for (int gi = 1; gi < n_groups; ++gi) {
+                Group nxt = load_group(kb + 4);
+                mul_group(cur);
+                cur = nxt;
+                kb += 4;
             }
+            mul_group(cur);
+            kb += 4;
         }
         for (; kb < kb_hi; ++kb) {
 #pragma unroll
