@@ -147,30 +147,48 @@ def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
             if rc != 0:
                 raise ee.EEError(rc, lib.ee_last_error().decode())
 
-    # warmup from the start state, then rewind and time exactly `steps` steps
+    def read_classes():
+        out = {}
+        for k, name in enumerate(ee.KERNEL_CLASSES):
+            n, ms = C.c_int(), C.c_float()
+            lib.ee_timing_read(k, C.byref(n), C.byref(ms))
+            out[name] = dict(launches=n.value, total_ms=round(ms.value, 3))
+        return out
+
+    # warmup from the start state, then rewind and time exactly `steps` steps.  Event pairs
+    # cost stream time, so the timed region brackets only the two kernels that can be the
+    # dominant one (their launch durations feed the roofline); the table of all kernel
+    # classes comes from a second, untimed pass over the same steps.
+    heavy = (1 << ee.KERNEL_CLASSES.index("attention")) | (1 << ee.KERNEL_CLASSES.index("gemm_gate_up"))
     batch.reset(tok0, ctx.astype(np.int32), None)
     run(args.warmup, 0)
     torch.cuda.synchronize()
     batch.reset(tok0, ctx.astype(np.int32), None)
     lib.ee_timing_reset()
-    lib.ee_timing_enable(1)
+    lib.ee_timing_enable(heavy)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run(args.steps, 0)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     lib.ee_timing_enable(0)
+    timed_kern = read_classes()
 
     f = batch.field
     assert int(f("status").cpu()[0]) == 0, "device status flag set"
     counts = f("exit_counts").cpu().numpy()[:len(s.resident_exits)].astype(np.int64)
     tokens = s.batch * args.steps
     assert counts.sum() == tokens, (counts, tokens)
-    kern = {}
-    for k, name in enumerate(ee.KERNEL_CLASSES):
-        n, ms = C.c_int(), C.c_float()
-        lib.ee_timing_read(k, C.byref(n), C.byref(ms))
-        kern[name] = dict(launches=n.value, total_ms=round(ms.value, 3))
+
+    batch.reset(tok0, ctx.astype(np.int32), None)
+    lib.ee_timing_reset()
+    lib.ee_timing_enable((1 << len(ee.KERNEL_CLASSES)) - 1)
+    run(args.steps, 0)
+    torch.cuda.synchronize()
+    lib.ee_timing_enable(0)
+    kern = read_classes()
+    for name in ("attention", "gemm_gate_up"):
+        kern[name] = timed_kern[name]            # the durations measured inside the timed region
 
     # rows that ran each layer, from the exit histogram (average per step)
     exits = s.resident_exits

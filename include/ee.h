@@ -149,11 +149,15 @@ int ee_model_resident_depth(const ee_model* m);
  * and the rows are laid out back to back: with T_b = capacity[0]+..+capacity[b-1]
  * and T the sum over all rows, the block of (layer l, row b, kv-head g) starts at
  * element  ((l-1)*T + T_b) * 2*H_kv*hd + g * 2*capacity[b]*hd  and holds
- *   K: capacity[b] x hd, position-major  K[p][i]
+ *   K: EE_F32 : capacity[b] x hd, position-major  K[p][i]
+ *      EE_BF16: blocks of 16 positions; inside block q the key of position p = 16 q + r,
+ *               feature i sits at (((q*4 + i/32) * 4 + (i%32)/8) * 16 + r) * 8 + i%8
  *   V: EE_F32 : capacity[b] x hd, position-major, right after K
  *      EE_BF16: right after K, in groups of 32 positions; inside group q the value
  *               of position p = 32 q + r, feature i sits at
- *               ((q*4 + (r%16)/4) * hd + i) * 8 + (r/16)*4 + r%4
+ *               (((q*(hd/16) + i/16) * 4 + (r%16)/4) * 16 + i%16) * 8 + (r/16)*4 + r%4
+ *   (both bf16 orders are the operand orders of the attention MFMAs; use
+ *   ee_kv_write_context / ee_kv_read_context to convert from and to plain position-major data)
  * ee_kv_pool_bytes gives the size for R resident layers.  host_capacity is a
  * host array [B]; the library keeps a device copy. */
 size_t ee_kv_pool_bytes(const ee_model* m, int n_resident_layers, const int32_t* host_capacity, int B);
@@ -272,12 +276,14 @@ typedef enum {
     EE_K_COUNT = 12
 } ee_kernel_class;
 
-/* With timing on, every launch of a kernel class is bracketed by a pair of HIP
- * events recorded on the launch stream (this creates events: not for code under
- * graph capture).  ee_timing_read waits for the recorded events, returns the
- * number of launches and their summed duration in milliseconds, and keeps
- * accumulating until ee_timing_reset. */
-int ee_timing_enable(int on);
+/* class_mask: bit k set = every launch of kernel class k is bracketed by a pair of
+ * HIP events recorded on the launch stream (this creates events: not for code
+ * under graph capture); 0 = off, (1 << EE_K_COUNT) - 1 = all classes.  An event
+ * pair costs a few microseconds of stream time, so time few classes when the
+ * whole step is being measured as well.  ee_timing_read waits for the recorded
+ * events, returns the number of launches and their summed duration in
+ * milliseconds, and keeps accumulating until ee_timing_reset. */
+int ee_timing_enable(int class_mask);
 int ee_timing_reset(void);
 int ee_timing_read(int kernel_class, int* launches, float* total_ms);
 

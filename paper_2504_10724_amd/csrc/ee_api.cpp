@@ -17,7 +17,7 @@ int ee_fail(int code, const std::string& msg) {
 static hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 // ------------------------------------------------------------------ kernel timing
-bool g_ee_timing_on = false;
+unsigned g_ee_timing_mask = 0;
 namespace {
 struct TimingPair { int kind; hipEvent_t a, b; bool closed; };
 std::vector<TimingPair> g_pairs;
@@ -73,8 +73,8 @@ int ee_device_count(void) {
     return n;
 }
 
-int ee_timing_enable(int on) {
-    g_ee_timing_on = on != 0;
+int ee_timing_enable(int class_mask) {
+    g_ee_timing_mask = (unsigned)class_mask & ((1u << EE_K_COUNT) - 1u);
     return EE_OK;
 }
 
@@ -367,6 +367,7 @@ static void lay_workspace(const ee_model* m, int B, WsLayout* W) {
         size_t pairs = Mpad * (size_t)c.n_kv_heads;   // position shares only when there are few pairs
         W->attn_part_bytes = pairs < 512 + 32 * (size_t)c.n_kv_heads ? pairs * 16 * 16 * 130 * 4 : 0;
         W->attn_part = take(W->attn_part_bytes);
+        W->attn_order = take(Mpad * 4);
     } else {
         size_t wide = (size_t)c.vocab > 2 * (size_t)c.d_ffn ? (size_t)c.vocab : 2 * (size_t)c.d_ffn;
         W->x = take(Mpad * c.d_model * 4);
@@ -384,6 +385,7 @@ static void lay_workspace(const ee_model* m, int B, WsLayout* W) {
         W->gemm_part_bytes = 0; W->gemm_part = take(0);
         W->gemm_cnt_ints = 0;   W->gemm_cnt = take(0);
         W->attn_part_bytes = 0; W->attn_part = take(0);
+        W->attn_order = take(0);
     }
     W->total = o;
 }

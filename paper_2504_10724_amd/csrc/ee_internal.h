@@ -46,6 +46,7 @@ struct WsLayout {
     size_t x, qkv, q_hi, q_lo, ao, act, part_max, part_sum, part_arg, logits, fill_x, fill_kv, total;
     size_t gemm_part, gemm_part_bytes, gemm_cnt, gemm_cnt_ints;   // K-slice partial planes
     size_t attn_part, attn_part_bytes;                            // attention position shares
+    size_t attn_order;                                            // int32 [Mpad]: list entries, longest context first
 };
 
 struct ee_batch {
@@ -74,14 +75,14 @@ int  ee_fail(int code, const std::string& msg);
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ----------------------------------------------------------------- kernel timing (opt-in)
-// When enabled, every launch of a kernel class is bracketed by a pair of HIP
-// events on the launch stream; ee_timing_read adds up the elapsed times.
+// Every launch of a kernel class whose bit is set in the mask is bracketed by a pair of
+// HIP events on the launch stream; ee_timing_read adds up the elapsed times.
 void ee_timing_mark(int kind, hipStream_t s, bool begin);
-extern bool g_ee_timing_on;
+extern unsigned g_ee_timing_mask;
 struct TimedScope {
-    int kind; hipStream_t s;
-    TimedScope(int k, hipStream_t st) : kind(k), s(st) { if (g_ee_timing_on) ee_timing_mark(kind, s, true); }
-    ~TimedScope() { if (g_ee_timing_on) ee_timing_mark(kind, s, false); }
+    int kind; hipStream_t s; bool on;
+    TimedScope(int k, hipStream_t st) : kind(k), s(st), on((g_ee_timing_mask >> k) & 1u) { if (on) ee_timing_mark(kind, s, true); }
+    ~TimedScope() { if (on) ee_timing_mark(kind, s, false); }
 };
 
 // Per-(layer,row,head) addressing of the key/value pool, passed by value to kernels.

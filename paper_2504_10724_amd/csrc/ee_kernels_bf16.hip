@@ -617,7 +617,8 @@ __global__ void __launch_bounds__(256)
 k_bf16_rope_append(const float* __restrict__ buf, int ld, int n_q, const int32_t* __restrict__ idx,
                    const int32_t* __restrict__ n_ptr, int B, const int32_t* __restrict__ pos,
                    const float* __restrict__ rope, int max_pos, KvView kv, bf16_t* __restrict__ q_hi,
-                   bf16_t* __restrict__ q_lo, int32_t* __restrict__ status, int64_t z_stride) {
+                   bf16_t* __restrict__ q_lo, int32_t* __restrict__ status, int64_t z_stride,
+                   int32_t* __restrict__ order) {
     int i = blockIdx.x;
     int n = min(*n_ptr, B);
     if (i >= n) return;
@@ -625,6 +626,19 @@ k_bf16_rope_append(const float* __restrict__ buf, int ld, int n_q, const int32_t
     kv.layer0 += blockIdx.z;
     int b = idx[i];
     int p = pos[b];
+    if (order != nullptr && threadIdx.x < 64) {
+        // launch order of the attention workgroups: list entries by falling context length (ties by
+        // entry), so that the longest rows start first and the last wave of workgroups is short.
+        // rank of this entry = how many entries come before it; the ranks form a permutation.
+        int before = 0;
+        for (int j = threadIdx.x; j < n; j += 64) {
+            int pj = pos[idx[j]];
+            before += (pj > p || (pj == p && j < i)) ? 1 : 0;
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) before += __shfl_xor(before, o, 64);
+        if (threadIdx.x == 0) order[before] = i;
+    }
     const int hd = 128, half = 64;
     int Hkv = kv.n_kv_heads;
     int cap = kv.cap[b];
@@ -652,8 +666,8 @@ k_bf16_rope_append(const float* __restrict__ buf, int ld, int n_q, const int32_t
         float c = cs[2 * j], s = cs[2 * j + 1];
         float a = kin[g * hd + j], bb = kin[g * hd + j + half];
         bf16_t* base = reinterpret_cast<bf16_t*>(kv.pool) + kv_block(kv, b, g, cap);
-        base[(int64_t)p * hd + j] = f32_to_bf16(a * c - bb * s);
-        base[(int64_t)p * hd + j + half] = f32_to_bf16(bb * c + a * s);
+        base[k_bf16_offset(p, j)] = f32_to_bf16(a * c - bb * s);
+        base[k_bf16_offset(p, j + half)] = f32_to_bf16(bb * c + a * s);
     }
     for (int t = threadIdx.x; t < Hkv * hd; t += 256) {
         int g = t >> 7, j = t & 127;
@@ -677,13 +691,14 @@ __global__ void __launch_bounds__(256)
 k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, int Hq,
             const int32_t* __restrict__ idx, const int32_t* __restrict__ n_ptr, int B,
             const int32_t* __restrict__ pos, KvView kv, uint4* __restrict__ ao, int KB_ao, int n_splits,
-            float* __restrict__ part) {
+            float* __restrict__ part, const int32_t* __restrict__ order) {
     __shared__ float sm_m[4][16];
     __shared__ float sm_l[4][16];
     __shared__ float sm_o[4][16][128];
-    const int g = blockIdx.x, i = blockIdx.y;
+    const int g = blockIdx.x;
     const int n = min(*n_ptr, B);
-    if (i >= n) return;
+    if ((int)blockIdx.y >= n) return;
+    const int i = order[blockIdx.y];       // longest contexts first
     const int b = idx[i];
     const int cap = kv.cap[b];
     const int n_pos = max(1, min(pos[b] + 1, cap));
@@ -714,15 +729,34 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
     // with n_splits > 1 this workgroup covers the blockIdx.z-th share of the position groups
     const int g_lo = (int)(((int64_t)n_groups * blockIdx.z) / n_splits);
     const int g_hi = (int)(((int64_t)n_groups * (blockIdx.z + 1)) / n_splits);
-    for (int t = g_lo + w; t < g_hi; t += 4) {
-        const int p0 = t << 5;
-        floatx4 S0 = {0.f, 0.f, 0.f, 0.f}, S1 = {0.f, 0.f, 0.f, 0.f};
-        const bf16_t* k0 = Kb + (int64_t)(p0 + n16) * 128 + 8 * gq;
-        const bf16_t* k1 = k0 + 16 * 128;
+    // K and V tiles of one 32-position group as this lane holds them for the MFMAs; the next
+    // group of the wave is in flight while the current one is processed
+    struct KVTiles { uint4 k[2][4]; uint4 v[8]; };
+    auto load_kv = [&](int t) -> KVTiles {
+        KVTiles x;
+        // K: two blocks of 16 positions; slice c of a block is 1 KiB, lane l takes bytes 16 l ..
+        const bf16_t* k0 = Kb + (int64_t)(2 * t) * 2048 + lane * 8;
+        const bf16_t* k1 = k0 + 2048;
+        const bf16_t* vg = Vb + (int64_t)t * 4096 + lane * 8;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            bf16x8 a0 = as_bf16x8(*reinterpret_cast<const uint4*>(k0 + 32 * c));
-            bf16x8 a1 = as_bf16x8(*reinterpret_cast<const uint4*>(k1 + 32 * c));
+            x.k[0][c] = *reinterpret_cast<const uint4*>(k0 + 512 * c);
+            x.k[1][c] = *reinterpret_cast<const uint4*>(k1 + 512 * c);
+        }
+#pragma unroll
+        for (int hb = 0; hb < 8; ++hb) x.v[hb] = *reinterpret_cast<const uint4*>(vg + hb * 512);
+        return x;
+    };
+    KVTiles cur;
+    if (g_lo + w < g_hi) cur = load_kv(g_lo + w);
+    for (int t = g_lo + w; t < g_hi; t += 4) {
+        const int p0 = t << 5;
+        KVTiles nxt = load_kv(min(t + 4, g_hi - 1));      // past the end: a harmless re-read
+        floatx4 S0 = {0.f, 0.f, 0.f, 0.f}, S1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            bf16x8 a0 = as_bf16x8(cur.k[0][c]);
+            bf16x8 a1 = as_bf16x8(cur.k[1][c]);
             S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qh[c], S0, 0, 0, 0);
             S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, ql[c], S0, 0, 0, 0);
             S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qh[c], S1, 0, 0, 0);
@@ -760,10 +794,9 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
                             lo[4] | ((uint32_t)lo[5] << 16), lo[6] | ((uint32_t)lo[7] << 16));
         }
         const bool partial = p0 + 32 > n_pos;
-        const bf16_t* vg = Vb + ((int64_t)(t * 4 + gq) * 128 + n16) * 8;
 #pragma unroll
         for (int hb = 0; hb < 8; ++hb) {
-            uint4 vv = *reinterpret_cast<const uint4*>(vg + (int64_t)hb * 16 * 8);
+            uint4 vv = cur.v[hb];
             if (partial) {
                 // element j of the chunk is position p0 + 4 gq + j (j < 4) or p0 + 16 + 4 gq + j - 4
                 uint32_t* vw = reinterpret_cast<uint32_t*>(&vv);
@@ -777,6 +810,7 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
             O[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), as_bf16x8(ph), O[hb], 0, 0, 0);
             O[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), as_bf16x8(pl), O[hb], 0, 0, 0);
         }
+        cur = nxt;
     }
     // O[hb][r]: feature 16 hb + 4 gq + r of head n16 (unnormalised), this wave's positions
     l_run += __shfl_xor(l_run, 16, 64);
@@ -964,7 +998,8 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
         TimedScope t(EE_K_ROPE_APPEND, s);
         hipLaunchKernelGGL(k_bf16_rope_append, dim3(B), dim3(256), 0, s, qkv, qkv_n, c.n_q_heads, idx, n_ptr, B,
                            b->st<int32_t>(L.pos), m->d_rope, c.max_pos, view, b->wsp<bf16_t>(b->W.q_hi),
-                           b->wsp<bf16_t>(b->W.q_lo), b->st<int32_t>(L.status), (int64_t)0);
+                           b->wsp<bf16_t>(b->W.q_lo), b->st<int32_t>(L.status), (int64_t)0,
+                           b->wsp<int32_t>(b->W.attn_order));
     }
     {
         TimedScope t(EE_K_ATTENTION, s);
@@ -975,7 +1010,7 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
         while (n_splits > 1 && (size_t)b->Mpad * c.n_kv_heads * n_splits * 16 * 130 * 4 > b->W.attn_part_bytes) --n_splits;
         hipLaunchKernelGGL(k_bf16_attn, dim3(c.n_kv_heads, B, n_splits), dim3(256), 0, s, b->wsp<bf16_t>(b->W.q_hi),
                            b->wsp<bf16_t>(b->W.q_lo), c.n_q_heads, idx, n_ptr, B, b->st<int32_t>(L.pos), view, ao,
-                           qd / 16, n_splits, b->wsp<float>(b->W.attn_part));
+                           qd / 16, n_splits, b->wsp<float>(b->W.attn_part), b->wsp<int32_t>(b->W.attn_order));
         if (n_splits > 1)
             hipLaunchKernelGGL(k_bf16_attn_merge, dim3(c.n_kv_heads, B), dim3(256), 0, s, b->wsp<float>(b->W.attn_part),
                                c.n_q_heads, c.n_kv_heads, n_splits, n_ptr, B, ao, qd / 16);
@@ -1059,7 +1094,8 @@ int bf16_fill_kv(const ee_model* m, int from_excl, int to_incl, ee_kv* kv, ee_ba
         gemm<1, EPI_STORE>(x, nullptr, kv_n, d, NBs, nb_off, n_ptr, B, ep, s, zb, nl);
     hipLaunchKernelGGL(k_bf16_rope_append, dim3(B, 1, nl), dim3(256), 0, s, kvb, kv_n, 0, idx, n_ptr, B,
                        b->st<int32_t>(L.pos), m->d_rope, c.max_pos, make_view(m, kv, from_excl + 1),
-                       (bf16_t*)nullptr, (bf16_t*)nullptr, b->st<int32_t>(L.status), zb.out_stride);
+                       (bf16_t*)nullptr, (bf16_t*)nullptr, b->st<int32_t>(L.status), zb.out_stride,
+                       (int32_t*)nullptr);
     EE_LAUNCH_CHECK();
     return EE_OK;
 }
