@@ -537,11 +537,27 @@ int ee_decode_step(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_
     void* s = stream;
     rc = ee_batch_begin_step(m, b, s);
     int next_exit = 0;
+    // bf16: the kernel that finishes a layer can leave the normalised operand of whatever comes
+    // next (the exit head, or the next layer when no compaction lies between): one launch less
+    bool x_ready = false;
     for (int l = 1; l <= R && rc == EE_OK; ++l) {
-        rc = ee_layer_forward(m, l, kv, b, s);
-        if (rc != EE_OK || c.exit_layers[next_exit] != l) continue;
+        const bool exit_here = c.exit_layers[next_exit] == l;
+        if (c.dtype == EE_BF16) {
+            const float* tail_gain = exit_here ? (const float*)m->exits[next_exit].gain
+                                               : (const float*)m->layers[l].g_attn;   // l < R here
+            bool x_done = false;
+            rc = bf16_layer_forward(m, l, kv, b, as_stream(s), x_ready, tail_gain, &x_done);
+            x_ready = x_done;
+        } else {
+            rc = ee_layer_forward(m, l, kv, b, s);
+        }
+        if (rc != EE_OK || !exit_here) continue;
         int e = next_exit++;
-        rc = ee_exit_head(m, e, host_thresholds[e], l == R, b, nullptr, s);
+        if (c.dtype == EE_BF16)
+            rc = bf16_exit_head(m, e, host_thresholds[e], l == R ? 1 : 0, b, nullptr, as_stream(s), x_ready);
+        else
+            rc = ee_exit_head(m, e, host_thresholds[e], l == R, b, nullptr, s);
+        x_ready = false;                                     // the compaction renumbers the list entries
         if (rc == EE_OK) rc = ee_compact_active(b, e, l, s);
         if (rc == EE_OK) rc = ee_fill_skipped_kv(m, l, R, kv, b, s);
     }

@@ -116,6 +116,8 @@ int f32_exit_head(const ee_model* m, int e, float th, int force, ee_batch* b, fl
 int f32_fill_kv(const ee_model* m, int from_excl, int to_incl, ee_kv* kv, ee_batch* b, hipStream_t s);
 
 // bf16 path (ee_kernels_bf16.hip)
-int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hipStream_t s);
-int bf16_exit_head(const ee_model* m, int e, float th, int force, ee_batch* b, float* dbg, hipStream_t s);
+int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hipStream_t s, bool x_ready = false,
+                       const float* tail_gain = nullptr, bool* x_done = nullptr);
+int bf16_exit_head(const ee_model* m, int e, float th, int force, ee_batch* b, float* dbg, hipStream_t s,
+                   bool x_ready = false);
 int bf16_fill_kv(const ee_model* m, int from_excl, int to_incl, ee_kv* kv, ee_batch* b, hipStream_t s);

@@ -40,17 +40,12 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
 }
 
 // ------------------------------------------------------------------ RMSNorm -> A tiles
-// one block per list entry i; out is the [Mpad][d] activation matrix in tile order
-__global__ void __launch_bounds__(256)
-k_bf16_rmsnorm(const float* __restrict__ h, const int32_t* __restrict__ idx, const int32_t* __restrict__ n_ptr,
-               int B, const float* __restrict__ gain, float eps, int d, uint4* __restrict__ out, ZBatch zb) {
-    __shared__ float red[4];
-    int i = blockIdx.x;
-    int n = min(*n_ptr, B);
-    if (i >= n) return;
-    if (zb.g_tab) gain = zb.g_tab[zb.z0 + blockIdx.z];
-    out += (int64_t)blockIdx.z * zb.x_stride;
-    const float4* hr = reinterpret_cast<const float4*>(h + (int64_t)idx[i] * d);
+// The 256 threads of a block normalise one row (hr: d floats) and write it as list entry i of
+// the [Mpad][d] activation matrix in tile order.  Every thread reads only the 8-float chunks
+// c = threadIdx.x + 256 j, so a caller may have written those same chunks just before.
+__device__ __forceinline__ void rmsnorm_row(const float* hr_, const float* gain, float eps, int d, uint4* out, int i,
+                                            float* red) {
+    const float4* hr = reinterpret_cast<const float4*>(hr_);
     const float4* g4 = reinterpret_cast<const float4*>(gain);
     int n8 = d >> 3;
     float ss = 0.f;
@@ -71,6 +66,19 @@ k_bf16_rmsnorm(const float* __restrict__ h, const int32_t* __restrict__ idx, con
         o.w = pack2((b.z * inv) * gb.z, (b.w * inv) * gb.w);
         out[afrag_chunk(i, c * 8, KB)] = o;
     }
+}
+
+// one block per list entry i; out is the [Mpad][d] activation matrix in tile order
+__global__ void __launch_bounds__(256)
+k_bf16_rmsnorm(const float* __restrict__ h, const int32_t* __restrict__ idx, const int32_t* __restrict__ n_ptr,
+               int B, const float* __restrict__ gain, float eps, int d, uint4* __restrict__ out, ZBatch zb) {
+    __shared__ float red[4];
+    int i = blockIdx.x;
+    int n = min(*n_ptr, B);
+    if (i >= n) return;
+    if (zb.g_tab) gain = zb.g_tab[zb.z0 + blockIdx.z];
+    out += (int64_t)blockIdx.z * zb.x_stride;
+    rmsnorm_row(h + (int64_t)idx[i] * d, gain, eps, d, out, i, red);
 }
 
 // ------------------------------------------------------------------ weight-streaming MFMA GEMM
@@ -618,7 +626,7 @@ k_bf16_rope_append(const float* __restrict__ buf, int ld, int n_q, const int32_t
                    const int32_t* __restrict__ n_ptr, int B, const int32_t* __restrict__ pos,
                    const float* __restrict__ rope, int max_pos, KvView kv, bf16_t* __restrict__ q_hi,
                    bf16_t* __restrict__ q_lo, int32_t* __restrict__ status, int64_t z_stride,
-                   int32_t* __restrict__ order) {
+                   int32_t* __restrict__ order, int splits, int64_t plane) {
     int i = blockIdx.x;
     int n = min(*n_ptr, B);
     if (i >= n) return;
@@ -626,7 +634,7 @@ k_bf16_rope_append(const float* __restrict__ buf, int ld, int n_q, const int32_t
     kv.layer0 += blockIdx.z;
     int b = idx[i];
     int p = pos[b];
-    if (order != nullptr && threadIdx.x < 64) {
+    if (order != nullptr && blockIdx.y == 0 && threadIdx.x < 64) {
         // launch order of the attention workgroups: list entries by falling context length (ties by
         // entry), so that the longest rows start first and the last wave of workgroups is short.
         // rank of this entry = how many entries come before it; the ranks form a permutation.
@@ -646,12 +654,22 @@ k_bf16_rope_append(const float* __restrict__ buf, int ld, int n_q, const int32_t
         if (threadIdx.x == 0) atomicOr(status, 1);
         return;
     }
-    const float* r = buf + (int64_t)i * ld;
+    // buf holds `splits` K-slice planes of the product (plane floats apart): their sum in slice
+    // order is the value; splits = 1 is a finished matrix
+    const float* r0 = buf + (int64_t)i * ld;
+    auto rd = [&](int x) -> float {
+        float v = r0[x];
+        for (int q = 1; q < splits; ++q) v += r0[x + (int64_t)q * plane];
+        return v;
+    };
     const float* cs = rope + (int64_t)p * half * 2;
-    for (int t = threadIdx.x; t < n_q * half; t += 256) {
+    // the work of a row is dealt out over the gridDim.y blocks that share it
+    const int t0 = blockIdx.y * 256 + threadIdx.x, tstep = 256 * gridDim.y;
+#pragma unroll 4
+    for (int t = t0; t < n_q * half; t += tstep) {
         int hh = t >> 6, j = t & 63;
         float c = cs[2 * j], s = cs[2 * j + 1];
-        float a = r[hh * hd + j], bb = r[hh * hd + j + half];
+        float a = rd(hh * hd + j), bb = rd(hh * hd + j + half);
         float x0 = a * c - bb * s, x1 = bb * c + a * s;
         bf16_t h0 = f32_to_bf16(x0), h1 = f32_to_bf16(x1);
         int64_t o = ((int64_t)i * n_q + hh) * hd + j;
@@ -659,20 +677,20 @@ k_bf16_rope_append(const float* __restrict__ buf, int ld, int n_q, const int32_t
         q_lo[o] = f32_to_bf16(x0 - bf16_to_f32(h0));
         q_lo[o + half] = f32_to_bf16(x1 - bf16_to_f32(h1));
     }
-    const float* kin = r + n_q * hd;
-    const float* vin = kin + Hkv * hd;
-    for (int t = threadIdx.x; t < Hkv * half; t += 256) {
+    const int kin = n_q * hd;
+    const int vin = kin + Hkv * hd;
+    for (int t = t0; t < Hkv * half; t += tstep) {
         int g = t >> 6, j = t & 63;
         float c = cs[2 * j], s = cs[2 * j + 1];
-        float a = kin[g * hd + j], bb = kin[g * hd + j + half];
+        float a = rd(kin + g * hd + j), bb = rd(kin + g * hd + j + half);
         bf16_t* base = reinterpret_cast<bf16_t*>(kv.pool) + kv_block(kv, b, g, cap);
         base[k_bf16_offset(p, j)] = f32_to_bf16(a * c - bb * s);
         base[k_bf16_offset(p, j + half)] = f32_to_bf16(bb * c + a * s);
     }
-    for (int t = threadIdx.x; t < Hkv * hd; t += 256) {
+    for (int t = t0; t < Hkv * hd; t += tstep) {
         int g = t >> 7, j = t & 127;
         bf16_t* base = reinterpret_cast<bf16_t*>(kv.pool) + kv_block(kv, b, g, cap);
-        base[(int64_t)cap * hd + v_bf16_offset(p, j, hd)] = f32_to_bf16(vin[g * hd + j]);
+        base[(int64_t)cap * hd + v_bf16_offset(p, j, hd)] = f32_to_bf16(rd(vin + g * hd + j));
     }
 }
 
@@ -687,7 +705,7 @@ k_bf16_rope_append(const float* __restrict__ buf, int ld, int n_q, const int32_t
 // The result registers of the score MFMAs are, lane for lane, the P operand
 // of the value MFMAs (the grouped V layout is chosen to make that so).
 // q and P enter as bf16 (hi, lo) pairs: two MFMAs each, fp32-grade products.
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 3)
 k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, int Hq,
             const int32_t* __restrict__ idx, const int32_t* __restrict__ n_ptr, int B,
             const int32_t* __restrict__ pos, KvView kv, uint4* __restrict__ ao, int KB_ao, int n_splits,
@@ -729,8 +747,8 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
     // with n_splits > 1 this workgroup covers the blockIdx.z-th share of the position groups
     const int g_lo = (int)(((int64_t)n_groups * blockIdx.z) / n_splits);
     const int g_hi = (int)(((int64_t)n_groups * (blockIdx.z + 1)) / n_splits);
-    // K and V tiles of one 32-position group as this lane holds them for the MFMAs; the next
-    // group of the wave is in flight while the current one is processed
+    // K and V tiles of one 32-position group as this lane holds them for the MFMAs.  Three
+    // workgroups share a CU: while one wave waits for its group the others compute.
     struct KVTiles { uint4 k[2][4]; uint4 v[8]; };
     auto load_kv = [&](int t) -> KVTiles {
         KVTiles x;
@@ -747,11 +765,9 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
         for (int hb = 0; hb < 8; ++hb) x.v[hb] = *reinterpret_cast<const uint4*>(vg + hb * 512);
         return x;
     };
-    KVTiles cur;
-    if (g_lo + w < g_hi) cur = load_kv(g_lo + w);
     for (int t = g_lo + w; t < g_hi; t += 4) {
         const int p0 = t << 5;
-        KVTiles nxt = load_kv(min(t + 4, g_hi - 1));      // past the end: a harmless re-read
+        const KVTiles cur = load_kv(t);
         floatx4 S0 = {0.f, 0.f, 0.f, 0.f}, S1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -810,7 +826,6 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
             O[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), as_bf16x8(ph), O[hb], 0, 0, 0);
             O[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), as_bf16x8(pl), O[hb], 0, 0, 0);
         }
-        cur = nxt;
     }
     // O[hb][r]: feature 16 hb + 4 gq + r of head n16 (unnormalised), this wave's positions
     l_run += __shfl_xor(l_run, 16, 64);
@@ -930,12 +945,76 @@ k_splitk_finish(const float* __restrict__ partial, int64_t plane, int ld, int sp
     }
 }
 
+// Residual finish of a K-sliced product, one block per list entry: h[row id] += sum of the
+// slice planes (in slice order, as k_splitk_finish does), and, if a gain is given, the RMSNorm
+// of the updated row straight into the operand matrix of the next product.
+__global__ void __launch_bounds__(256)
+k_splitk_resid_norm(const float* __restrict__ partial, int64_t plane, int ld, int splits, int N,
+                    const int32_t* __restrict__ n_ptr, int B, float* h, int ldh, const int32_t* __restrict__ idx,
+                    const float* gain, float eps, uint4* xout) {
+    __shared__ float red[4];
+    const int n = min(*n_ptr, B);
+    const int i = blockIdx.x;
+    if (i >= n) return;
+    float* hrow = h + (int64_t)idx[i] * ldh;
+    const float* prow = partial + (int64_t)i * ld;
+    // four 8-float chunks per thread and pass: the loads of one plane are all in flight together
+    for (int c0 = threadIdx.x; c0 < (N >> 3); c0 += 1024) {
+        float4 sum[4][2];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = min(c0 + 256 * j, (N >> 3) - 1);
+            sum[j][0] = *reinterpret_cast<const float4*>(prow + c * 8);
+            sum[j][1] = *reinterpret_cast<const float4*>(prow + c * 8 + 4);
+        }
+        for (int q = 1; q < splits; ++q) {
+            float4 v[4][2];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int c = min(c0 + 256 * j, (N >> 3) - 1);
+                v[j][0] = *reinterpret_cast<const float4*>(prow + (int64_t)q * plane + c * 8);
+                v[j][1] = *reinterpret_cast<const float4*>(prow + (int64_t)q * plane + c * 8 + 4);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    sum[j][u].x += v[j][u].x; sum[j][u].y += v[j][u].y; sum[j][u].z += v[j][u].z; sum[j][u].w += v[j][u].w;
+                }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = c0 + 256 * j;
+            if (c < (N >> 3)) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    float4* hp = reinterpret_cast<float4*>(hrow + c * 8 + u * 4);
+                    float4 o = *hp;
+                    o.x += sum[j][u].x; o.y += sum[j][u].y; o.z += sum[j][u].z; o.w += sum[j][u].w;
+                    *hp = o;
+                }
+            }
+        }
+    }
+    if (gain != nullptr) rmsnorm_row(hrow, gain, eps, N, xout, i, red);   // reads back this thread's own chunks
+}
+
+// what the caller wants done with the K-slice planes of a product
+struct SliceTail {
+    const float* norm_gain = nullptr;   // RESID: also normalise the updated rows with this gain ...
+    float        eps = 0.f;
+    uint4*       norm_out = nullptr;    // ... into this operand matrix
+    bool*        norm_done = nullptr;   // set when that happened
+    bool         defer_store = false;   // STORE: leave the planes to the caller ...
+    int*         splits_out = nullptr;  // ... who gets their number (1 = the result is in out already)
+};
+
 // batches above 64 rows: the 256-row tile kernel, 128 or 256 columns wide, K sliced so that about
 // one workgroup per CU runs
 template <int EPI>
 static bool gemm_big(const ee_batch* b, const void* X, const void* W, int N, int K, int NBs, int nb_off,
                      const int32_t* n_ptr, int B, const EpiArgs& ep, hipStream_t s, const ZBatch& zb = ZBatch{},
-                     int nz = 1) {
+                     int nz = 1, const SliceTail& tail = SliceTail{}) {
     if (B <= 64 || N % 128 != 0 || K % 128 != 0) return false;
     int row_groups = (B + 255) / 256;
     int Mpad = (B + 31) / 32 * 32;
@@ -960,15 +1039,26 @@ static bool gemm_big(const ee_batch* b, const void* X, const void* W, int N, int
         hipLaunchKernelGGL((k_bf16_gemm_big<EPI, 2>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
                            K / 16, NBs, nb_off, n_tiles, splits, n_ptr, B, b->wsp<float>(b->W.gemm_part),
                            (int64_t)Mpad * N, N, ep, zb);
+    if (tail.splits_out) *tail.splits_out = splits;
     if (splits > 1) {
-        constexpr int FIN = (EPI == EPI_RESID) ? EPI_RESID : EPI_STORE;
-        hipLaunchKernelGGL((k_splitk_finish<FIN>), dim3((N / 4 + 255) / 256, B), dim3(256), 0, s,
-                           b->wsp<float>(b->W.gemm_part), (int64_t)Mpad * N, N, splits, N, n_ptr, B, ep);
+        if (EPI == EPI_RESID) {
+            hipLaunchKernelGGL(k_splitk_resid_norm, dim3(B), dim3(256), 0, s, b->wsp<float>(b->W.gemm_part),
+                               (int64_t)Mpad * N, N, splits, N, n_ptr, B, ep.out, ep.ldo, ep.idx, tail.norm_gain,
+                               tail.eps, tail.norm_out);
+            if (tail.norm_gain && tail.norm_done) *tail.norm_done = true;
+        } else if (!tail.defer_store) {
+            hipLaunchKernelGGL((k_splitk_finish<EPI_STORE>), dim3((N / 4 + 255) / 256, B), dim3(256), 0, s,
+                               b->wsp<float>(b->W.gemm_part), (int64_t)Mpad * N, N, splits, N, n_ptr, B, ep);
+        }
     }
     return true;
 }
 
-int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hipStream_t s) {
+// x_ready: the operand matrix already holds RMSNorm(h; attention gain of this layer).
+// tail_gain (with x_done): if the last product of the layer is finished from K-slice planes, that
+// kernel also leaves RMSNorm(h; tail_gain) in the operand matrix and sets *x_done.
+int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hipStream_t s, bool x_ready,
+                       const float* tail_gain, bool* x_done) {
     const ee_model_config& c = m->cfg;
     const ee_layer_weights& w = m->layers[layer - 1];
     const ee_batch_layout& L = b->L;
@@ -983,23 +1073,27 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
     bf16_t* act = b->wsp<bf16_t>(b->W.act);
     KvView view = make_view(m, kv, layer);
 
-    {
+    if (!x_ready) {
         TimedScope t(EE_K_NORM, s);
         hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, h, idx, n_ptr, B, w.g_attn, c.rms_eps, d, x, ZBatch{});
     }
     EpiArgs e1{};
     e1.out = qkv; e1.ldo = qkv_n; e1.idx = idx;
+    int qkv_splits = 1;
     {
         TimedScope t(EE_K_GEMM_QKV, s);
-        if (!gemm_big<EPI_STORE>(b, x, w.w_qkv, qkv_n, d, qkv_n / 32, 0, n_ptr, B, e1, s))
+        SliceTail st;                  // K-slice planes of q|k|v are added up by the RoPE kernel
+        st.defer_store = true; st.splits_out = &qkv_splits;
+        if (!gemm_big<EPI_STORE>(b, x, w.w_qkv, qkv_n, d, qkv_n / 32, 0, n_ptr, B, e1, s, ZBatch{}, 1, st))
             gemm<1, EPI_STORE>(x, w.w_qkv, qkv_n, d, qkv_n / 32, 0, n_ptr, B, e1, s);
     }
     {
         TimedScope t(EE_K_ROPE_APPEND, s);
-        hipLaunchKernelGGL(k_bf16_rope_append, dim3(B), dim3(256), 0, s, qkv, qkv_n, c.n_q_heads, idx, n_ptr, B,
+        const float* src = qkv_splits > 1 ? b->wsp<float>(b->W.gemm_part) : qkv;
+        hipLaunchKernelGGL(k_bf16_rope_append, dim3(B, 4), dim3(256), 0, s, src, qkv_n, c.n_q_heads, idx, n_ptr, B,
                            b->st<int32_t>(L.pos), m->d_rope, c.max_pos, view, b->wsp<bf16_t>(b->W.q_hi),
                            b->wsp<bf16_t>(b->W.q_lo), b->st<int32_t>(L.status), (int64_t)0,
-                           b->wsp<int32_t>(b->W.attn_order));
+                           b->wsp<int32_t>(b->W.attn_order), qkv_splits, (int64_t)b->Mpad * qkv_n);
     }
     {
         TimedScope t(EE_K_ATTENTION, s);
@@ -1017,12 +1111,15 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
     }
     EpiArgs e2{};
     e2.out = h; e2.ldo = d; e2.idx = idx;
+    bool ffn_x_done = false;
     {
         TimedScope t(EE_K_GEMM_O, s);
-        if (!gemm_big<EPI_RESID>(b, ao, w.w_o, d, qd, d / 32, 0, n_ptr, B, e2, s))
+        SliceTail st;                  // the finish of a sliced product also normalises for the FFN
+        st.norm_gain = w.g_ffn; st.eps = c.rms_eps; st.norm_out = x; st.norm_done = &ffn_x_done;
+        if (!gemm_big<EPI_RESID>(b, ao, w.w_o, d, qd, d / 32, 0, n_ptr, B, e2, s, ZBatch{}, 1, st))
             gemm<1, EPI_RESID>(ao, w.w_o, d, qd, d / 32, 0, n_ptr, B, e2, s);
     }
-    {
+    if (!ffn_x_done) {
         TimedScope t(EE_K_NORM, s);
         hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, h, idx, n_ptr, B, w.g_ffn, c.rms_eps, d, x, ZBatch{});
     }
@@ -1035,21 +1132,24 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
     }
     {
         TimedScope t(EE_K_GEMM_DOWN, s);
-        if (!gemm_big<EPI_RESID>(b, act, w.w_down, d, F, d / 32, 0, n_ptr, B, e2, s))
+        SliceTail st;
+        st.norm_gain = tail_gain; st.eps = c.rms_eps; st.norm_out = x; st.norm_done = x_done;
+        if (!gemm_big<EPI_RESID>(b, act, w.w_down, d, F, d / 32, 0, n_ptr, B, e2, s, ZBatch{}, 1, st))
             gemm<1, EPI_RESID>(act, w.w_down, d, F, d / 32, 0, n_ptr, B, e2, s);
     }
     EE_LAUNCH_CHECK();
     return EE_OK;
 }
 
-int bf16_exit_head(const ee_model* m, int e, float th, int force, ee_batch* b, float* dbg, hipStream_t s) {
+int bf16_exit_head(const ee_model* m, int e, float th, int force, ee_batch* b, float* dbg, hipStream_t s,
+                   bool x_ready) {
     const ee_model_config& c = m->cfg;
     const ee_batch_layout& L = b->L;
     int B = b->B, d = c.d_model, V = c.vocab;
     const int32_t* idx = b->st<int32_t>(L.active_idx);
     const int32_t* n_ptr = b->st<int32_t>(L.n_active);
     uint4* x = b->wsp<uint4>(b->W.x);
-    {
+    if (!x_ready) {
         TimedScope t(EE_K_NORM, s);
         hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, b->st<float>(L.h), idx, n_ptr, B,
                            m->exits[e].gain, c.rms_eps, d, x, ZBatch{});
@@ -1095,7 +1195,7 @@ int bf16_fill_kv(const ee_model* m, int from_excl, int to_incl, ee_kv* kv, ee_ba
     hipLaunchKernelGGL(k_bf16_rope_append, dim3(B, 1, nl), dim3(256), 0, s, kvb, kv_n, 0, idx, n_ptr, B,
                        b->st<int32_t>(L.pos), m->d_rope, c.max_pos, make_view(m, kv, from_excl + 1),
                        (bf16_t*)nullptr, (bf16_t*)nullptr, b->st<int32_t>(L.status), zb.out_stride,
-                       (int32_t*)nullptr);
+                       (int32_t*)nullptr, 1, (int64_t)0);
     EE_LAUNCH_CHECK();
     return EE_OK;
 }

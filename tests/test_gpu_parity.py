@@ -208,6 +208,37 @@ def test_two_runs_are_bitwise_identical():
             assert np.array_equal(K1, K2) and np.array_equal(V1, V2)
 
 
+@pytest.mark.parametrize("s", [MID, BIG_M], ids=lambda s: s.name)
+def test_step_equals_its_calls_one_by_one(s):
+    """ee_decode_step and the same sequence of the per-call entry points give the same bits:
+    the step may hand a normalised operand from one kernel to the next, the calls may not."""
+    s = s.with_(steps=1)
+    _say(f"[case] step_vs_calls {s.name}")
+    o, g1 = _fresh(s, jitter=0.1)
+    g2 = GpuSide(s, weights=o.weights)
+    sc = synth.row_scale(s, 0)
+    r1 = g1.step(0, scale=sc)
+    g2.batch.set_row_scale(sc)
+    g2.batch.begin_step()
+    e = 0
+    for l in range(1, s.resident + 1):
+        assert S.layer_forward(g2.model, l, g2.kv, g2.batch) == 0
+        if l in s.exit_layers:
+            assert S.exit_head(g2.model, e, float(s.thresholds[e]), l == s.resident, g2.batch) == 0
+            assert S.compact_active(g2.batch, e, l) == 0
+            assert S.fill_skipped_kv(g2.model, l, s.resident, g2.kv, g2.batch) == 0
+            e += 1
+    torch.cuda.synchronize()
+    f1, f2 = g1.batch.field, g2.batch.field
+    for k in ("out_tok", "out_layer", "out_conf", "out_breach", "h"):
+        assert torch.equal(f1(k), f2(k)), k
+    for b in (0, s.batch // 2, s.batch - 1):
+        for l in (1, s.resident):
+            K1, V1 = g1.kv.read_context(l, b, int(g1.ctx[b]) + 1)
+            K2, V2 = g2.kv.read_context(l, b, int(g2.ctx[b]) + 1)
+            assert np.array_equal(K1, K2) and np.array_equal(V1, V2)
+
+
 # ---------------------------------------------------------------- error paths through the C ABI
 def test_error_codes():
     s = PARTIAL
