@@ -339,6 +339,12 @@ __device__ __forceinline__ void epilogue_tile(const EpiArgs& ep, const floatx16&
     }
 }
 
+// The last loads of the peeled group feed only the loop; the compiler would sink them behind
+// the loop's entry test, after the W loads of the same stage, and the order of the loads in
+// flight at the loop head would again differ between its two predecessors.  A use after the
+// loop keeps them where they are written.
+#define KEEP_LOADS_IN_PLACE(A, B) \
+    asm volatile("" ::"v"((A).a.x), "v"((A).b.x), "v"((A).c.x), "v"((A).d.x), "v"((B).a.x), "v"((B).b.x), "v"((B).c.x), "v"((B).d.x));
 template <int NS> struct WFrag { uint4 v[2][NS]; };   // W tiles of one stage: [K half][column tile]
 
 template <int EPI, int NS>
@@ -433,37 +439,65 @@ k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
         o.v[i + 1] = xl[buf][(4 * wm + i + 1) * 2 + kk][lane];
     };
 #define SB __builtin_amdgcn_sched_barrier(0);
+    // one load (NS / 2 for the W quarters) behind each MFMA group, not all eight in one burst
+    auto ldx = [&](int t, int j) -> uint4 {
+        const int kb0 = 2 * (ks_lo + min(t, T - 1));
+        const int m = min(2 * wave + (j >> 1), mbs - 1);
+        return xg[((int64_t)m * KB + kb0 + (j & 1)) * 64];
+    };
+    auto ldw_quarter = [&](WFrag<NS>& q, int t, int part) {
+        const int kb0 = 2 * (ks_lo + min(t, T - 1));
+#pragma unroll
+        for (int e = 0; e < NS / 2; ++e) {
+            const int f = part * (NS / 2) + e, kk = f / NS, ns = f % NS;
+            q.v[kk][ns] = wg[((int64_t)(kb0 + kk) * NBs + ns) * 64];
+        }
+    };
 #define BIG_STEP(MF, U, XNEW, BNEW, BCUR, XOUT)                                               \
-    MF(a0, BCUR, 0, 0); SB read_a2(a1, (t0 + (U)) % 3, 1, 0); SB                              \
-    MF(a0, BCUR, 0, 1); SB read_a2(a1, (t0 + (U)) % 3, 1, 2); SB                              \
-    MF(a0, BCUR, 0, 2); SB                                                                    \
-    MF(a0, BCUR, 0, 3); SB                                                                    \
-    MF(a1, BCUR, 1, 0); SB read_a2(a0, (t0 + (U) + 1) % 3, 0, 0); SB                          \
-    MF(a1, BCUR, 1, 1); SB read_a2(a0, (t0 + (U) + 1) % 3, 0, 2); SB                          \
-    MF(a1, BCUR, 1, 2); SB store_x01((t0 + (U) + 2) % 3, XOUT); store_x23((t0 + (U) + 2) % 3, XOUT); SB \
-    MF(a1, BCUR, 1, 3); SB XNEW = load_x(t0 + (U) + 3); BNEW = load_w(t0 + (U) + 3); SB       \
+    MF(a0, BCUR, 0, 0); SB XNEW.a = ldx(t0 + (U) + 3, 0); read_a2(a1, (t0 + (U)) % 3, 1, 0); SB \
+    MF(a0, BCUR, 0, 1); SB XNEW.b = ldx(t0 + (U) + 3, 1); read_a2(a1, (t0 + (U)) % 3, 1, 2); SB \
+    MF(a0, BCUR, 0, 2); SB XNEW.c = ldx(t0 + (U) + 3, 2); SB                                  \
+    MF(a0, BCUR, 0, 3); SB XNEW.d = ldx(t0 + (U) + 3, 3); SB                                  \
+    MF(a1, BCUR, 1, 0); SB ldw_quarter(BNEW, t0 + (U) + 3, 0); read_a2(a0, (t0 + (U) + 1) % 3, 0, 0); SB \
+    MF(a1, BCUR, 1, 1); SB ldw_quarter(BNEW, t0 + (U) + 3, 1); read_a2(a0, (t0 + (U) + 1) % 3, 0, 2); SB \
+    MF(a1, BCUR, 1, 2); SB ldw_quarter(BNEW, t0 + (U) + 3, 2); store_x01((t0 + (U) + 2) % 3, XOUT); store_x23((t0 + (U) + 2) % 3, XOUT); SB \
+    MF(a1, BCUR, 1, 3); SB ldw_quarter(BNEW, t0 + (U) + 3, 3); SB                             \
     lds_barrier();
     // step t stores X(t+2) from xr(t % 2) and loads X(t+3) into the other set, which held X(t+1)
     // and was written to LDS during step t-1; W(t+3) replaces W(t-1), consumed during step t-1.
-#define BIG_LOOP(MF)                                 \
-    for (int t0 = 0; t0 < T; t0 += 4) {              \
+    // The first group of four stages runs outside the loop: the loads in flight at the loop head
+    // are then the same, in the same order, whether control comes from it or from the loop's end.
+    // (With the prologue as the other predecessor the compiler's wait counts of the first stage
+    // are the prologue's, and they drain every load in flight once per group.)
+#define BIG_GROUP(MF)                                \
         BIG_STEP(MF, 0, xr1, br3, br0, xr0)          \
         BIG_STEP(MF, 1, xr0, br0, br1, xr1)          \
         BIG_STEP(MF, 2, xr1, br1, br2, xr0)          \
-        BIG_STEP(MF, 3, xr0, br2, br3, xr1)          \
-    }
+        BIG_STEP(MF, 3, xr0, br2, br3, xr1)
+#define BIG_LOOP(MF)                                 \
+    { const int t0 = 0; BIG_GROUP(MF) }              \
+    for (int t0 = 4; t0 < T; t0 += 4) { BIG_GROUP(MF) }
 
     xr0 = load_x(0); br0 = load_w(0);
     xr1 = load_x(1); br1 = load_w(1);
     store_x01(0, xr0); store_x23(0, xr0);
     store_x01(1, xr1); store_x23(1, xr1);
-    xr0 = load_x(2); br2 = load_w(2);
-    br3 = br2;
+    // the loads in flight at loop entry must be the ones (and in the order) every later pass
+    // through the loop head has: otherwise the wait counts of the first stage are the entry's,
+    // and they drain the pipeline once per unrolled group
+    __builtin_amdgcn_sched_barrier(0);
+    xr0 = load_x(2);
+    __builtin_amdgcn_sched_barrier(0);
+    br2 = load_w(2);
+    __builtin_amdgcn_sched_barrier(0);
+    br3 = WFrag<NS>{};
     lds_barrier();
     a1 = Half{};
     read_a2(a0, 0, 0, 0); read_a2(a0, 0, 0, 2);
     if (cnt == 4) { BIG_LOOP(mf) } else { BIG_LOOP(mf_some) }
+    KEEP_LOADS_IN_PLACE(xr0, xr1)
 #undef BIG_LOOP
+#undef BIG_GROUP
 #undef BIG_STEP
 #undef SB
 
@@ -572,32 +606,50 @@ k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
         o.v[i + 1] = xl[buf][(i + 1) * 2 + kk][lane];
     };
 #define SB __builtin_amdgcn_sched_barrier(0);
+    // one global load after each group of four MFMAs: issued in one burst, the eight loads of a
+    // stage (times four waves) queue up in the vector-memory path and hold the wave at the issue
+    auto ldx = [&](int t, int j) -> uint4 {
+        const int kb0 = 2 * (ks_lo + min(t, T - 1));
+        const int m = min(2 * wave + (j >> 1), mbs - 1);
+        return xg[((int64_t)m * KB + kb0 + (j & 1)) * 64];
+    };
+    auto ldw = [&](int t, int kk, int ns) -> uint4 {
+        const int kb0 = 2 * (ks_lo + min(t, T - 1));
+        return wg[((int64_t)(kb0 + kk) * NBs + ns) * 64];
+    };
 #define WIDE_STEP(U, XNEW, BNEW, BCUR, XOUT)                                                  \
-    mf(a0, BCUR, 0, 0); SB read_a2(a1, (t0 + (U)) % 3, 1, 0); read_a2(a1, (t0 + (U)) % 3, 1, 2); SB         \
-    mf(a0, BCUR, 0, 2); SB read_a2(a1, (t0 + (U)) % 3, 1, 4); read_a2(a1, (t0 + (U)) % 3, 1, 6); SB         \
-    mf(a0, BCUR, 0, 4); SB                                                                    \
-    mf(a0, BCUR, 0, 6); SB                                                                    \
-    mf(a1, BCUR, 1, 0); SB read_a2(a0, (t0 + (U) + 1) % 3, 0, 0); read_a2(a0, (t0 + (U) + 1) % 3, 0, 2); SB \
-    mf(a1, BCUR, 1, 2); SB read_a2(a0, (t0 + (U) + 1) % 3, 0, 4); read_a2(a0, (t0 + (U) + 1) % 3, 0, 6); SB \
-    mf(a1, BCUR, 1, 4); SB store_x((t0 + (U) + 2) % 3, XOUT); SB                              \
-    mf(a1, BCUR, 1, 6); SB XNEW = load_x(t0 + (U) + 3); BNEW = load_w(t0 + (U) + 3); SB       \
+    mf(a0, BCUR, 0, 0); SB XNEW.a = ldx(t0 + (U) + 3, 0); read_a2(a1, (t0 + (U)) % 3, 1, 0); read_a2(a1, (t0 + (U)) % 3, 1, 2); SB \
+    mf(a0, BCUR, 0, 2); SB XNEW.b = ldx(t0 + (U) + 3, 1); read_a2(a1, (t0 + (U)) % 3, 1, 4); read_a2(a1, (t0 + (U)) % 3, 1, 6); SB \
+    mf(a0, BCUR, 0, 4); SB XNEW.c = ldx(t0 + (U) + 3, 2); SB                                  \
+    mf(a0, BCUR, 0, 6); SB XNEW.d = ldx(t0 + (U) + 3, 3); SB                                  \
+    mf(a1, BCUR, 1, 0); SB BNEW.v[0][0] = ldw(t0 + (U) + 3, 0, 0); read_a2(a0, (t0 + (U) + 1) % 3, 0, 0); read_a2(a0, (t0 + (U) + 1) % 3, 0, 2); SB \
+    mf(a1, BCUR, 1, 2); SB BNEW.v[0][1] = ldw(t0 + (U) + 3, 0, 1); read_a2(a0, (t0 + (U) + 1) % 3, 0, 4); read_a2(a0, (t0 + (U) + 1) % 3, 0, 6); SB \
+    mf(a1, BCUR, 1, 4); SB BNEW.v[1][0] = ldw(t0 + (U) + 3, 1, 0); store_x((t0 + (U) + 2) % 3, XOUT); SB \
+    mf(a1, BCUR, 1, 6); SB BNEW.v[1][1] = ldw(t0 + (U) + 3, 1, 1); SB                         \
     lds_barrier();
 
     xr0 = load_x(0); br0 = load_w(0);
     xr1 = load_x(1); br1 = load_w(1);
     store_x(0, xr0);
     store_x(1, xr1);
-    xr0 = load_x(2); br2 = load_w(2);
-    br3 = br2;
+    __builtin_amdgcn_sched_barrier(0);   // same loads in flight, in the same order, as at every later loop head
+    xr0 = load_x(2);
+    __builtin_amdgcn_sched_barrier(0);
+    br2 = load_w(2);
+    __builtin_amdgcn_sched_barrier(0);
+    br3 = WFrag<2>{};
     lds_barrier();
     a1 = Oct{};
     read_a2(a0, 0, 0, 0); read_a2(a0, 0, 0, 2); read_a2(a0, 0, 0, 4); read_a2(a0, 0, 0, 6);
-    for (int t0 = 0; t0 < T; t0 += 4) {
-        WIDE_STEP(0, xr1, br3, br0, xr0)
-        WIDE_STEP(1, xr0, br0, br1, xr1)
-        WIDE_STEP(2, xr1, br1, br2, xr0)
-        WIDE_STEP(3, xr0, br2, br3, xr1)
-    }
+#define WIDE_GROUP                       \
+    WIDE_STEP(0, xr1, br3, br0, xr0)     \
+    WIDE_STEP(1, xr0, br0, br1, xr1)     \
+    WIDE_STEP(2, xr1, br1, br2, xr0)     \
+    WIDE_STEP(3, xr0, br2, br3, xr1)
+    { const int t0 = 0; WIDE_GROUP }     // first group outside the loop, as in k_bf16_gemm_big
+    for (int t0 = 4; t0 < T; t0 += 4) { WIDE_GROUP }
+    KEEP_LOADS_IN_PLACE(xr0, xr1)
+#undef WIDE_GROUP
 #undef WIDE_STEP
 #undef SB
 #define EPI_ROW(E, ARGS, I) \
