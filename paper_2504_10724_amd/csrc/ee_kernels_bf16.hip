@@ -370,8 +370,11 @@ k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
     const int KS4 = KB >> 3;                                 // groups of four 32-wide K steps
     const int ks_lo = 4 * (int)(((int64_t)KS4 * sp) / splits), ks_hi = 4 * (int)(((int64_t)KS4 * (sp + 1)) / splits);
     const int T = ks_hi - ks_lo;                             // K steps of this slice: a positive multiple of 4
-    const uint4* xg = Xp + ((int64_t)rg * 8 * KB) * 64 + lane;
-    const uint4* wg = Wp + (int64_t)(nb_off + nbw) * 64 + lane;   // tile (r, c) sits at slot c * NBs + r
+    // uniform bases; the lane index is added last, so that the loads take a scalar base and a
+    // 32-bit vector offset
+    const uint4* xg = Xp + ((int64_t)rg * 8 * KB) * 64;
+    const uint4* wg = Wp + (int64_t)(nb_off + nbw) * 64;           // tile (r, c) sits at slot c * NBs + r
+    const unsigned ul = (unsigned)lane;
 
     floatx16 acc[4][NS];
 #pragma unroll
@@ -401,10 +404,10 @@ k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
         // dead row tiles re-read a live one: no branch, nothing out of range
         const int m0 = min(2 * wave, mbs - 1), m1 = min(2 * wave + 1, mbs - 1);
         Quad q;
-        q.a = xg[((int64_t)m0 * KB + kb0) * 64];
-        q.b = xg[((int64_t)m0 * KB + kb0 + 1) * 64];
-        q.c = xg[((int64_t)m1 * KB + kb0) * 64];
-        q.d = xg[((int64_t)m1 * KB + kb0 + 1) * 64];
+        q.a = (xg + ((int64_t)m0 * KB + kb0) * 64)[ul];
+        q.b = (xg + ((int64_t)m0 * KB + kb0 + 1) * 64)[ul];
+        q.c = (xg + ((int64_t)m1 * KB + kb0) * 64)[ul];
+        q.d = (xg + ((int64_t)m1 * KB + kb0 + 1) * 64)[ul];
         return q;
     };
     auto load_w = [&](int t) -> WFrag<NS> {
@@ -413,7 +416,7 @@ k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-            for (int ns = 0; ns < NS; ++ns) q.v[kk][ns] = wg[((int64_t)(kb0 + kk) * NBs + ns) * 64];
+            for (int ns = 0; ns < NS; ++ns) q.v[kk][ns] = (wg + ((int64_t)(kb0 + kk) * NBs + ns) * 64)[ul];
         return q;
     };
     auto store_x01 = [&](int buf, const Quad& q) {
@@ -443,14 +446,14 @@ k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
     auto ldx = [&](int t, int j) -> uint4 {
         const int kb0 = 2 * (ks_lo + min(t, T - 1));
         const int m = min(2 * wave + (j >> 1), mbs - 1);
-        return xg[((int64_t)m * KB + kb0 + (j & 1)) * 64];
+        return (xg + ((int64_t)m * KB + kb0 + (j & 1)) * 64)[ul];
     };
     auto ldw_quarter = [&](WFrag<NS>& q, int t, int part) {
         const int kb0 = 2 * (ks_lo + min(t, T - 1));
 #pragma unroll
         for (int e = 0; e < NS / 2; ++e) {
             const int f = part * (NS / 2) + e, kk = f / NS, ns = f % NS;
-            q.v[kk][ns] = wg[((int64_t)(kb0 + kk) * NBs + ns) * 64];
+            q.v[kk][ns] = (wg + ((int64_t)(kb0 + kk) * NBs + ns) * 64)[ul];
         }
     };
 #define BIG_STEP(MF, U, XNEW, BNEW, BCUR, XOUT)                                               \
@@ -551,8 +554,9 @@ k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
     const int KS4 = KB >> 3;                                 // groups of four 32-wide K steps
     const int ks_lo = 4 * (int)(((int64_t)KS4 * sp) / splits), ks_hi = 4 * (int)(((int64_t)KS4 * (sp + 1)) / splits);
     const int T = ks_hi - ks_lo;                             // K steps of this slice: a positive multiple of 4
-    const uint4* xg = Xp + ((int64_t)rg * 8 * KB) * 64 + lane;
-    const uint4* wg = Wp + (int64_t)(nb_off + nbw) * 64 + lane;
+    const uint4* xg = Xp + ((int64_t)rg * 8 * KB) * 64;            // uniform bases, lane added last
+    const uint4* wg = Wp + (int64_t)(nb_off + nbw) * 64;
+    const unsigned ul = (unsigned)lane;
 
     floatx16 acc[8][2];
 #pragma unroll
@@ -569,10 +573,10 @@ k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
         const int kb0 = 2 * (ks_lo + min(t, T - 1));
         const int m0 = min(2 * wave, mbs - 1), m1 = min(2 * wave + 1, mbs - 1);
         Quad q;
-        q.a = xg[((int64_t)m0 * KB + kb0) * 64];
-        q.b = xg[((int64_t)m0 * KB + kb0 + 1) * 64];
-        q.c = xg[((int64_t)m1 * KB + kb0) * 64];
-        q.d = xg[((int64_t)m1 * KB + kb0 + 1) * 64];
+        q.a = (xg + ((int64_t)m0 * KB + kb0) * 64)[ul];
+        q.b = (xg + ((int64_t)m0 * KB + kb0 + 1) * 64)[ul];
+        q.c = (xg + ((int64_t)m1 * KB + kb0) * 64)[ul];
+        q.d = (xg + ((int64_t)m1 * KB + kb0 + 1) * 64)[ul];
         return q;
     };
     auto load_w = [&](int t) -> WFrag<2> {
@@ -581,7 +585,7 @@ k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-            for (int ns = 0; ns < 2; ++ns) q.v[kk][ns] = wg[((int64_t)(kb0 + kk) * NBs + ns) * 64];
+            for (int ns = 0; ns < 2; ++ns) q.v[kk][ns] = (wg + ((int64_t)(kb0 + kk) * NBs + ns) * 64)[ul];
         return q;
     };
     auto store_x = [&](int buf, const Quad& q) {
@@ -590,10 +594,13 @@ k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
         xl[buf][4 * wave + 2][lane] = q.c;
         xl[buf][4 * wave + 3][lane] = q.d;
     };
-    auto mf = [&](const Oct& a, const WFrag<2>& bw, int kk, int i) {   // 4 MFMAs: row tiles i, i+1
+    // 4 MFMAs: row tiles i, i+1; MBS = number of live row tiles, a compile-time constant of the
+    // loop instance, so that the steady state carries no branch and no mask arithmetic
+    auto mf_n = [&](auto mbs_c, const Oct& a, const WFrag<2>& bw, int kk, int i) {
+        constexpr int MBS = decltype(mbs_c)::value;
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
-            if (i + r < mbs) {
+            if (i + r < MBS) {
                 acc[i + r][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[i + r]), as_bf16x8(bw.v[kk][0]),
                                                                         acc[i + r][0], 0, 0, 0);
                 acc[i + r][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[i + r]), as_bf16x8(bw.v[kk][1]),
@@ -611,11 +618,11 @@ k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
     auto ldx = [&](int t, int j) -> uint4 {
         const int kb0 = 2 * (ks_lo + min(t, T - 1));
         const int m = min(2 * wave + (j >> 1), mbs - 1);
-        return xg[((int64_t)m * KB + kb0 + (j & 1)) * 64];
+        return (xg + ((int64_t)m * KB + kb0 + (j & 1)) * 64)[ul];
     };
     auto ldw = [&](int t, int kk, int ns) -> uint4 {
         const int kb0 = 2 * (ks_lo + min(t, T - 1));
-        return wg[((int64_t)(kb0 + kk) * NBs + ns) * 64];
+        return (wg + ((int64_t)(kb0 + kk) * NBs + ns) * 64)[ul];
     };
 #define WIDE_STEP(U, XNEW, BNEW, BCUR, XOUT)                                                  \
     mf(a0, BCUR, 0, 0); SB XNEW.a = ldx(t0 + (U) + 3, 0); read_a2(a1, (t0 + (U)) % 3, 1, 0); read_a2(a1, (t0 + (U)) % 3, 1, 2); SB \
@@ -646,8 +653,18 @@ k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
     WIDE_STEP(1, xr0, br0, br1, xr1)     \
     WIDE_STEP(2, xr1, br1, br2, xr0)     \
     WIDE_STEP(3, xr0, br2, br3, xr1)
-    { const int t0 = 0; WIDE_GROUP }     // first group outside the loop, as in k_bf16_gemm_big
-    for (int t0 = 4; t0 < T; t0 += 4) { WIDE_GROUP }
+#define WIDE_LOOP(N)                                                                          \
+    case N: {                                                                                 \
+        auto mf = [&](const Oct& a, const WFrag<2>& bw, int kk, int i) {                      \
+            mf_n(std::integral_constant<int, N>{}, a, bw, kk, i);                             \
+        };                                                                                    \
+        { const int t0 = 0; WIDE_GROUP }  /* first group outside the loop, as in k_bf16_gemm_big */ \
+        for (int t0 = 4; t0 < T; t0 += 4) { WIDE_GROUP }                                      \
+    } break;
+    switch (mbs) {
+        WIDE_LOOP(1) WIDE_LOOP(2) WIDE_LOOP(3) WIDE_LOOP(4) WIDE_LOOP(5) WIDE_LOOP(6) WIDE_LOOP(7) WIDE_LOOP(8)
+    }
+#undef WIDE_LOOP
     KEEP_LOADS_IN_PLACE(xr0, xr1)
 #undef WIDE_GROUP
 #undef WIDE_STEP
