@@ -661,10 +661,56 @@ k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
         { const int t0 = 0; WIDE_GROUP }  /* first group outside the loop, as in k_bf16_gemm_big */ \
         for (int t0 = 4; t0 < T; t0 += 4) { WIDE_GROUP }                                      \
     } break;
+    // At most four live row tiles: a stage has so few MFMAs that LDS reads issued half a stage
+    // ahead arrive late.  Half of each operand register set is idle then, so the A operands of
+    // stage t+1 (both K halves) are read at the top of stage t into the half that stage t does
+    // not use (set = stage parity): a whole stage of lead.
+    auto rd_low = [&](auto mbs_c, Oct& o, int set, int buf, int kk) {
+        constexpr int MBS = decltype(mbs_c)::value;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (i < MBS) o.v[4 * set + i] = xl[buf][i * 2 + kk][lane];
+    };
+    auto mf_low = [&](auto mbs_c, const Oct& a, const WFrag<2>& bw, int kk, int set, int i) {
+        constexpr int MBS = decltype(mbs_c)::value;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            if (i + r < MBS) {
+                acc[i + r][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[4 * set + i + r]),
+                                                                        as_bf16x8(bw.v[kk][0]), acc[i + r][0], 0, 0, 0);
+                acc[i + r][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[4 * set + i + r]),
+                                                                        as_bf16x8(bw.v[kk][1]), acc[i + r][1], 0, 0, 0);
+            }
+        }
+    };
+#define LOW_STEP(U, XNEW, BNEW, BCUR, XOUT)                                                   \
+    rd_low(MC, a0, ((U) + 1) & 1, (t0 + (U) + 1) % 3, 0); rd_low(MC, a1, ((U) + 1) & 1, (t0 + (U) + 1) % 3, 1); SB \
+    mf_low(MC, a0, BCUR, 0, (U) & 1, 0); SB XNEW.a = ldx(t0 + (U) + 3, 0); XNEW.b = ldx(t0 + (U) + 3, 1); SB \
+    mf_low(MC, a0, BCUR, 0, (U) & 1, 2); SB XNEW.c = ldx(t0 + (U) + 3, 2); XNEW.d = ldx(t0 + (U) + 3, 3); SB \
+    mf_low(MC, a1, BCUR, 1, (U) & 1, 0); SB BNEW.v[0][0] = ldw(t0 + (U) + 3, 0, 0); BNEW.v[0][1] = ldw(t0 + (U) + 3, 0, 1); \
+                                            store_x((t0 + (U) + 2) % 3, XOUT); SB             \
+    mf_low(MC, a1, BCUR, 1, (U) & 1, 2); SB BNEW.v[1][0] = ldw(t0 + (U) + 3, 1, 0); BNEW.v[1][1] = ldw(t0 + (U) + 3, 1, 1); SB \
+    lds_barrier();
+#define LOW_GROUP                       \
+    LOW_STEP(0, xr1, br3, br0, xr0)     \
+    LOW_STEP(1, xr0, br0, br1, xr1)     \
+    LOW_STEP(2, xr1, br1, br2, xr0)     \
+    LOW_STEP(3, xr0, br2, br3, xr1)
+#define WIDE_LOOP_LOW(N)                                                                      \
+    case N: {                                                                                 \
+        const std::integral_constant<int, N> MC{};                                            \
+        rd_low(MC, a1, 0, 0, 1);   /* stage 0, second K half (the first is in a0 already) */  \
+        { const int t0 = 0; LOW_GROUP }                                                       \
+        for (int t0 = 4; t0 < T; t0 += 4) { LOW_GROUP }                                       \
+    } break;
     switch (mbs) {
-        WIDE_LOOP(1) WIDE_LOOP(2) WIDE_LOOP(3) WIDE_LOOP(4) WIDE_LOOP(5) WIDE_LOOP(6) WIDE_LOOP(7) WIDE_LOOP(8)
+        WIDE_LOOP_LOW(1) WIDE_LOOP_LOW(2) WIDE_LOOP_LOW(3) WIDE_LOOP_LOW(4)
+        WIDE_LOOP(5) WIDE_LOOP(6) WIDE_LOOP(7) WIDE_LOOP(8)
     }
 #undef WIDE_LOOP
+#undef WIDE_LOOP_LOW
+#undef LOW_GROUP
+#undef LOW_STEP
     KEEP_LOADS_IN_PLACE(xr0, xr1)
 #undef WIDE_GROUP
 #undef WIDE_STEP
@@ -672,6 +718,152 @@ k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
 #define EPI_ROW(E, ARGS, I) \
     if ((I) < mbs) epilogue_tile<E>(ARGS, acc[I][0], acc[I][1], row_base + 32 * (I), n, nbw, lane);
     if (splits > 1) {   // K slices: fp32 partial planes, finished by k_splitk_finish
+        EpiArgs pe = ep;
+        pe.out = partial + (int64_t)sp * part_plane;
+        pe.ldo = part_ld;
+        EPI_ROW(EPI_STORE, pe, 0) EPI_ROW(EPI_STORE, pe, 1) EPI_ROW(EPI_STORE, pe, 2) EPI_ROW(EPI_STORE, pe, 3)
+        EPI_ROW(EPI_STORE, pe, 4) EPI_ROW(EPI_STORE, pe, 5) EPI_ROW(EPI_STORE, pe, 6) EPI_ROW(EPI_STORE, pe, 7)
+        return;
+    }
+    EPI_ROW(EPI, ep, 0) EPI_ROW(EPI, ep, 1) EPI_ROW(EPI, ep, 2) EPI_ROW(EPI, ep, 3)
+    EPI_ROW(EPI, ep, 4) EPI_ROW(EPI, ep, 5) EPI_ROW(EPI, ep, 6) EPI_ROW(EPI, ep, 7)
+#undef EPI_ROW
+}
+
+// ------------------------------------------------------------------ wide tile fed by LDS-DMA loads
+// Same tile and wave layout as k_bf16_gemm_wide, but no operand passes through registers on
+// its way in: every wave sends its four X tiles and its own four W tiles of a stage straight
+// from global memory into LDS (64 lanes x 16 B per instruction, lane l lands at byte 16 l of
+// the slot), and all MFMA operands are read from LDS.  A load that returns into registers
+// holds up the matrix pipe of its SIMD while it writes back (measured: streaming and MFMA
+// time add up); a load into LDS does not, so here the weight stream runs under the MFMAs.
+//   LDS: 4 stage buffers x 32 slots of 1 KiB: slots 0..15 X tile (row tile m, K half kk) at
+//        2 m + kk, slots 16..31 W tile (wave w, K half kk, column tile ns) at 16 + 4 w + 2 kk + ns
+//   stage t: MFMAs of stage t; LDS reads of its second K half, then of the first K half of
+//        stage t+1; the 8 loads of stage t+3 into the buffer stage t-1 used, one behind each
+//        MFMA group; at the end wait until only those 8 are in flight (stage t+2 has landed),
+//        then the barrier that makes stage t+2 readable by all waves.
+// The compiler does not see these loads, so it adds no wait of its own; the waits are here.
+struct BPair { uint4 v[2]; };   // W operands of one K half: 2 column tiles
+
+__device__ __forceinline__ void dma_tile(const uint4* tile, unsigned lane_bytes, unsigned lds_byte) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte), "v"(lane_bytes), "s"(tile)
+                 : "memory");
+}
+
+template <int EPI>
+__global__ void __launch_bounds__(BIG_THREADS, 1)
+k_bf16_gemm_dma(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int NBs, int nb_off,
+                int n_tiles, int splits, const int32_t* __restrict__ n_ptr, int B, float* __restrict__ partial,
+                int64_t part_plane, int part_ld, EpiArgs ep, ZBatch zb) {
+    __shared__ uint4 lds[4][32][64];
+    const int n = min(*n_ptr, B);
+    const int rg = blockIdx.y;
+    const int row_base = rg * 256;
+    if (row_base >= n) return;
+    if (zb.w_tab) Wp = reinterpret_cast<const uint4*>(zb.w_tab[zb.z0 + blockIdx.z]);
+    Xp += (int64_t)blockIdx.z * zb.x_stride;
+    ep.out += (int64_t)blockIdx.z * zb.out_stride;
+    const int mbs = min(8, (n - row_base + 31) >> 5);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tile = blockIdx.x / splits, sp = blockIdx.x % splits;
+    const int nbw = (tile * 4 + wave) * 2;                   // this wave's two tile-rows of W
+    const int KS4 = KB >> 3;                                 // groups of four 32-wide K stages
+    const int ks_lo = 4 * (int)(((int64_t)KS4 * sp) / splits), ks_hi = 4 * (int)(((int64_t)KS4 * (sp + 1)) / splits);
+    const int T = ks_hi - ks_lo;                             // stages of this slice: a positive multiple of 4
+    const uint4* xg = Xp + ((int64_t)rg * 8 * KB) * 64;      // uniform bases; the lane offset goes in a register
+    const uint4* wg = Wp + (int64_t)(nb_off + nbw) * 64;
+    const unsigned lane_bytes = (unsigned)lane * 16u;
+    const unsigned lds0 = (unsigned)(size_t)&lds[0][0][0];
+
+    floatx16 acc[8][2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // j-th load of stage t into buffer buf: j = 0..3 X tiles (row tile 2 wave + j/2, K half j%2),
+    // j = 4..7 W tiles (K half (j-4)/2, column tile (j-4)%2).  Stages past the end re-read the last.
+    auto issue = [&](int t, int buf, int j) {
+        const int kb0 = 2 * (ks_lo + min(t, T - 1));
+        if (j < 4) {
+            const int mt = 2 * wave + (j >> 1);
+            const int m = min(mt, mbs - 1);                  // a dead row tile re-reads a live one
+            dma_tile(xg + ((int64_t)m * KB + kb0 + (j & 1)) * 64, lane_bytes,
+                     lds0 + (unsigned)((buf * 32 + mt * 2 + (j & 1)) << 10));
+        } else {
+            const int kk = (j - 4) >> 1, ns = (j - 4) & 1;
+            dma_tile(wg + ((int64_t)(kb0 + kk) * NBs + ns) * 64, lane_bytes,
+                     lds0 + (unsigned)((buf * 32 + 16 + wave * 4 + kk * 2 + ns) << 10));
+        }
+    };
+    Oct a0, a1;
+    BPair b0, b1;
+    auto rd_a = [&](auto mbs_c, Oct& o, int buf, int kk, int i) {      // row tiles i, i+1
+        constexpr int MBS = decltype(mbs_c)::value;
+        if (i < MBS) o.v[i] = lds[buf][i * 2 + kk][lane];
+        if (i + 1 < MBS) o.v[i + 1] = lds[buf][(i + 1) * 2 + kk][lane];
+    };
+    auto rd_b = [&](BPair& o, int buf, int kk) {
+        o.v[0] = lds[buf][16 + wave * 4 + kk * 2][lane];
+        o.v[1] = lds[buf][16 + wave * 4 + kk * 2 + 1][lane];
+    };
+    auto mf_d = [&](auto mbs_c, const Oct& a, const BPair& bw, int i) {   // 4 MFMAs: row tiles i, i+1
+        constexpr int MBS = decltype(mbs_c)::value;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            if (i + r < MBS) {
+                acc[i + r][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[i + r]), as_bf16x8(bw.v[0]),
+                                                                        acc[i + r][0], 0, 0, 0);
+                acc[i + r][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[i + r]), as_bf16x8(bw.v[1]),
+                                                                        acc[i + r][1], 0, 0, 0);
+            }
+        }
+    };
+#define SB __builtin_amdgcn_sched_barrier(0);
+#define STAGE_END asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#define DMA_STAGE(U)                                                                          \
+    mf_d(MC, a0, b0, 0); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 0); rd_a(MC, a1, (U), 1, 0); rd_a(MC, a1, (U), 1, 2); rd_b(b1, (U), 1); SB \
+    mf_d(MC, a0, b0, 2); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 1); rd_a(MC, a1, (U), 1, 4); rd_a(MC, a1, (U), 1, 6); SB \
+    mf_d(MC, a0, b0, 4); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 2); SB                         \
+    mf_d(MC, a0, b0, 6); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 3); SB                         \
+    mf_d(MC, a1, b1, 0); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 4); rd_a(MC, a0, ((U) + 1) & 3, 0, 0); rd_a(MC, a0, ((U) + 1) & 3, 0, 2); rd_b(b0, ((U) + 1) & 3, 0); SB \
+    mf_d(MC, a1, b1, 2); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 5); rd_a(MC, a0, ((U) + 1) & 3, 0, 4); rd_a(MC, a0, ((U) + 1) & 3, 0, 6); SB \
+    mf_d(MC, a1, b1, 4); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 6); SB                         \
+    mf_d(MC, a1, b1, 6); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 7); SB                         \
+    STAGE_END
+#define DMA_LOOP(N)                                                                           \
+    case N: {                                                                                 \
+        const std::integral_constant<int, N> MC{};                                            \
+        rd_a(MC, a0, 0, 0, 0); rd_a(MC, a0, 0, 0, 2); rd_a(MC, a0, 0, 0, 4); rd_a(MC, a0, 0, 0, 6); \
+        for (int t0 = 0; t0 < T; t0 += 4) { DMA_STAGE(0) DMA_STAGE(1) DMA_STAGE(2) DMA_STAGE(3) } \
+    } break;
+
+    // stages 0, 1, 2 on their way; 0 and 1 must have landed before the first reads
+#pragma unroll
+    for (int j = 0; j < 8; ++j) issue(0, 0, j);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) issue(1, 1, j);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) issue(2, 2, j);
+    STAGE_END
+    a0 = Oct{}; a1 = Oct{};
+    rd_b(b0, 0, 0);
+    b1 = BPair{};
+    switch (mbs) {
+        DMA_LOOP(1) DMA_LOOP(2) DMA_LOOP(3) DMA_LOOP(4) DMA_LOOP(5) DMA_LOOP(6) DMA_LOOP(7) DMA_LOOP(8)
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the re-reads past the end have landed before the block ends
+#undef DMA_LOOP
+#undef DMA_STAGE
+#undef STAGE_END
+#undef SB
+#define EPI_ROW(E, ARGS, I) \
+    if ((I) < mbs) epilogue_tile<E>(ARGS, acc[I][0], acc[I][1], row_base + 32 * (I), n, nbw, lane);
+    if (splits > 1) {   // K slices: fp32 partial planes, finished by the caller's choice of kernel
         EpiArgs pe = ep;
         pe.out = partial + (int64_t)sp * part_plane;
         pe.ldo = part_ld;
@@ -1101,7 +1293,7 @@ static bool gemm_big(const ee_batch* b, const void* X, const void* W, int N, int
     }
     dim3 grid(n_tiles * splits, row_groups, nz);
     if (wide)
-        hipLaunchKernelGGL((k_bf16_gemm_wide<EPI>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
+        hipLaunchKernelGGL((k_bf16_gemm_dma<EPI>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
                            K / 16, NBs, nb_off, n_tiles, splits, n_ptr, B, b->wsp<float>(b->W.gemm_part),
                            (int64_t)Mpad * N, N, ep, zb);
     else
