@@ -746,8 +746,14 @@ k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
 // The compiler does not see these loads, so it adds no wait of its own; the waits are here.
 struct BPair { uint4 v[2]; };   // W operands of one K half: 2 column tiles
 
+// tile and lds_byte are the same in all lanes; going through readfirstlane makes that explicit, so
+// that both end up in scalar registers whatever the optimiser did to the address arithmetic
 __device__ __forceinline__ void dma_tile(const uint4* tile, unsigned lane_bytes, unsigned lds_byte) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte), "v"(lane_bytes), "s"(tile)
+    const uint64_t a = reinterpret_cast<uint64_t>(tile);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a), hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+    const uint64_t base = ((uint64_t)hi << 32) | lo;
+    const uint32_t slot = __builtin_amdgcn_readfirstlane(lds_byte);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(slot), "v"(lane_bytes), "s"(base)
                  : "memory");
 }
 
@@ -873,6 +879,122 @@ k_bf16_gemm_dma(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
     }
     EPI_ROW(EPI, ep, 0) EPI_ROW(EPI, ep, 1) EPI_ROW(EPI, ep, 2) EPI_ROW(EPI, ep, 3)
     EPI_ROW(EPI, ep, 4) EPI_ROW(EPI, ep, 5) EPI_ROW(EPI, ep, 6) EPI_ROW(EPI, ep, 7)
+#undef EPI_ROW
+}
+
+// ------------------------------------------------------------------ 128-column tile fed by LDS-DMA loads
+// The tile and wave layout of k_bf16_gemm_big (256 x 128, waves 2 x 2, each 128 rows x 64
+// columns) with the operand path of k_bf16_gemm_dma.  LDS: 4 stage buffers x 24 slots: X tile
+// (row tile m, K half kk) at 2 m + kk, W tile (column tile nb of the 4, K half kk) at
+// 16 + 2 nb + kk.  A wave sends 4 X tiles and 2 W tiles per stage and reads the 8 + 4 it needs.
+struct BHalf { uint4 v[2]; };
+
+template <int EPI>
+__global__ void __launch_bounds__(BIG_THREADS, 1)
+k_bf16_gemm_dma2(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int NBs, int nb_off,
+                 int n_tiles, int splits, const int32_t* __restrict__ n_ptr, int B, float* __restrict__ partial,
+                 int64_t part_plane, int part_ld, EpiArgs ep, ZBatch zb) {
+    __shared__ uint4 lds[4][24][64];
+    const int n = min(*n_ptr, B);
+    const int rg = blockIdx.y;
+    const int row_base = rg * 256;
+    if (row_base >= n) return;
+    if (zb.w_tab) Wp = reinterpret_cast<const uint4*>(zb.w_tab[zb.z0 + blockIdx.z]);
+    Xp += (int64_t)blockIdx.z * zb.x_stride;
+    ep.out += (int64_t)blockIdx.z * zb.out_stride;
+    const int mbs = min(8, (n - row_base + 31) >> 5);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int cnt = max(0, min(4, mbs - 4 * wm));            // live 32-row tiles of this wave
+    const int tile = blockIdx.x / splits, sp = blockIdx.x % splits;
+    const int nbw = (tile * 2 + wn) * 2;                     // first of this wave's two tile-rows of W
+    const int KS4 = KB >> 3;
+    const int ks_lo = 4 * (int)(((int64_t)KS4 * sp) / splits), ks_hi = 4 * (int)(((int64_t)KS4 * (sp + 1)) / splits);
+    const int T = ks_hi - ks_lo;                             // stages of this slice: a positive multiple of 4
+    const uint4* xg = Xp + ((int64_t)rg * 8 * KB) * 64;
+    const uint4* wg = Wp + (int64_t)(nb_off + tile * 4) * 64;   // the tile's four tile-rows of W
+    const unsigned lane_bytes = (unsigned)lane * 16u;
+    const unsigned lds0 = (unsigned)(size_t)&lds[0][0][0];
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // j-th load of stage t: j = 0..3 X tiles (row tile 2 wave + j/2, K half j%2); j = 4, 5 the W
+    // slots 2 wave + (j - 4) of the stage's eight (column tile q/2, K half q%2)
+    auto issue = [&](int t, int buf, int j) {
+        const int kb0 = 2 * (ks_lo + min(t, T - 1));
+        if (j < 4) {
+            const int mt = 2 * wave + (j >> 1);
+            const int m = min(mt, mbs - 1);
+            dma_tile(xg + ((int64_t)m * KB + kb0 + (j & 1)) * 64, lane_bytes,
+                     lds0 + (unsigned)((buf * 24 + mt * 2 + (j & 1)) << 10));
+        } else {
+            const int q = 2 * wave + (j - 4), nb = q >> 1, kk = q & 1;
+            dma_tile(wg + ((int64_t)(kb0 + kk) * NBs + nb) * 64, lane_bytes, lds0 + (unsigned)((buf * 24 + 16 + q) << 10));
+        }
+    };
+    Half a0, a1;
+    BHalf b0, b1;
+    auto rd_a = [&](Half& o, int buf, int kk, int i) { o.v[i] = lds[buf][(4 * wm + i) * 2 + kk][lane]; };
+    auto rd_b = [&](BHalf& o, int buf, int kk) {
+        o.v[0] = lds[buf][16 + (2 * wn) * 2 + kk][lane];
+        o.v[1] = lds[buf][16 + (2 * wn + 1) * 2 + kk][lane];
+    };
+    auto mf_all = [&](const Half& a, const BHalf& bw, int i) {
+        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[i]), as_bf16x8(bw.v[0]), acc[i][0], 0, 0, 0);
+        acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[i]), as_bf16x8(bw.v[1]), acc[i][1], 0, 0, 0);
+    };
+    auto mf_some = [&](const Half& a, const BHalf& bw, int i) {
+        if (i < cnt) mf_all(a, bw, i);
+    };
+#define SB __builtin_amdgcn_sched_barrier(0);
+#define STAGE_END asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#define DMA2_STAGE(MF, U)                                                                     \
+    MF(a0, b0, 0); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 0); rd_a(a1, (U), 1, 0); rd_a(a1, (U), 1, 1); rd_b(b1, (U), 1); SB \
+    MF(a0, b0, 1); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 1); rd_a(a1, (U), 1, 2); rd_a(a1, (U), 1, 3); SB \
+    MF(a0, b0, 2); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 2); SB                               \
+    MF(a0, b0, 3); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 3); SB                               \
+    MF(a1, b1, 0); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 4); rd_a(a0, ((U) + 1) & 3, 0, 0); rd_a(a0, ((U) + 1) & 3, 0, 1); rd_b(b0, ((U) + 1) & 3, 0); SB \
+    MF(a1, b1, 1); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 5); rd_a(a0, ((U) + 1) & 3, 0, 2); rd_a(a0, ((U) + 1) & 3, 0, 3); SB \
+    MF(a1, b1, 2); SB                                                                         \
+    MF(a1, b1, 3); SB                                                                         \
+    STAGE_END
+#define DMA2_LOOP(MF) \
+    for (int t0 = 0; t0 < T; t0 += 4) { DMA2_STAGE(MF, 0) DMA2_STAGE(MF, 1) DMA2_STAGE(MF, 2) DMA2_STAGE(MF, 3) }
+
+#pragma unroll
+    for (int j = 0; j < 6; ++j) issue(0, 0, j);
+#pragma unroll
+    for (int j = 0; j < 6; ++j) issue(1, 1, j);
+#pragma unroll
+    for (int j = 0; j < 6; ++j) issue(2, 2, j);
+    STAGE_END                                  // stages 0 and 1 have landed
+    a1 = Half{};
+    b1 = BHalf{};
+    rd_a(a0, 0, 0, 0); rd_a(a0, 0, 0, 1); rd_a(a0, 0, 0, 2); rd_a(a0, 0, 0, 3);
+    rd_b(b0, 0, 0);
+    if (cnt == 4) { DMA2_LOOP(mf_all) } else { DMA2_LOOP(mf_some) }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#undef DMA2_LOOP
+#undef DMA2_STAGE
+#undef STAGE_END
+#undef SB
+#define EPI_ROW(E, ARGS, I) \
+    if (4 * wm + (I) < mbs) epilogue_tile<E>(ARGS, acc[I][0], acc[I][1], row_base + 32 * (4 * wm + (I)), n, nbw, lane);
+    if (splits > 1) {
+        EpiArgs pe = ep;
+        pe.out = partial + (int64_t)sp * part_plane;
+        pe.ldo = part_ld;
+        EPI_ROW(EPI_STORE, pe, 0) EPI_ROW(EPI_STORE, pe, 1) EPI_ROW(EPI_STORE, pe, 2) EPI_ROW(EPI_STORE, pe, 3)
+        return;
+    }
+    EPI_ROW(EPI, ep, 0) EPI_ROW(EPI, ep, 1) EPI_ROW(EPI, ep, 2) EPI_ROW(EPI, ep, 3)
 #undef EPI_ROW
 }
 
@@ -1297,7 +1419,7 @@ static bool gemm_big(const ee_batch* b, const void* X, const void* W, int N, int
                            K / 16, NBs, nb_off, n_tiles, splits, n_ptr, B, b->wsp<float>(b->W.gemm_part),
                            (int64_t)Mpad * N, N, ep, zb);
     else
-        hipLaunchKernelGGL((k_bf16_gemm_big<EPI, 2>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
+        hipLaunchKernelGGL((k_bf16_gemm_dma2<EPI>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
                            K / 16, NBs, nb_off, n_tiles, splits, n_ptr, B, b->wsp<float>(b->W.gemm_part),
                            (int64_t)Mpad * N, N, ep, zb);
     if (tail.splits_out) *tail.splits_out = splits;
