@@ -268,20 +268,13 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
 }
 
 // ------------------------------------------------------------------ large-batch MFMA GEMM
-// For 65..256 rows per row group.  A workgroup of 2 x 2 waves owns a 256-row x
-// 128-column tile and one slice of K; wave (wm, wn) owns rows 128 wm .. +127 and
-// columns 64 wn .. +63 of the tile (4 x 2 MFMA tiles of 32x32, 128 accumulator
-// registers).  W tiles go from HBM straight into B-operand registers; the X
-// tiles of a 32-wide K step (16 KiB) are staged in LDS, double buffered, and
-// both are fetched several steps ahead.  When K is sliced, every slice writes
-// an fp32 partial tile and k_splitk_finish adds the slices in order.
+// For 65..256 rows per row group: 256-row tiles, 128 or 256 columns wide, one K slice per
+// workgroup, operands fed by LDS-DMA loads (k_bf16_gemm_dma, k_bf16_gemm_dma2 below).  When K
+// is sliced, every slice writes an fp32 partial tile into its own plane and a later kernel adds
+// the planes in slice order, so the result does not depend on timing and needs no atomics.
 #define BIG_THREADS 256
-struct Quad { uint4 a, b, c, d; };
 struct Half { uint4 v[4]; };   // A operands of one K half: 4 row tiles
-
-__device__ __forceinline__ void lds_barrier() {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
+struct Oct { uint4 v[8]; };    // A operands of one K half: 8 row tiles
 
 template <int EPI>
 __device__ __forceinline__ void epilogue_tile(const EpiArgs& ep, const floatx16& v0, const floatx16& v1, int row0,
@@ -339,411 +332,26 @@ __device__ __forceinline__ void epilogue_tile(const EpiArgs& ep, const floatx16&
     }
 }
 
-// The last loads of the peeled group feed only the loop; the compiler would sink them behind
-// the loop's entry test, after the W loads of the same stage, and the order of the loads in
-// flight at the loop head would again differ between its two predecessors.  A use after the
-// loop keeps them where they are written.
-#define KEEP_LOADS_IN_PLACE(A, B) \
-    asm volatile("" ::"v"((A).a.x), "v"((A).b.x), "v"((A).c.x), "v"((A).d.x), "v"((B).a.x), "v"((B).b.x), "v"((B).c.x), "v"((B).d.x));
-template <int NS> struct WFrag { uint4 v[2][NS]; };   // W tiles of one stage: [K half][column tile]
-
-template <int EPI, int NS>
-__global__ void __launch_bounds__(BIG_THREADS, 1)
-k_bf16_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int NBs, int nb_off,
-                int n_tiles, int splits, const int32_t* __restrict__ n_ptr, int B, float* __restrict__ partial,
-                int64_t part_plane, int part_ld, EpiArgs ep, ZBatch zb) {
-    __shared__ uint4 xl[3][16][64];          // 3 stages x (8 row tiles x 2 k tiles) x 1 KiB
-    const int n = min(*n_ptr, B);
-    const int rg = blockIdx.y;
-    const int row_base = rg * 256;
-    if (row_base >= n) return;
-    if (zb.w_tab) Wp = reinterpret_cast<const uint4*>(zb.w_tab[zb.z0 + blockIdx.z]);
-    Xp += (int64_t)blockIdx.z * zb.x_stride;
-    ep.out += (int64_t)blockIdx.z * zb.out_stride;
-    const int mbs = min(8, (n - row_base + 31) >> 5);
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, lives in an SGPR
-    const int wm = wave >> 1, wn = wave & 1;
-    const int cnt = max(0, min(4, mbs - 4 * wm));            // live 32-row tiles of this wave
-    const int tile = blockIdx.x / splits, sp = blockIdx.x % splits;
-    const int nbw = (tile * 2 + wn) * NS;                    // first of this wave's NS tile-rows of W
-    const int KS4 = KB >> 3;                                 // groups of four 32-wide K steps
-    const int ks_lo = 4 * (int)(((int64_t)KS4 * sp) / splits), ks_hi = 4 * (int)(((int64_t)KS4 * (sp + 1)) / splits);
-    const int T = ks_hi - ks_lo;                             // K steps of this slice: a positive multiple of 4
-    // uniform bases; the lane index is added last, so that the loads take a scalar base and a
-    // 32-bit vector offset
-    const uint4* xg = Xp + ((int64_t)rg * 8 * KB) * 64;
-    const uint4* wg = Wp + (int64_t)(nb_off + nbw) * 64;           // tile (r, c) sits at slot c * NBs + r
-    const unsigned ul = (unsigned)lane;
-
-    floatx16 acc[4][NS];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < NS; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    // Software pipeline over the 32-wide K steps ("stages").  Stage s uses the register sets
-    // xr(s % 2) (X tiles on their way to LDS; this wave stages tiles 4 wave .. 4 wave + 3),
-    // br(s % 4) (W tiles), the LDS buffer s % 3, and the A-operand registers a0 (first K half)
-    // and a1 (second K half), which are refilled from LDS half a step ahead of their use.
-    // During step t the wave runs the 8 NS MFMAs of stage t and, slotted between them so that
-    // they issue in the shadow of the matrix pipe,
-    //   writes X(t+2) to LDS,
-    //   reads a1 <- A(t, second half) and then a0 <- A(t+1, first half) from LDS,
-    //   issues the HBM/L2 loads of X(t+3) and W(t+3);
-    // then it meets the other waves at the barrier.  T is a multiple of 4 and the loop is
-    // unrolled by 4, so every register set is named statically and the steady state has no
-    // branch.  Loads past the end re-read the last stage.
-    Quad xr0, xr1;
-    WFrag<NS> br0, br1, br2, br3;
-    Half a0, a1;
-    auto load_x = [&](int t) -> Quad {
-        const int kb0 = 2 * (ks_lo + min(t, T - 1));
-        // dead row tiles re-read a live one: no branch, nothing out of range
-        const int m0 = min(2 * wave, mbs - 1), m1 = min(2 * wave + 1, mbs - 1);
-        Quad q;
-        q.a = (xg + ((int64_t)m0 * KB + kb0) * 64)[ul];
-        q.b = (xg + ((int64_t)m0 * KB + kb0 + 1) * 64)[ul];
-        q.c = (xg + ((int64_t)m1 * KB + kb0) * 64)[ul];
-        q.d = (xg + ((int64_t)m1 * KB + kb0 + 1) * 64)[ul];
-        return q;
-    };
-    auto load_w = [&](int t) -> WFrag<NS> {
-        const int kb0 = 2 * (ks_lo + min(t, T - 1));
-        WFrag<NS> q;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-            for (int ns = 0; ns < NS; ++ns) q.v[kk][ns] = (wg + ((int64_t)(kb0 + kk) * NBs + ns) * 64)[ul];
-        return q;
-    };
-    auto store_x01 = [&](int buf, const Quad& q) {
-        xl[buf][4 * wave + 0][lane] = q.a;
-        xl[buf][4 * wave + 1][lane] = q.b;
-    };
-    auto store_x23 = [&](int buf, const Quad& q) {
-        xl[buf][4 * wave + 2][lane] = q.c;
-        xl[buf][4 * wave + 3][lane] = q.d;
-    };
-    // NS MFMAs: row tile i, K half kk, all column tiles
-    auto mf = [&](const Half& a, const WFrag<NS>& bw, int kk, int i) {
-#pragma unroll
-        for (int ns = 0; ns < NS; ++ns)
-            acc[i][ns] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[i]), as_bf16x8(bw.v[kk][ns]), acc[i][ns],
-                                                                 0, 0, 0);
-    };
-    auto mf_some = [&](const Half& a, const WFrag<NS>& bw, int kk, int i) {
-        if (i < cnt) mf(a, bw, kk, i);
-    };
-    auto read_a2 = [&](Half& o, int buf, int kk, int i) {   // two A tiles
-        o.v[i] = xl[buf][(4 * wm + i) * 2 + kk][lane];
-        o.v[i + 1] = xl[buf][(4 * wm + i + 1) * 2 + kk][lane];
-    };
-#define SB __builtin_amdgcn_sched_barrier(0);
-    // one load (NS / 2 for the W quarters) behind each MFMA group, not all eight in one burst
-    auto ldx = [&](int t, int j) -> uint4 {
-        const int kb0 = 2 * (ks_lo + min(t, T - 1));
-        const int m = min(2 * wave + (j >> 1), mbs - 1);
-        return (xg + ((int64_t)m * KB + kb0 + (j & 1)) * 64)[ul];
-    };
-    auto ldw_quarter = [&](WFrag<NS>& q, int t, int part) {
-        const int kb0 = 2 * (ks_lo + min(t, T - 1));
-#pragma unroll
-        for (int e = 0; e < NS / 2; ++e) {
-            const int f = part * (NS / 2) + e, kk = f / NS, ns = f % NS;
-            q.v[kk][ns] = (wg + ((int64_t)(kb0 + kk) * NBs + ns) * 64)[ul];
-        }
-    };
-#define BIG_STEP(MF, U, XNEW, BNEW, BCUR, XOUT)                                               \
-    MF(a0, BCUR, 0, 0); SB XNEW.a = ldx(t0 + (U) + 3, 0); read_a2(a1, (t0 + (U)) % 3, 1, 0); SB \
-    MF(a0, BCUR, 0, 1); SB XNEW.b = ldx(t0 + (U) + 3, 1); read_a2(a1, (t0 + (U)) % 3, 1, 2); SB \
-    MF(a0, BCUR, 0, 2); SB XNEW.c = ldx(t0 + (U) + 3, 2); SB                                  \
-    MF(a0, BCUR, 0, 3); SB XNEW.d = ldx(t0 + (U) + 3, 3); SB                                  \
-    MF(a1, BCUR, 1, 0); SB ldw_quarter(BNEW, t0 + (U) + 3, 0); read_a2(a0, (t0 + (U) + 1) % 3, 0, 0); SB \
-    MF(a1, BCUR, 1, 1); SB ldw_quarter(BNEW, t0 + (U) + 3, 1); read_a2(a0, (t0 + (U) + 1) % 3, 0, 2); SB \
-    MF(a1, BCUR, 1, 2); SB ldw_quarter(BNEW, t0 + (U) + 3, 2); store_x01((t0 + (U) + 2) % 3, XOUT); store_x23((t0 + (U) + 2) % 3, XOUT); SB \
-    MF(a1, BCUR, 1, 3); SB ldw_quarter(BNEW, t0 + (U) + 3, 3); SB                             \
-    lds_barrier();
-    // step t stores X(t+2) from xr(t % 2) and loads X(t+3) into the other set, which held X(t+1)
-    // and was written to LDS during step t-1; W(t+3) replaces W(t-1), consumed during step t-1.
-    // The first group of four stages runs outside the loop: the loads in flight at the loop head
-    // are then the same, in the same order, whether control comes from it or from the loop's end.
-    // (With the prologue as the other predecessor the compiler's wait counts of the first stage
-    // are the prologue's, and they drain every load in flight once per group.)
-#define BIG_GROUP(MF)                                \
-        BIG_STEP(MF, 0, xr1, br3, br0, xr0)          \
-        BIG_STEP(MF, 1, xr0, br0, br1, xr1)          \
-        BIG_STEP(MF, 2, xr1, br1, br2, xr0)          \
-        BIG_STEP(MF, 3, xr0, br2, br3, xr1)
-#define BIG_LOOP(MF)                                 \
-    { const int t0 = 0; BIG_GROUP(MF) }              \
-    for (int t0 = 4; t0 < T; t0 += 4) { BIG_GROUP(MF) }
-
-    xr0 = load_x(0); br0 = load_w(0);
-    xr1 = load_x(1); br1 = load_w(1);
-    store_x01(0, xr0); store_x23(0, xr0);
-    store_x01(1, xr1); store_x23(1, xr1);
-    // the loads in flight at loop entry must be the ones (and in the order) every later pass
-    // through the loop head has: otherwise the wait counts of the first stage are the entry's,
-    // and they drain the pipeline once per unrolled group
-    __builtin_amdgcn_sched_barrier(0);
-    xr0 = load_x(2);
-    __builtin_amdgcn_sched_barrier(0);
-    br2 = load_w(2);
-    __builtin_amdgcn_sched_barrier(0);
-    br3 = WFrag<NS>{};
-    lds_barrier();
-    a1 = Half{};
-    read_a2(a0, 0, 0, 0); read_a2(a0, 0, 0, 2);
-    if (cnt == 4) { BIG_LOOP(mf) } else { BIG_LOOP(mf_some) }
-    KEEP_LOADS_IN_PLACE(xr0, xr1)
-#undef BIG_LOOP
-#undef BIG_GROUP
-#undef BIG_STEP
-#undef SB
-
-    // ---- K slices: each slice writes its fp32 partial tile row-major into its own plane of the
-    // workspace ([slice][row][N]); k_splitk_finish adds the planes in slice order and applies the
-    // epilogue, so the result does not depend on timing and no atomics or fences are needed.
-    // (written out per row tile: the accumulators must be named statically)
-#define EPI_ROW(E, ARGS, I)                                                                                   \
-    if (4 * wm + (I) < mbs) {                                                                                 \
-        epilogue_tile<E>(ARGS, acc[I][0], acc[I][1], row_base + 32 * (4 * wm + (I)), n, nbw, lane);           \
-        if constexpr (NS == 4)                                                                                \
-            epilogue_tile<E>(ARGS, acc[I][NS - 2], acc[I][NS - 1], row_base + 32 * (4 * wm + (I)), n, nbw + 2, lane); \
-    }
-    if (splits > 1) {
-        EpiArgs pe = ep;
-        pe.out = partial + (int64_t)sp * part_plane;
-        pe.ldo = part_ld;
-        EPI_ROW(EPI_STORE, pe, 0) EPI_ROW(EPI_STORE, pe, 1) EPI_ROW(EPI_STORE, pe, 2) EPI_ROW(EPI_STORE, pe, 3)
-        return;
-    }
-    EPI_ROW(EPI, ep, 0) EPI_ROW(EPI, ep, 1) EPI_ROW(EPI, ep, 2) EPI_ROW(EPI, ep, 3)
-#undef EPI_ROW
-}
-
-// ------------------------------------------------------------------ wide-tile variant
-// 256 rows x 256 columns per workgroup with the four waves side by side along N: wave w owns
-// columns 64 w .. 64 w + 63 for all eight row tiles (8 x 2 MFMA tiles, 256 accumulator
-// registers).  Every W tile is fetched by exactly one wave, so the vector-memory path carries
-// the weights once per CU instead of once per row half; the price is that every wave reads all
-// A tiles from LDS (2 MFMAs per 1 KiB read).  Same stage pipeline as k_bf16_gemm_big.
-struct Oct { uint4 v[8]; };   // A operands of one K half: 8 row tiles
-
-template <int EPI>
-__global__ void __launch_bounds__(BIG_THREADS, 1)
-k_bf16_gemm_wide(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int NBs, int nb_off,
-                 int n_tiles, int splits, const int32_t* __restrict__ n_ptr, int B, float* __restrict__ partial,
-                 int64_t part_plane, int part_ld, EpiArgs ep, ZBatch zb) {
-    __shared__ uint4 xl[3][16][64];
-    const int n = min(*n_ptr, B);
-    const int rg = blockIdx.y;
-    const int row_base = rg * 256;
-    if (row_base >= n) return;
-    if (zb.w_tab) Wp = reinterpret_cast<const uint4*>(zb.w_tab[zb.z0 + blockIdx.z]);
-    Xp += (int64_t)blockIdx.z * zb.x_stride;
-    ep.out += (int64_t)blockIdx.z * zb.out_stride;
-    const int mbs = min(8, (n - row_base + 31) >> 5);
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int tile = blockIdx.x / splits, sp = blockIdx.x % splits;
-    const int nbw = (tile * 4 + wave) * 2;                   // this wave's two tile-rows of W
-    const int KS4 = KB >> 3;                                 // groups of four 32-wide K steps
-    const int ks_lo = 4 * (int)(((int64_t)KS4 * sp) / splits), ks_hi = 4 * (int)(((int64_t)KS4 * (sp + 1)) / splits);
-    const int T = ks_hi - ks_lo;                             // K steps of this slice: a positive multiple of 4
-    const uint4* xg = Xp + ((int64_t)rg * 8 * KB) * 64;            // uniform bases, lane added last
-    const uint4* wg = Wp + (int64_t)(nb_off + nbw) * 64;
-    const unsigned ul = (unsigned)lane;
-
-    floatx16 acc[8][2];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    Quad xr0, xr1;
-    WFrag<2> br0, br1, br2, br3;
-    Oct a0, a1;
-    auto load_x = [&](int t) -> Quad {
-        const int kb0 = 2 * (ks_lo + min(t, T - 1));
-        const int m0 = min(2 * wave, mbs - 1), m1 = min(2 * wave + 1, mbs - 1);
-        Quad q;
-        q.a = (xg + ((int64_t)m0 * KB + kb0) * 64)[ul];
-        q.b = (xg + ((int64_t)m0 * KB + kb0 + 1) * 64)[ul];
-        q.c = (xg + ((int64_t)m1 * KB + kb0) * 64)[ul];
-        q.d = (xg + ((int64_t)m1 * KB + kb0 + 1) * 64)[ul];
-        return q;
-    };
-    auto load_w = [&](int t) -> WFrag<2> {
-        const int kb0 = 2 * (ks_lo + min(t, T - 1));
-        WFrag<2> q;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-            for (int ns = 0; ns < 2; ++ns) q.v[kk][ns] = (wg + ((int64_t)(kb0 + kk) * NBs + ns) * 64)[ul];
-        return q;
-    };
-    auto store_x = [&](int buf, const Quad& q) {
-        xl[buf][4 * wave + 0][lane] = q.a;
-        xl[buf][4 * wave + 1][lane] = q.b;
-        xl[buf][4 * wave + 2][lane] = q.c;
-        xl[buf][4 * wave + 3][lane] = q.d;
-    };
-    // 4 MFMAs: row tiles i, i+1; MBS = number of live row tiles, a compile-time constant of the
-    // loop instance, so that the steady state carries no branch and no mask arithmetic
-    auto mf_n = [&](auto mbs_c, const Oct& a, const WFrag<2>& bw, int kk, int i) {
-        constexpr int MBS = decltype(mbs_c)::value;
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            if (i + r < MBS) {
-                acc[i + r][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[i + r]), as_bf16x8(bw.v[kk][0]),
-                                                                        acc[i + r][0], 0, 0, 0);
-                acc[i + r][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[i + r]), as_bf16x8(bw.v[kk][1]),
-                                                                        acc[i + r][1], 0, 0, 0);
-            }
-        }
-    };
-    auto read_a2 = [&](Oct& o, int buf, int kk, int i) {
-        o.v[i] = xl[buf][i * 2 + kk][lane];
-        o.v[i + 1] = xl[buf][(i + 1) * 2 + kk][lane];
-    };
-#define SB __builtin_amdgcn_sched_barrier(0);
-    // one global load after each group of four MFMAs: issued in one burst, the eight loads of a
-    // stage (times four waves) queue up in the vector-memory path and hold the wave at the issue
-    auto ldx = [&](int t, int j) -> uint4 {
-        const int kb0 = 2 * (ks_lo + min(t, T - 1));
-        const int m = min(2 * wave + (j >> 1), mbs - 1);
-        return (xg + ((int64_t)m * KB + kb0 + (j & 1)) * 64)[ul];
-    };
-    auto ldw = [&](int t, int kk, int ns) -> uint4 {
-        const int kb0 = 2 * (ks_lo + min(t, T - 1));
-        return (wg + ((int64_t)(kb0 + kk) * NBs + ns) * 64)[ul];
-    };
-#define WIDE_STEP(U, XNEW, BNEW, BCUR, XOUT)                                                  \
-    mf(a0, BCUR, 0, 0); SB XNEW.a = ldx(t0 + (U) + 3, 0); read_a2(a1, (t0 + (U)) % 3, 1, 0); read_a2(a1, (t0 + (U)) % 3, 1, 2); SB \
-    mf(a0, BCUR, 0, 2); SB XNEW.b = ldx(t0 + (U) + 3, 1); read_a2(a1, (t0 + (U)) % 3, 1, 4); read_a2(a1, (t0 + (U)) % 3, 1, 6); SB \
-    mf(a0, BCUR, 0, 4); SB XNEW.c = ldx(t0 + (U) + 3, 2); SB                                  \
-    mf(a0, BCUR, 0, 6); SB XNEW.d = ldx(t0 + (U) + 3, 3); SB                                  \
-    mf(a1, BCUR, 1, 0); SB BNEW.v[0][0] = ldw(t0 + (U) + 3, 0, 0); read_a2(a0, (t0 + (U) + 1) % 3, 0, 0); read_a2(a0, (t0 + (U) + 1) % 3, 0, 2); SB \
-    mf(a1, BCUR, 1, 2); SB BNEW.v[0][1] = ldw(t0 + (U) + 3, 0, 1); read_a2(a0, (t0 + (U) + 1) % 3, 0, 4); read_a2(a0, (t0 + (U) + 1) % 3, 0, 6); SB \
-    mf(a1, BCUR, 1, 4); SB BNEW.v[1][0] = ldw(t0 + (U) + 3, 1, 0); store_x((t0 + (U) + 2) % 3, XOUT); SB \
-    mf(a1, BCUR, 1, 6); SB BNEW.v[1][1] = ldw(t0 + (U) + 3, 1, 1); SB                         \
-    lds_barrier();
-
-    xr0 = load_x(0); br0 = load_w(0);
-    xr1 = load_x(1); br1 = load_w(1);
-    store_x(0, xr0);
-    store_x(1, xr1);
-    __builtin_amdgcn_sched_barrier(0);   // same loads in flight, in the same order, as at every later loop head
-    xr0 = load_x(2);
-    __builtin_amdgcn_sched_barrier(0);
-    br2 = load_w(2);
-    __builtin_amdgcn_sched_barrier(0);
-    br3 = WFrag<2>{};
-    lds_barrier();
-    a1 = Oct{};
-    read_a2(a0, 0, 0, 0); read_a2(a0, 0, 0, 2); read_a2(a0, 0, 0, 4); read_a2(a0, 0, 0, 6);
-#define WIDE_GROUP                       \
-    WIDE_STEP(0, xr1, br3, br0, xr0)     \
-    WIDE_STEP(1, xr0, br0, br1, xr1)     \
-    WIDE_STEP(2, xr1, br1, br2, xr0)     \
-    WIDE_STEP(3, xr0, br2, br3, xr1)
-#define WIDE_LOOP(N)                                                                          \
-    case N: {                                                                                 \
-        auto mf = [&](const Oct& a, const WFrag<2>& bw, int kk, int i) {                      \
-            mf_n(std::integral_constant<int, N>{}, a, bw, kk, i);                             \
-        };                                                                                    \
-        { const int t0 = 0; WIDE_GROUP }  /* first group outside the loop, as in k_bf16_gemm_big */ \
-        for (int t0 = 4; t0 < T; t0 += 4) { WIDE_GROUP }                                      \
-    } break;
-    // At most four live row tiles: a stage has so few MFMAs that LDS reads issued half a stage
-    // ahead arrive late.  Half of each operand register set is idle then, so the A operands of
-    // stage t+1 (both K halves) are read at the top of stage t into the half that stage t does
-    // not use (set = stage parity): a whole stage of lead.
-    auto rd_low = [&](auto mbs_c, Oct& o, int set, int buf, int kk) {
-        constexpr int MBS = decltype(mbs_c)::value;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (i < MBS) o.v[4 * set + i] = xl[buf][i * 2 + kk][lane];
-    };
-    auto mf_low = [&](auto mbs_c, const Oct& a, const WFrag<2>& bw, int kk, int set, int i) {
-        constexpr int MBS = decltype(mbs_c)::value;
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            if (i + r < MBS) {
-                acc[i + r][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[4 * set + i + r]),
-                                                                        as_bf16x8(bw.v[kk][0]), acc[i + r][0], 0, 0, 0);
-                acc[i + r][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[4 * set + i + r]),
-                                                                        as_bf16x8(bw.v[kk][1]), acc[i + r][1], 0, 0, 0);
-            }
-        }
-    };
-#define LOW_STEP(U, XNEW, BNEW, BCUR, XOUT)                                                   \
-    rd_low(MC, a0, ((U) + 1) & 1, (t0 + (U) + 1) % 3, 0); rd_low(MC, a1, ((U) + 1) & 1, (t0 + (U) + 1) % 3, 1); SB \
-    mf_low(MC, a0, BCUR, 0, (U) & 1, 0); SB XNEW.a = ldx(t0 + (U) + 3, 0); XNEW.b = ldx(t0 + (U) + 3, 1); SB \
-    mf_low(MC, a0, BCUR, 0, (U) & 1, 2); SB XNEW.c = ldx(t0 + (U) + 3, 2); XNEW.d = ldx(t0 + (U) + 3, 3); SB \
-    mf_low(MC, a1, BCUR, 1, (U) & 1, 0); SB BNEW.v[0][0] = ldw(t0 + (U) + 3, 0, 0); BNEW.v[0][1] = ldw(t0 + (U) + 3, 0, 1); \
-                                            store_x((t0 + (U) + 2) % 3, XOUT); SB             \
-    mf_low(MC, a1, BCUR, 1, (U) & 1, 2); SB BNEW.v[1][0] = ldw(t0 + (U) + 3, 1, 0); BNEW.v[1][1] = ldw(t0 + (U) + 3, 1, 1); SB \
-    lds_barrier();
-#define LOW_GROUP                       \
-    LOW_STEP(0, xr1, br3, br0, xr0)     \
-    LOW_STEP(1, xr0, br0, br1, xr1)     \
-    LOW_STEP(2, xr1, br1, br2, xr0)     \
-    LOW_STEP(3, xr0, br2, br3, xr1)
-#define WIDE_LOOP_LOW(N)                                                                      \
-    case N: {                                                                                 \
-        const std::integral_constant<int, N> MC{};                                            \
-        rd_low(MC, a1, 0, 0, 1);   /* stage 0, second K half (the first is in a0 already) */  \
-        { const int t0 = 0; LOW_GROUP }                                                       \
-        for (int t0 = 4; t0 < T; t0 += 4) { LOW_GROUP }                                       \
-    } break;
-    switch (mbs) {
-        WIDE_LOOP_LOW(1) WIDE_LOOP_LOW(2) WIDE_LOOP_LOW(3) WIDE_LOOP_LOW(4)
-        WIDE_LOOP(5) WIDE_LOOP(6) WIDE_LOOP(7) WIDE_LOOP(8)
-    }
-#undef WIDE_LOOP
-#undef WIDE_LOOP_LOW
-#undef LOW_GROUP
-#undef LOW_STEP
-    KEEP_LOADS_IN_PLACE(xr0, xr1)
-#undef WIDE_GROUP
-#undef WIDE_STEP
-#undef SB
-#define EPI_ROW(E, ARGS, I) \
-    if ((I) < mbs) epilogue_tile<E>(ARGS, acc[I][0], acc[I][1], row_base + 32 * (I), n, nbw, lane);
-    if (splits > 1) {   // K slices: fp32 partial planes, finished by k_splitk_finish
-        EpiArgs pe = ep;
-        pe.out = partial + (int64_t)sp * part_plane;
-        pe.ldo = part_ld;
-        EPI_ROW(EPI_STORE, pe, 0) EPI_ROW(EPI_STORE, pe, 1) EPI_ROW(EPI_STORE, pe, 2) EPI_ROW(EPI_STORE, pe, 3)
-        EPI_ROW(EPI_STORE, pe, 4) EPI_ROW(EPI_STORE, pe, 5) EPI_ROW(EPI_STORE, pe, 6) EPI_ROW(EPI_STORE, pe, 7)
-        return;
-    }
-    EPI_ROW(EPI, ep, 0) EPI_ROW(EPI, ep, 1) EPI_ROW(EPI, ep, 2) EPI_ROW(EPI, ep, 3)
-    EPI_ROW(EPI, ep, 4) EPI_ROW(EPI, ep, 5) EPI_ROW(EPI, ep, 6) EPI_ROW(EPI, ep, 7)
-#undef EPI_ROW
-}
-
-// ------------------------------------------------------------------ wide tile fed by LDS-DMA loads
-// Same tile and wave layout as k_bf16_gemm_wide, but no operand passes through registers on
-// its way in: every wave sends its four X tiles and its own four W tiles of a stage straight
-// from global memory into LDS (64 lanes x 16 B per instruction, lane l lands at byte 16 l of
-// the slot), and all MFMA operands are read from LDS.  A load that returns into registers
-// holds up the matrix pipe of its SIMD while it writes back (measured: streaming and MFMA
-// time add up); a load into LDS does not, so here the weight stream runs under the MFMAs.
+// ------------------------------------------------------------------ 256-column tile fed by LDS-DMA loads
+// 256 rows x 256 columns per workgroup, the four waves side by side along N: wave w owns columns
+// 64 w .. 64 w + 63 for all eight row tiles (8 x 2 MFMA tiles of 32x32, 256 accumulator
+// registers).  No operand passes through registers on its way in: every wave sends its four X
+// tiles and its own four W tiles of a 32-wide K stage straight from global memory into LDS (64
+// lanes x 16 B per instruction, lane l lands at byte 16 l of the slot), and all MFMA operands are
+// read from LDS.  A load that returns into registers holds up the matrix pipe of its SIMD while
+// it writes back (measured: streaming time and MFMA time add up, even across waves); a load
+// into LDS does not, so here the weight stream runs under the MFMAs.
 //   LDS: 4 stage buffers x 32 slots of 1 KiB: slots 0..15 X tile (row tile m, K half kk) at
 //        2 m + kk, slots 16..31 W tile (wave w, K half kk, column tile ns) at 16 + 4 w + 2 kk + ns
 //   stage t: MFMAs of stage t; LDS reads of its second K half, then of the first K half of
 //        stage t+1; the 8 loads of stage t+3 into the buffer stage t-1 used, one behind each
-//        MFMA group; at the end wait until only those 8 are in flight (stage t+2 has landed),
-//        then the barrier that makes stage t+2 readable by all waves.
-// The compiler does not see these loads, so it adds no wait of its own; the waits are here.
+//        MFMA group (a burst would queue up in the vector-memory path and hold the wave); at
+//        the end wait until only those 8 are in flight (stage t+2 has landed), then the barrier
+//        that makes stage t+2 readable by all waves.
+// The loop exists once per number of live row tiles (1..8), so the steady state has no branch.
+// T is a multiple of 4 and the loop is unrolled by 4: every buffer is named statically.  Loads
+// past the end re-read the last stage.  The compiler does not see these loads, so it adds no
+// wait of its own; the waits are written out here.
 struct BPair { uint4 v[2]; };   // W operands of one K half: 2 column tiles
 
 // tile and lds_byte are the same in all lanes; going through readfirstlane makes that explicit, so
@@ -869,7 +477,7 @@ k_bf16_gemm_dma(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
 #undef SB
 #define EPI_ROW(E, ARGS, I) \
     if ((I) < mbs) epilogue_tile<E>(ARGS, acc[I][0], acc[I][1], row_base + 32 * (I), n, nbw, lane);
-    if (splits > 1) {   // K slices: fp32 partial planes, finished by the caller's choice of kernel
+    if (splits > 1) {   // K slices: fp32 partial planes, added up by a later kernel
         EpiArgs pe = ep;
         pe.out = partial + (int64_t)sp * part_plane;
         pe.ldo = part_ld;
@@ -883,10 +491,12 @@ k_bf16_gemm_dma(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
 }
 
 // ------------------------------------------------------------------ 128-column tile fed by LDS-DMA loads
-// The tile and wave layout of k_bf16_gemm_big (256 x 128, waves 2 x 2, each 128 rows x 64
-// columns) with the operand path of k_bf16_gemm_dma.  LDS: 4 stage buffers x 24 slots: X tile
-// (row tile m, K half kk) at 2 m + kk, W tile (column tile nb of the 4, K half kk) at
-// 16 + 2 nb + kk.  A wave sends 4 X tiles and 2 W tiles per stage and reads the 8 + 4 it needs.
+// 256 rows x 128 columns per workgroup, waves 2 x 2: wave (wm, wn) owns rows 128 wm .. +127
+// and columns 64 wn .. +63 (4 x 2 MFMA tiles, 128 accumulator registers); the operand path
+// is that of k_bf16_gemm_dma.  LDS: 4 stage buffers x 24 slots: X tile (row tile m, K half kk)
+// at 2 m + kk, W tile (column tile nb of the 4, K half kk) at 16 + 2 nb + kk.  A wave sends 4 X
+// tiles and 2 W tiles per stage and reads the 8 + 4 it needs.  For products with few columns
+// (QKV, O projection, exit head) it gives twice as many workgroups per K slice as the wide tile.
 struct BHalf { uint4 v[2]; };
 
 template <int EPI>
@@ -1402,9 +1012,8 @@ static bool gemm_big(const ee_batch* b, const void* X, const void* W, int N, int
     int row_groups = (B + 255) / 256;
     int Mpad = (B + 31) / 32 * 32;
     int KS = K / 32;
-    // wide tiles halve the LDS traffic per MFMA; worth it when they still give every CU a workgroup
-    // the wide tile moves every weight tile through the vector-memory path once; worth it when it
-    // still fills the chip, or when K is long enough that a deeper K slicing costs little
+    // the 256-column tile reads less from LDS per MFMA; worth it when it still gives every CU a
+    // workgroup, or when K is long enough that a deeper K slicing costs little
     bool wide = (N % 256 == 0) && ((N / 256) * row_groups * nz >= 200 || (EPI == EPI_RESID && K >= 2 * N));
     int n_tiles = wide ? N / 256 : N / 128;
     int splits = 1;
