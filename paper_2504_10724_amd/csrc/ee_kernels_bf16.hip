@@ -399,19 +399,23 @@ k_bf16_gemm_dma(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // j-th load of stage t into buffer buf: j = 0..3 X tiles (row tile 2 wave + j/2, K half j%2),
-    // j = 4..7 W tiles (K half (j-4)/2, column tile (j-4)%2).  Stages past the end re-read the last.
-    auto issue = [&](int t, int buf, int j) {
+    // j-th load of stage t into buffer buf.  j = 0..3: W tiles (K half j/2, column tile j%2).
+    // j = 4..: X slots; only the 2 MBS slots of live row tiles are needed, dealt out round-robin:
+    // this wave takes slots wave, wave + 4, ... (ceil(MBS / 2) of them; a slot past the live ones
+    // re-reads a live tile, so that every wave issues the same number of loads per stage and
+    // one wait count fits all).  Stages past the end re-read the last.
+    auto issue = [&](auto mbs_c, int t, int buf, int j) {
+        constexpr int MBS = decltype(mbs_c)::value;
         const int kb0 = 2 * (ks_lo + min(t, T - 1));
         if (j < 4) {
-            const int mt = 2 * wave + (j >> 1);
-            const int m = min(mt, mbs - 1);                  // a dead row tile re-reads a live one
-            dma_tile(xg + ((int64_t)m * KB + kb0 + (j & 1)) * 64, lane_bytes,
-                     lds0 + (unsigned)((buf * 32 + mt * 2 + (j & 1)) << 10));
-        } else {
-            const int kk = (j - 4) >> 1, ns = (j - 4) & 1;
+            const int kk = j >> 1, ns = j & 1;
             dma_tile(wg + ((int64_t)(kb0 + kk) * NBs + ns) * 64, lane_bytes,
                      lds0 + (unsigned)((buf * 32 + 16 + wave * 4 + kk * 2 + ns) << 10));
+        } else if (j - 4 < (MBS + 1) / 2) {
+            const int slot = wave + 4 * (j - 4);             // = 2 m + kk
+            const int src = min(slot, 2 * MBS - 1);
+            dma_tile(xg + ((int64_t)(src >> 1) * KB + kb0 + (src & 1)) * 64, lane_bytes,
+                     lds0 + (unsigned)((buf * 32 + slot) << 10));
         }
     };
     Oct a0, a1;
@@ -438,34 +442,32 @@ k_bf16_gemm_dma(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
         }
     };
 #define SB __builtin_amdgcn_sched_barrier(0);
-#define STAGE_END asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+// at most N_LOADS loads in flight = everything older than the stage just issued has landed
+#define STAGE_END(N_LOADS) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N_LOADS) : "memory");
 #define DMA_STAGE(U)                                                                          \
-    mf_d(MC, a0, b0, 0); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 0); rd_a(MC, a1, (U), 1, 0); rd_a(MC, a1, (U), 1, 2); rd_b(b1, (U), 1); SB \
-    mf_d(MC, a0, b0, 2); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 1); rd_a(MC, a1, (U), 1, 4); rd_a(MC, a1, (U), 1, 6); SB \
-    mf_d(MC, a0, b0, 4); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 2); SB                         \
-    mf_d(MC, a0, b0, 6); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 3); SB                         \
-    mf_d(MC, a1, b1, 0); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 4); rd_a(MC, a0, ((U) + 1) & 3, 0, 0); rd_a(MC, a0, ((U) + 1) & 3, 0, 2); rd_b(b0, ((U) + 1) & 3, 0); SB \
-    mf_d(MC, a1, b1, 2); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 5); rd_a(MC, a0, ((U) + 1) & 3, 0, 4); rd_a(MC, a0, ((U) + 1) & 3, 0, 6); SB \
-    mf_d(MC, a1, b1, 4); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 6); SB                         \
-    mf_d(MC, a1, b1, 6); SB issue(t0 + (U) + 3, ((U) + 3) & 3, 7); SB                         \
-    STAGE_END
+    mf_d(MC, a0, b0, 0); SB issue(MC, t0 + (U) + 3, ((U) + 3) & 3, 0); rd_a(MC, a1, (U), 1, 0); rd_a(MC, a1, (U), 1, 2); rd_b(b1, (U), 1); SB \
+    mf_d(MC, a0, b0, 2); SB issue(MC, t0 + (U) + 3, ((U) + 3) & 3, 1); rd_a(MC, a1, (U), 1, 4); rd_a(MC, a1, (U), 1, 6); SB \
+    mf_d(MC, a0, b0, 4); SB issue(MC, t0 + (U) + 3, ((U) + 3) & 3, 2); SB                         \
+    mf_d(MC, a0, b0, 6); SB issue(MC, t0 + (U) + 3, ((U) + 3) & 3, 3); SB                         \
+    mf_d(MC, a1, b1, 0); SB issue(MC, t0 + (U) + 3, ((U) + 3) & 3, 4); rd_a(MC, a0, ((U) + 1) & 3, 0, 0); rd_a(MC, a0, ((U) + 1) & 3, 0, 2); rd_b(b0, ((U) + 1) & 3, 0); SB \
+    mf_d(MC, a1, b1, 2); SB issue(MC, t0 + (U) + 3, ((U) + 3) & 3, 5); rd_a(MC, a0, ((U) + 1) & 3, 0, 4); rd_a(MC, a0, ((U) + 1) & 3, 0, 6); SB \
+    mf_d(MC, a1, b1, 4); SB issue(MC, t0 + (U) + 3, ((U) + 3) & 3, 6); SB                         \
+    mf_d(MC, a1, b1, 6); SB issue(MC, t0 + (U) + 3, ((U) + 3) & 3, 7); SB                         \
+    STAGE_END(4 + (decltype(MC)::value + 1) / 2)
 #define DMA_LOOP(N)                                                                           \
     case N: {                                                                                 \
         const std::integral_constant<int, N> MC{};                                            \
+        /* stages 0, 1, 2 on their way; 0 and 1 must have landed before the first reads */    \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) issue(MC, 0, 0, j);                     \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) issue(MC, 1, 1, j);                     \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) issue(MC, 2, 2, j);                     \
+        STAGE_END(4 + (N + 1) / 2)                                                            \
+        rd_b(b0, 0, 0);                                                                       \
         rd_a(MC, a0, 0, 0, 0); rd_a(MC, a0, 0, 0, 2); rd_a(MC, a0, 0, 0, 4); rd_a(MC, a0, 0, 0, 6); \
         for (int t0 = 0; t0 < T; t0 += 4) { DMA_STAGE(0) DMA_STAGE(1) DMA_STAGE(2) DMA_STAGE(3) } \
     } break;
 
-    // stages 0, 1, 2 on their way; 0 and 1 must have landed before the first reads
-#pragma unroll
-    for (int j = 0; j < 8; ++j) issue(0, 0, j);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) issue(1, 1, j);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) issue(2, 2, j);
-    STAGE_END
     a0 = Oct{}; a1 = Oct{};
-    rd_b(b0, 0, 0);
     b1 = BPair{};
     switch (mbs) {
         DMA_LOOP(1) DMA_LOOP(2) DMA_LOOP(3) DMA_LOOP(4) DMA_LOOP(5) DMA_LOOP(6) DMA_LOOP(7) DMA_LOOP(8)
