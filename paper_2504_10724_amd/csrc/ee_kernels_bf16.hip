@@ -268,7 +268,7 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
 }
 
 // ------------------------------------------------------------------ large-batch MFMA GEMM
-// For 65..256 rows per row group: 256-row tiles, 128 or 256 columns wide, one K slice per
+// 256-row tiles (up to 256 rows per row group), 128 or 256 columns wide, one K slice per
 // workgroup, operands fed by LDS-DMA loads (k_bf16_gemm_dma, k_bf16_gemm_dma2 below).  When K
 // is sliced, every slice writes an fp32 partial tile into its own plane and a later kernel adds
 // the planes in slice order, so the result does not depend on timing and needs no atomics.
@@ -1004,13 +1004,22 @@ struct SliceTail {
     int*         splits_out = nullptr;  // ... who gets their number (1 = the result is in out already)
 };
 
-// batches above 64 rows: the 256-row tile kernel, 128 or 256 columns wide, K sliced so that about
-// one workgroup per CU runs
+// the 256-row tile kernels, 128 or 256 columns wide, K sliced so that about one workgroup per CU
+// runs; returns false where the weight-streaming kernel is the better choice
 template <int EPI>
 static bool gemm_big(const ee_batch* b, const void* X, const void* W, int N, int K, int NBs, int nb_off,
                      const int32_t* n_ptr, int B, const EpiArgs& ep, hipStream_t s, const ZBatch& zb = ZBatch{},
                      int nz = 1, const SliceTail& tail = SliceTail{}) {
-    if (B <= 64 || N % 128 != 0 || K % 128 != 0) return false;
+    if (N % 128 != 0 || K % 128 != 0) return false;
+    // smallest batch capacity from which the tile kernels beat the weight-streaming kernel
+    // (measured per product on the 70B shapes): the gate/up product always, QKV and the down
+    // projection above 32 rows, the O projection, the exit head and multi-layer launches above 64
+    int min_rows = 65;
+    if (nz == 1) {
+        if (EPI == EPI_SWIGLU) min_rows = 1;
+        else if (EPI == EPI_STORE || (EPI == EPI_RESID && K >= 2 * N)) min_rows = 33;
+    }
+    if (B < min_rows) return false;
     int row_groups = (B + 255) / 256;
     int Mpad = (B + 31) / 32 * 32;
     int KS = K / 32;
