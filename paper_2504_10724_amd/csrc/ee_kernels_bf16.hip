@@ -40,23 +40,26 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
 }
 
 // ------------------------------------------------------------------ RMSNorm -> A tiles
-// The 256 threads of a block normalise one row (hr: d floats) and write it as list entry i of
-// the [Mpad][d] activation matrix in tile order.  Every thread reads only the 8-float chunks
-// c = threadIdx.x + 256 j, so a caller may have written those same chunks just before.
+// The NORM_THREADS threads of a block normalise one row (hr: d floats) and write it as list entry
+// i of the [Mpad][d] activation matrix in tile order.  Every thread reads only the 8-float chunks
+// c = threadIdx.x + NORM_THREADS j, so a caller may have written those same chunks just before.
+// (1024 threads: one chunk each at d = 8192; the kernels here are latency bound, and every
+// user of this routine takes the same thread count so that all give the same bits.)
+#define NORM_THREADS 1024
 __device__ __forceinline__ void rmsnorm_row(const float* hr_, const float* gain, float eps, int d, uint4* out, int i,
-                                            float* red) {
+                                            float* red /* NORM_THREADS / 64 floats */) {
     const float4* hr = reinterpret_cast<const float4*>(hr_);
     const float4* g4 = reinterpret_cast<const float4*>(gain);
     int n8 = d >> 3;
     float ss = 0.f;
-    for (int c = threadIdx.x; c < n8; c += 256) {
+    for (int c = threadIdx.x; c < n8; c += NORM_THREADS) {
         float4 a = hr[2 * c], b = hr[2 * c + 1];
         ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w + b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
     }
-    ss = block_sum<256>(ss, red);
+    ss = block_sum<NORM_THREADS>(ss, red);
     float inv = 1.0f / sqrtf(ss / (float)d + eps);
     int KB = d >> 4;
-    for (int c = threadIdx.x; c < n8; c += 256) {
+    for (int c = threadIdx.x; c < n8; c += NORM_THREADS) {
         float4 a = hr[2 * c], b = hr[2 * c + 1];
         float4 ga = g4[2 * c], gb = g4[2 * c + 1];
         uint4 o;
@@ -69,10 +72,10 @@ __device__ __forceinline__ void rmsnorm_row(const float* hr_, const float* gain,
 }
 
 // one block per list entry i; out is the [Mpad][d] activation matrix in tile order
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(NORM_THREADS)
 k_bf16_rmsnorm(const float* __restrict__ h, const int32_t* __restrict__ idx, const int32_t* __restrict__ n_ptr,
                int B, const float* __restrict__ gain, float eps, int d, uint4* __restrict__ out, ZBatch zb) {
-    __shared__ float red[4];
+    __shared__ float red[NORM_THREADS / 64];
     int i = blockIdx.x;
     int n = min(*n_ptr, B);
     if (i >= n) return;
@@ -943,53 +946,31 @@ k_splitk_finish(const float* __restrict__ partial, int64_t plane, int ld, int sp
 // Residual finish of a K-sliced product, one block per list entry: h[row id] += sum of the
 // slice planes (in slice order, as k_splitk_finish does), and, if a gain is given, the RMSNorm
 // of the updated row straight into the operand matrix of the next product.
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(NORM_THREADS)
 k_splitk_resid_norm(const float* __restrict__ partial, int64_t plane, int ld, int splits, int N,
                     const int32_t* __restrict__ n_ptr, int B, float* h, int ldh, const int32_t* __restrict__ idx,
                     const float* gain, float eps, uint4* xout) {
-    __shared__ float red[4];
+    __shared__ float red[NORM_THREADS / 64];
     const int n = min(*n_ptr, B);
     const int i = blockIdx.x;
     if (i >= n) return;
     float* hrow = h + (int64_t)idx[i] * ldh;
     const float* prow = partial + (int64_t)i * ld;
-    // four 8-float chunks per thread and pass: the loads of one plane are all in flight together
-    for (int c0 = threadIdx.x; c0 < (N >> 3); c0 += 1024) {
-        float4 sum[4][2];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int c = min(c0 + 256 * j, (N >> 3) - 1);
-            sum[j][0] = *reinterpret_cast<const float4*>(prow + c * 8);
-            sum[j][1] = *reinterpret_cast<const float4*>(prow + c * 8 + 4);
-        }
+    for (int c = threadIdx.x; c < (N >> 3); c += NORM_THREADS) {
+        const float* p = prow + c * 8;
+        float4 s0 = *reinterpret_cast<const float4*>(p), s1 = *reinterpret_cast<const float4*>(p + 4);
+#pragma unroll 4
         for (int q = 1; q < splits; ++q) {
-            float4 v[4][2];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int c = min(c0 + 256 * j, (N >> 3) - 1);
-                v[j][0] = *reinterpret_cast<const float4*>(prow + (int64_t)q * plane + c * 8);
-                v[j][1] = *reinterpret_cast<const float4*>(prow + (int64_t)q * plane + c * 8 + 4);
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    sum[j][u].x += v[j][u].x; sum[j][u].y += v[j][u].y; sum[j][u].z += v[j][u].z; sum[j][u].w += v[j][u].w;
-                }
+            const float4 v0 = *reinterpret_cast<const float4*>(p + (int64_t)q * plane);
+            const float4 v1 = *reinterpret_cast<const float4*>(p + (int64_t)q * plane + 4);
+            s0.x += v0.x; s0.y += v0.y; s0.z += v0.z; s0.w += v0.w;
+            s1.x += v1.x; s1.y += v1.y; s1.z += v1.z; s1.w += v1.w;
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int c = c0 + 256 * j;
-            if (c < (N >> 3)) {
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    float4* hp = reinterpret_cast<float4*>(hrow + c * 8 + u * 4);
-                    float4 o = *hp;
-                    o.x += sum[j][u].x; o.y += sum[j][u].y; o.z += sum[j][u].z; o.w += sum[j][u].w;
-                    *hp = o;
-                }
-            }
-        }
+        float4* hp = reinterpret_cast<float4*>(hrow + c * 8);
+        float4 o0 = hp[0], o1 = hp[1];
+        o0.x += s0.x; o0.y += s0.y; o0.z += s0.z; o0.w += s0.w;
+        o1.x += s1.x; o1.y += s1.y; o1.z += s1.z; o1.w += s1.w;
+        hp[0] = o0; hp[1] = o1;
     }
     if (gain != nullptr) rmsnorm_row(hrow, gain, eps, N, xout, i, red);   // reads back this thread's own chunks
 }
@@ -1045,7 +1026,7 @@ static bool gemm_big(const ee_batch* b, const void* X, const void* W, int N, int
     if (tail.splits_out) *tail.splits_out = splits;
     if (splits > 1) {
         if (EPI == EPI_RESID) {
-            hipLaunchKernelGGL(k_splitk_resid_norm, dim3(B), dim3(256), 0, s, b->wsp<float>(b->W.gemm_part),
+            hipLaunchKernelGGL(k_splitk_resid_norm, dim3(B), dim3(NORM_THREADS), 0, s, b->wsp<float>(b->W.gemm_part),
                                (int64_t)Mpad * N, N, splits, N, n_ptr, B, ep.out, ep.ldo, ep.idx, tail.norm_gain,
                                tail.eps, tail.norm_out);
             if (tail.norm_gain && tail.norm_done) *tail.norm_done = true;
@@ -1078,7 +1059,7 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
 
     if (!x_ready) {
         TimedScope t(EE_K_NORM, s);
-        hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, h, idx, n_ptr, B, w.g_attn, c.rms_eps, d, x, ZBatch{});
+        hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(NORM_THREADS), 0, s, h, idx, n_ptr, B, w.g_attn, c.rms_eps, d, x, ZBatch{});
     }
     EpiArgs e1{};
     e1.out = qkv; e1.ldo = qkv_n; e1.idx = idx;
@@ -1124,7 +1105,7 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
     }
     if (!ffn_x_done) {
         TimedScope t(EE_K_NORM, s);
-        hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, h, idx, n_ptr, B, w.g_ffn, c.rms_eps, d, x, ZBatch{});
+        hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(NORM_THREADS), 0, s, h, idx, n_ptr, B, w.g_ffn, c.rms_eps, d, x, ZBatch{});
     }
     EpiArgs e3{};
     e3.act = act; e3.KB_act = F / 16; e3.idx = idx;
@@ -1154,7 +1135,7 @@ int bf16_exit_head(const ee_model* m, int e, float th, int force, ee_batch* b, f
     uint4* x = b->wsp<uint4>(b->W.x);
     if (!x_ready) {
         TimedScope t(EE_K_NORM, s);
-        hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(256), 0, s, b->st<float>(L.h), idx, n_ptr, B,
+        hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B), dim3(NORM_THREADS), 0, s, b->st<float>(L.h), idx, n_ptr, B,
                            m->exits[e].gain, c.rms_eps, d, x, ZBatch{});
     }
     EpiArgs ep{};
@@ -1187,7 +1168,7 @@ int bf16_fill_kv(const ee_model* m, int from_excl, int to_incl, ee_kv* kv, ee_ba
     ZBatch zb{};
     zb.w_tab = m->d_wqkv_tab; zb.g_tab = m->d_gattn_tab; zb.z0 = from_excl;
     zb.x_stride = (int64_t)b->Mpad * d / 8; zb.out_stride = (int64_t)b->Mpad * kv_n;
-    hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B, 1, nl), dim3(256), 0, s, b->st<float>(L.h), idx, n_ptr, B,
+    hipLaunchKernelGGL(k_bf16_rmsnorm, dim3(B, 1, nl), dim3(NORM_THREADS), 0, s, b->st<float>(L.h), idx, n_ptr, B,
                        (const float*)nullptr, c.rms_eps, d, x, zb);
     // key and value rows are the last 2*H_kv*hd rows of W_qkv: tile-rows H_q*hd/32 onwards
     EpiArgs ep{};
