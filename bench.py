@@ -28,8 +28,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the gate/up GEMM at batch 256 from the rocprofv3 counter runs summarised in
 # profiles/llama2_70b_b256_hbm_traffic.md (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, KiB -> bytes); valid
 # only for the kernel source it was measured on.
-TRAFFIC_KERNEL_SHA1 = "43758ade4e4b75246feb3edfff094d90a8c1135e"
-TRAFFIC_GATE_UP_BYTES = (948245 + 18172) * 1024
+TRAFFIC_KERNEL_SHA1 = "0a9c1f54ab1177caef50fb6eb57e8dcbae2c88bd"
+TRAFFIC_GATE_UP_BYTES = (943291 + 13412) * 1024
 
 
 def measured_traffic(batch):
@@ -183,8 +183,11 @@ def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
     batch.reset(tok0, ctx.astype(np.int32), None)
     lib.ee_timing_reset()
     lib.ee_timing_enable((1 << len(ee.KERNEL_CLASSES)) - 1)
-    run(args.steps, 0)
-    torch.cuda.synchronize()
+    live_launches = 0          # layer launches that still had a row (the others return at once)
+    for t in range(args.steps):
+        run(1, t)
+        torch.cuda.synchronize()
+        live_launches += int(f("out_layer").max())
     lib.ee_timing_enable(0)
     kern = read_classes()
     for name in ("attention", "gemm_gate_up"):
@@ -199,20 +202,23 @@ def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
     # gate/up projection with the SwiGLU epilogue: weights streamed once per launch
     gu = kern["gemm_gate_up"]
     gu_bytes = 2 * F * d * 2
-    gu_flops = 2.0 * rows_per_launch.mean() * d * 2 * F                          # per launch, average active rows
-    gu_t = gu["total_ms"] / max(1, gu["launches"]) * 1e-3
+    # per-launch durations are per launch with live rows: at small batches the deep layers run empty
+    live_frac = live_launches / max(1, gu["launches"])
+    rows_live = float(rows_per_launch.sum()) * args.steps / max(1, live_launches)   # average rows of a live launch
+    gu_flops = 2.0 * rows_live * d * 2 * F
+    gu_t = gu["total_ms"] / max(1, gu["launches"]) / max(live_frac, 1e-9) * 1e-3
     at = kern["attention"]
     kv_bytes_token = 2 * s.n_kv_heads * s.head_dim * 2
     mean_pos = float(ctx.mean()) + (args.steps + 1) / 2.0
-    at_bytes = rows_per_launch.mean() * mean_pos * kv_bytes_token
-    at_t = at["total_ms"] / max(1, at["launches"]) * 1e-3
+    at_bytes = rows_live * mean_pos * kv_bytes_token
+    at_t = at["total_ms"] / max(1, at["launches"]) / max(live_frac, 1e-9) * 1e-3
     layer_kernels = ["norm", "gemm_qkv", "rope_append", "attention", "gemm_o", "gemm_gate_up", "gemm_down"]
     dominant = max(layer_kernels, key=lambda k: kern[k]["total_ms"])
     if dominant == "attention":
         roof = dict(kernel="k_bf16_attn", bound="hbm", achieved=at_bytes / at_t / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
                     traffic=None)
     else:
-        roof = dict(kernel="k_bf16_gemm (gate/up + SwiGLU)", bound="hbm", achieved=gu_bytes / gu_t / 1e9,
+        roof = dict(kernel="k_bf16_gemm_dma<SWIGLU> (gate/up + SwiGLU)", bound="hbm", achieved=gu_bytes / gu_t / 1e9,
                     peak=HBM_PEAK_GBS, unit="GB/s", traffic=measured_traffic(s.batch))
     roof["frac"] = roof["achieved"] / roof["peak"]
     weights_per_layer = s.layer_params() * 2
@@ -220,15 +226,15 @@ def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
         batch=s.batch, tokens_per_s=tokens / dt, ms_per_step=dt / args.steps * 1e3,
         exit_fractions={str(l): float(c) / tokens for l, c in zip(exits, counts)},
         avg_layers_per_token=float((np.asarray(exits) * counts).sum() / tokens),
-        avg_active_rows=float(rows_per_launch.mean()),
+        avg_active_rows=float(rows_per_launch.mean()), live_layer_launches=live_launches,
         gate_up_gemm=dict(avg_us=gu_t * 1e6, hbm_gbs=gu_bytes / gu_t / 1e9, hbm_frac=gu_bytes / gu_t / 1e9 / HBM_PEAK_GBS,
                           tflops=gu_flops / gu_t / 1e12, mfma_frac=gu_flops / gu_t / 1e12 / MFMA_BF16_PEAK_TFLOPS),
         attention=dict(avg_us=at_t * 1e6, hbm_gbs=at_bytes / at_t / 1e9, hbm_frac=at_bytes / at_t / 1e9 / HBM_PEAK_GBS),
         # all weights of a layer streamed once per launch over the four GEMMs of the layer
         layer_gemms=dict(avg_us=sum(kern[k]["total_ms"] for k in ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down")) /
-                         max(1, gu["launches"]) * 1e3,
+                         max(1, live_launches) * 1e3,
                          hbm_gbs=weights_per_layer / (sum(kern[k]["total_ms"] for k in ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down")) /
-                                                      max(1, gu["launches"]) * 1e-3) / 1e9),
+                                                      max(1, live_launches) * 1e-3) / 1e9),
         exit_head_plus_compaction_us_per_step=(kern["exit_gemm"]["total_ms"] + kern["exit_decide"]["total_ms"] +
                                                kern["compact"]["total_ms"]) * 1e3 / args.steps,
         kernels_ms=kern, roofline=roof, counts=counts.tolist())
@@ -299,7 +305,7 @@ def main():
                                     f"F={s.d_ffn} V={s.vocab} exits={list(exits)} th={list(s.thresholds)}",
                            batch=s.batch, ctx=[s.ctx_lo, s.ctx_hi], valid_config=valid),
                exit_fractions=head["exit_fractions"], roofline=head["roofline"],
-               detail={k: head[k] for k in ("avg_layers_per_token", "avg_active_rows", "gate_up_gemm", "attention",
+               detail={k: head[k] for k in ("avg_layers_per_token", "avg_active_rows", "live_layer_launches", "gate_up_gemm", "attention",
                                             "layer_gemms", "exit_head_plus_compaction_us_per_step", "kernels_ms")},
                batch_sweep=sweep)
     if not args.no_cpu_baseline:
