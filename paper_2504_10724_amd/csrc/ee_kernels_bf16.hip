@@ -501,7 +501,7 @@ k_bf16_gemm_dma(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
 // is that of k_bf16_gemm_dma.  LDS: 4 stage buffers x 24 slots: X tile (row tile m, K half kk)
 // at 2 m + kk, W tile (column tile nb of the 4, K half kk) at 16 + 2 nb + kk.  A wave sends 4 X
 // tiles and 2 W tiles per stage and reads the 8 + 4 it needs.  For products with few columns
-// (QKV, O projection, exit head) it gives twice as many workgroups per K slice as the wide tile.
+// (QKV, O projection, exit head) it gives twice as many workgroups per K slice as the 256-column tile.
 struct BHalf { uint4 v[2]; };
 
 template <int EPI>
@@ -988,7 +988,7 @@ struct SliceTail {
 // the 256-row tile kernels, 128 or 256 columns wide, K sliced so that about one workgroup per CU
 // runs; returns false where the weight-streaming kernel is the better choice
 template <int EPI>
-static bool gemm_big(const ee_batch* b, const void* X, const void* W, int N, int K, int NBs, int nb_off,
+static bool gemm_tiled(const ee_batch* b, const void* X, const void* W, int N, int K, int NBs, int nb_off,
                      const int32_t* n_ptr, int B, const EpiArgs& ep, hipStream_t s, const ZBatch& zb = ZBatch{},
                      int nz = 1, const SliceTail& tail = SliceTail{}) {
     if (N % 128 != 0 || K % 128 != 0) return false;
@@ -1068,7 +1068,7 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
         TimedScope t(EE_K_GEMM_QKV, s);
         SliceTail st;                  // K-slice planes of q|k|v are added up by the RoPE kernel
         st.defer_store = true; st.splits_out = &qkv_splits;
-        if (!gemm_big<EPI_STORE>(b, x, w.w_qkv, qkv_n, d, qkv_n / 32, 0, n_ptr, B, e1, s, ZBatch{}, 1, st))
+        if (!gemm_tiled<EPI_STORE>(b, x, w.w_qkv, qkv_n, d, qkv_n / 32, 0, n_ptr, B, e1, s, ZBatch{}, 1, st))
             gemm<1, EPI_STORE>(x, w.w_qkv, qkv_n, d, qkv_n / 32, 0, n_ptr, B, e1, s);
     }
     {
@@ -1100,7 +1100,7 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
         TimedScope t(EE_K_GEMM_O, s);
         SliceTail st;                  // the finish of a sliced product also normalises for the FFN
         st.norm_gain = w.g_ffn; st.eps = c.rms_eps; st.norm_out = x; st.norm_done = &ffn_x_done;
-        if (!gemm_big<EPI_RESID>(b, ao, w.w_o, d, qd, d / 32, 0, n_ptr, B, e2, s, ZBatch{}, 1, st))
+        if (!gemm_tiled<EPI_RESID>(b, ao, w.w_o, d, qd, d / 32, 0, n_ptr, B, e2, s, ZBatch{}, 1, st))
             gemm<1, EPI_RESID>(ao, w.w_o, d, qd, d / 32, 0, n_ptr, B, e2, s);
     }
     if (!ffn_x_done) {
@@ -1111,14 +1111,14 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
     e3.act = act; e3.KB_act = F / 16; e3.idx = idx;
     {
         TimedScope t(EE_K_GEMM_GATE_UP, s);
-        if (!gemm_big<EPI_SWIGLU>(b, x, w.w_gate_up, 2 * F, d, 2 * F / 32, 0, n_ptr, B, e3, s))
+        if (!gemm_tiled<EPI_SWIGLU>(b, x, w.w_gate_up, 2 * F, d, 2 * F / 32, 0, n_ptr, B, e3, s))
             gemm<2, EPI_SWIGLU>(x, w.w_gate_up, 2 * F, d, 2 * F / 32, 0, n_ptr, B, e3, s);
     }
     {
         TimedScope t(EE_K_GEMM_DOWN, s);
         SliceTail st;
         st.norm_gain = tail_gain; st.eps = c.rms_eps; st.norm_out = x; st.norm_done = x_done;
-        if (!gemm_big<EPI_RESID>(b, act, w.w_down, d, F, d / 32, 0, n_ptr, B, e2, s, ZBatch{}, 1, st))
+        if (!gemm_tiled<EPI_RESID>(b, act, w.w_down, d, F, d / 32, 0, n_ptr, B, e2, s, ZBatch{}, 1, st))
             gemm<1, EPI_RESID>(act, w.w_down, d, F, d / 32, 0, n_ptr, B, e2, s);
     }
     EE_LAUNCH_CHECK();
@@ -1145,7 +1145,7 @@ int bf16_exit_head(const ee_model* m, int e, float th, int force, ee_batch* b, f
     ep.dbg_logits = dbg; ep.ldo = V;
     {
         TimedScope t(EE_K_EXIT_GEMM, s);
-        if (!gemm_big<EPI_EXIT>(b, x, m->exits[e].w, V, d, V / 32, 0, n_ptr, B, ep, s))
+        if (!gemm_tiled<EPI_EXIT>(b, x, m->exits[e].w, V, d, V / 32, 0, n_ptr, B, ep, s))
             gemm<1, EPI_EXIT>(x, m->exits[e].w, V, d, V / 32, 0, n_ptr, B, ep, s);
     }
     EE_LAUNCH_CHECK();
@@ -1174,7 +1174,7 @@ int bf16_fill_kv(const ee_model* m, int from_excl, int to_incl, ee_kv* kv, ee_ba
     EpiArgs ep{};
     ep.out = kvb; ep.ldo = kv_n; ep.idx = idx;
     int NBs = (c.n_q_heads + 2 * c.n_kv_heads) * hd / 32, nb_off = c.n_q_heads * hd / 32;
-    if (!gemm_big<EPI_STORE>(b, x, nullptr, kv_n, d, NBs, nb_off, n_ptr, B, ep, s, zb, nl))
+    if (!gemm_tiled<EPI_STORE>(b, x, nullptr, kv_n, d, NBs, nb_off, n_ptr, B, ep, s, zb, nl))
         gemm<1, EPI_STORE>(x, nullptr, kv_n, d, NBs, nb_off, n_ptr, B, ep, s, zb, nl);
     hipLaunchKernelGGL(k_bf16_rope_append, dim3(B, 1, nl), dim3(256), 0, s, kvb, kv_n, 0, idx, n_ptr, B,
                        b->st<int32_t>(L.pos), m->d_rope, c.max_pos, make_view(m, kv, from_excl + 1),
