@@ -184,11 +184,14 @@ def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
     lib.ee_timing_reset()
     lib.ee_timing_enable((1 << len(ee.KERNEL_CLASSES)) - 1)
     live_launches = 0          # layer launches that still had a row (the others return at once)
+    cbc = S.BreachCounter(lib)  # the device-side confidence-breach counter, fed after every step
     for t in range(args.steps):
         run(1, t)
+        cbc.push_step(batch)
         torch.cuda.synchronize()
         live_launches += int(f("out_layer").max())
     lib.ee_timing_enable(0)
+    cbc_state = cbc.read()
     kern = read_classes()
     for name in ("attention", "gemm_gate_up"):
         kern[name] = timed_kern[name]            # the durations measured inside the timed region
@@ -237,7 +240,9 @@ def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
                                                       max(1, live_launches) * 1e-3) / 1e9),
         exit_head_plus_compaction_us_per_step=(kern["exit_gemm"]["total_ms"] + kern["exit_decide"]["total_ms"] +
                                                kern["compact"]["total_ms"]) * 1e3 / args.steps,
-        kernels_ms=kern, roofline=roof, counts=counts.tolist())
+        kernels_ms=kern, roofline=roof, counts=counts.tolist(),
+        breach_counter=dict(update_us_per_step=kern["cbc"]["total_ms"] * 1e3 / args.steps,
+                            reassessments=cbc_state["n_triggers"], tokens=cbc_state["tokens_seen"]))
     res["layer_gemms"]["hbm_frac"] = res["layer_gemms"]["hbm_gbs"] / HBM_PEAK_GBS
     del batch, kv
     torch.cuda.empty_cache()
@@ -306,7 +311,7 @@ def main():
                            batch=s.batch, ctx=[s.ctx_lo, s.ctx_hi], valid_config=valid),
                exit_fractions=head["exit_fractions"], roofline=head["roofline"],
                detail={k: head[k] for k in ("avg_layers_per_token", "avg_active_rows", "live_layer_launches", "gate_up_gemm", "attention",
-                                            "layer_gemms", "exit_head_plus_compaction_us_per_step", "kernels_ms")},
+                                            "layer_gemms", "exit_head_plus_compaction_us_per_step", "breach_counter", "kernels_ms")},
                batch_sweep=sweep)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(s, head["counts"])

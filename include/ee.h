@@ -257,6 +257,44 @@ int ee_fill_skipped_kv(const ee_model* m, int from_layer_excl, int to_layer_incl
 int ee_decode_step(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_thresholds,
                    int n_thresholds, void* stream);
 
+/* ------------------------------------------------------------------ confidence-breach counter
+ *
+ * The serving loop above the decode step re-assesses its choice of model (load more
+ * layers or switch) only when more than cbc_max of the last `window` emitted tokens
+ * stopped below their confidence threshold (Sec. 3.3.3 and Algorithm 1 of the paper;
+ * defaults 100 and 50).  The counter lives on the device so that no step has to wait
+ * for the host: tokens are taken in the order (decode step, row id); the window holds
+ * the most recent `window` tokens since the last re-assessment; after every token the
+ * breaches in the window are compared with cbc_max; "more than" is strict; a
+ * re-assessment empties the window.
+ *
+ * State: device memory owned by the caller, ee_cbc_state_bytes(window) bytes, 8-byte
+ * aligned: this header followed by uint8 ring[window].  The host reads n_triggers (and
+ * trigger_at) after synchronising the stream. */
+#define EE_CBC_LOG 64
+#define EE_CBC_MAX_WINDOW 4096
+typedef struct {
+    int32_t window;                 /* tokens in the sliding window                         */
+    int32_t cbc_max;                /* breaches tolerated inside the window                 */
+    int32_t head;                   /* ring slot the next token goes to                     */
+    int32_t filled;                 /* tokens in the window (<= window)                     */
+    int32_t count;                  /* breaches among them                                  */
+    int32_t n_triggers;             /* re-assessments fired since ee_cbc_init               */
+    int64_t tokens_seen;            /* tokens fed since ee_cbc_init                         */
+    int64_t trigger_at[EE_CBC_LOG]; /* 1-based ordinal of the token of each of the first
+                                       EE_CBC_LOG re-assessments                            */
+} ee_cbc_state;
+
+/* Bytes of a counter state for the given window; 0 if window is outside 1..EE_CBC_MAX_WINDOW. */
+size_t ee_cbc_state_bytes(int window);
+/* Writes a fresh state (enqueue only).  EE_ERR_INVALID_ARG on a null pointer, a window outside
+ * 1..EE_CBC_MAX_WINDOW or a negative cbc_max. */
+int ee_cbc_init(void* dev_state, int window, int cbc_max, void* stream);
+/* Feeds n tokens: dev_flags[j] != 0 means token j stopped below its threshold.  Enqueue only. */
+int ee_cbc_push(void* dev_state, const uint8_t* dev_flags, int n, void* stream);
+/* Feeds the tokens of the decode step that just ran on this batch: out_breach[0 .. B). */
+int ee_cbc_push_step(void* dev_state, const ee_batch* b, void* stream);
+
 /* ------------------------------------------------------------------ measurement aid */
 
 /* Kernel classes of the decode step, for ee_timing_read. */
@@ -273,7 +311,8 @@ typedef enum {
     EE_K_EXIT_DECIDE = 9,
     EE_K_COMPACT = 10,
     EE_K_FILL_KV = 11,      /* all kernels of ee_fill_skipped_kv                      */
-    EE_K_COUNT = 12
+    EE_K_CBC = 12,          /* confidence-breach counter update                       */
+    EE_K_COUNT = 13
 } ee_kernel_class;
 
 /* class_mask: bit k set = every launch of kernel class k is bracketed by a pair of

@@ -65,12 +65,16 @@ _SIGS = {
     "ee_compact_active": (_i, [_vp, _i, _i, _vp]),
     "ee_fill_skipped_kv": (_i, [_vp, _i, _i, _vp, _vp, _vp]),
     "ee_decode_step": (_i, [_vp, _vp, _vp, C.POINTER(C.c_float), _i, _vp]),
+    "ee_cbc_state_bytes": (C.c_size_t, [_i]),
+    "ee_cbc_init": (_i, [_vp, _i, _i, _vp]),
+    "ee_cbc_push": (_i, [_vp, _vp, _i, _vp]),
+    "ee_cbc_push_step": (_i, [_vp, _vp, _vp]),
     "ee_timing_enable": (_i, [_i]),
     "ee_timing_reset": (_i, []),
     "ee_timing_read": (_i, [_i, C.POINTER(_i), C.POINTER(_f)]),
 }
 KERNEL_CLASSES = ["embed", "norm", "gemm_qkv", "rope_append", "attention", "gemm_o", "gemm_gate_up", "gemm_down",
-                  "exit_gemm", "exit_decide", "compact", "fill_kv"]
+                  "exit_gemm", "exit_decide", "compact", "fill_kv", "cbc"]
 
 _lib = None
 

@@ -512,6 +512,30 @@ int ee_fill_skipped_kv(const ee_model* m, int from_layer_excl, int to_layer_incl
                                    : f32_fill_kv(m, from_layer_excl, to_layer_incl, kv, b, as_stream(stream));
 }
 
+size_t ee_cbc_state_bytes(int window) {
+    if (window < 1 || window > EE_CBC_MAX_WINDOW) return 0;
+    return align_up(sizeof(ee_cbc_state) + (size_t)window, 8);
+}
+
+int ee_cbc_init(void* dev_state, int window, int cbc_max, void* stream) {
+    if (!dev_state) return ee_fail(EE_ERR_INVALID_ARG, "ee_cbc_init: null state");
+    if (window < 1 || window > EE_CBC_MAX_WINDOW) return ee_fail(EE_ERR_INVALID_ARG, "ee_cbc_init: window out of range");
+    if (cbc_max < 0) return ee_fail(EE_ERR_INVALID_ARG, "ee_cbc_init: negative cbc_max");
+    return launch_cbc_init(dev_state, window, cbc_max, as_stream(stream));
+}
+
+int ee_cbc_push(void* dev_state, const uint8_t* dev_flags, int n, void* stream) {
+    if (!dev_state || (!dev_flags && n > 0)) return ee_fail(EE_ERR_INVALID_ARG, "ee_cbc_push: null pointer");
+    if (n < 0) return ee_fail(EE_ERR_INVALID_ARG, "ee_cbc_push: negative token count");
+    if (n == 0) return EE_OK;
+    return launch_cbc_push(dev_state, dev_flags, n, as_stream(stream));
+}
+
+int ee_cbc_push_step(void* dev_state, const ee_batch* b, void* stream) {
+    if (!dev_state || !b) return ee_fail(EE_ERR_INVALID_ARG, "ee_cbc_push_step: null pointer");
+    return launch_cbc_push(dev_state, b->st<uint8_t>(b->L.out_breach), b->B, as_stream(stream));
+}
+
 int ee_decode_step(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_thresholds, int n_thresholds,
                    void* stream) {
     int rc = check_pair("ee_decode_step", m, kv, b);

@@ -105,6 +105,8 @@ int launch_reset(ee_batch* b, const int32_t* tok, const int32_t* pos, const floa
 int launch_set_scale(ee_batch* b, const float* scale, hipStream_t s);
 int launch_compact(ee_batch* b, int exit_idx, int exit_layer, hipStream_t s);
 int launch_exit_decide(ee_batch* b, int n_part, float th, int force, hipStream_t s);
+int launch_cbc_init(void* st, int window, int cbc_max, hipStream_t s);
+int launch_cbc_push(void* st, const uint8_t* flags, int n, hipStream_t s);
 int launch_pack_weight(const void* src, int n_out, int n_in, void* dst, int tile_off, int tile_stride,
                        int dst_tile_rows, hipStream_t s);
 int launch_kv_copy_context(const ee_model* m, const ee_kv* kv, int layer, int row, int pos0, int n_pos,

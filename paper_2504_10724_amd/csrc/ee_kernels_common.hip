@@ -197,6 +197,73 @@ int launch_compact(ee_batch* b, int exit_idx, int exit_layer, hipStream_t s) {
     return EE_OK;
 }
 
+// ------------------------------------------------------------------ confidence-breach counter
+// One wave.  The ring of breach bits and the incoming flags are staged in LDS; lane 0 then takes
+// the tokens one by one, exactly as the rule is stated (the work is a few hundred tokens per
+// decode step: the sequential loop costs microseconds once per step).
+__global__ void k_cbc_init(ee_cbc_state* st, int window, int cbc_max) {
+    uint8_t* ring = reinterpret_cast<uint8_t*>(st + 1);
+    for (int j = threadIdx.x; j < window; j += blockDim.x) ring[j] = 0;
+    for (int j = threadIdx.x; j < EE_CBC_LOG; j += blockDim.x) st->trigger_at[j] = 0;
+    if (threadIdx.x == 0) {
+        st->window = window; st->cbc_max = cbc_max;
+        st->head = 0; st->filled = 0; st->count = 0; st->n_triggers = 0; st->tokens_seen = 0;
+    }
+}
+
+#define CBC_CHUNK 1024
+__global__ void __launch_bounds__(64)
+k_cbc_push(ee_cbc_state* st, const uint8_t* __restrict__ flags, int n) {
+    __shared__ uint8_t s_ring[EE_CBC_MAX_WINDOW];
+    __shared__ uint8_t s_flag[CBC_CHUNK];
+    uint8_t* ring = reinterpret_cast<uint8_t*>(st + 1);
+    const int window = min(max(st->window, 1), EE_CBC_MAX_WINDOW);
+    const int cbc_max = st->cbc_max;
+    for (int j = threadIdx.x; j < window; j += 64) s_ring[j] = ring[j];
+    int head = st->head, filled = st->filled, count = st->count, n_trig = st->n_triggers;
+    int64_t seen = st->tokens_seen;
+    for (int base = 0; base < n; base += CBC_CHUNK) {
+        const int m = min(CBC_CHUNK, n - base);
+        __syncthreads();                                  // the previous chunk has been consumed
+        for (int j = threadIdx.x; j < m; j += 64) s_flag[j] = flags[base + j] ? 1 : 0;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int j = 0; j < m; ++j) {
+                const int f = s_flag[j];
+                ++seen;
+                if (filled == window) count -= s_ring[head];   // the oldest token leaves the window
+                else ++filled;
+                s_ring[head] = (uint8_t)f;
+                count += f;
+                head = head + 1 == window ? 0 : head + 1;
+                if (count > cbc_max) {                         // re-assessment: the window starts empty
+                    if (n_trig < EE_CBC_LOG) st->trigger_at[n_trig] = seen;
+                    ++n_trig;
+                    head = 0; filled = 0; count = 0;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    for (int j = threadIdx.x; j < window; j += 64) ring[j] = s_ring[j];
+    if (threadIdx.x == 0) {
+        st->head = head; st->filled = filled; st->count = count; st->n_triggers = n_trig; st->tokens_seen = seen;
+    }
+}
+
+int launch_cbc_init(void* st, int window, int cbc_max, hipStream_t s) {
+    hipLaunchKernelGGL(k_cbc_init, dim3(1), dim3(256), 0, s, (ee_cbc_state*)st, window, cbc_max);
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
+int launch_cbc_push(void* st, const uint8_t* flags, int n, hipStream_t s) {
+    TimedScope t(EE_K_CBC, s);
+    hipLaunchKernelGGL(k_cbc_push, dim3(1), dim3(64), 0, s, (ee_cbc_state*)st, flags, n);
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
 // ------------------------------------------------------------------ weight repacking
 // one thread per 8-value chunk of the packed matrix
 __global__ void k_pack_weight(const bf16_t* __restrict__ src, int n_out, int n_in, bf16_t* __restrict__ dst,

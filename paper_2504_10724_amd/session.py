@@ -243,6 +243,41 @@ def decode_step(model, kv, batch, thresholds):
     return model.lib.ee_decode_step(model.h, kv.h, batch.h, th, len(thresholds), _stream())
 
 
+class BreachCounter:
+    """Device-resident confidence-breach counter (window of the most recent tokens, re-assessment
+    when more than cbc_max of them stopped below their threshold)."""
+    HEADER_INT32 = 6          # window, cbc_max, head, filled, count, n_triggers
+    LOG = 64
+
+    def __init__(self, lib, window=100, cbc_max=50):
+        self.lib = lib
+        nbytes = lib.ee_cbc_state_bytes(window)
+        if nbytes == 0:
+            raise ValueError("window out of range")
+        self.window = window
+        self.state = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+        ee.check(lib.ee_cbc_init(C.c_void_p(self.state.data_ptr()), window, cbc_max, _stream()))
+
+    def push(self, flags):
+        """flags: uint8 device tensor, one entry per token in stream order"""
+        ee.check(self.lib.ee_cbc_push(C.c_void_p(self.state.data_ptr()), C.c_void_p(flags.data_ptr()),
+                                        int(flags.numel()), _stream()))
+
+    def push_step(self, batch):
+        ee.check(self.lib.ee_cbc_push_step(C.c_void_p(self.state.data_ptr()), batch.h, _stream()))
+
+    def read(self):
+        """synchronises; returns dict(count, filled, n_triggers, tokens_seen, trigger_at)"""
+        torch.cuda.current_stream().synchronize()
+        raw = self.state.cpu().numpy()
+        h = raw[:24].view(np.int32)
+        seen = int(raw[24:32].view(np.int64)[0])
+        log = raw[32:32 + 8 * self.LOG].view(np.int64)
+        n = int(h[5])
+        return dict(window=int(h[0]), cbc_max=int(h[1]), filled=int(h[3]), count=int(h[4]), n_triggers=n,
+                    tokens_seen=seen, trigger_at=[int(v) for v in log[:min(n, self.LOG)]])
+
+
 class WindowSwitcher:
     """Host-side routing of one batch between several resident (partially loaded) models in fixed
     windows of decode steps: each model serves one window first, afterwards every window goes to

@@ -1,5 +1,7 @@
 """GPU parity: libee (through the C ABI) against the CPU oracle on the same
 seeded inputs, element by element.  Run with -m gpu on an MI355X."""
+import ctypes as C
+
 import numpy as np
 import pytest
 import torch
@@ -411,3 +413,62 @@ def test_two_model_window_switching():
             break
     assert np.array_equal(gpus[0].batch.field("pos").cpu().numpy(), oracles[0].pos)
     assert np.array_equal(gpus[1].batch.field("pos").cpu().numpy(), oracles[1].pos)
+
+
+# ---------------------------------------------------------------- confidence-breach counter
+def test_breach_counter_matches_the_oracle_on_synthetic_streams():
+    """Integer work: every field bit-exact against oracle/ee_cbc.py, fed in uneven pieces."""
+    from oracle.ee_cbc import CBC
+    lib = ee.load()
+    rng = np.random.default_rng(11)
+    for window, cbc_max, p, total in ((100, 50, 0.5, 6000), (100, 50, 0.62, 6000), (10, 3, 0.4, 3000), (7, 0, 0.1, 500),
+                                      (1, 0, 0.5, 300), (64, 63, 0.99, 2000), (4096, 100, 0.05, 9000), (100, 50, 1.0, 3000)):
+        _say(f"[case] cbc window={window} max={cbc_max} p={p}")
+        flags = (rng.random(total) < p).astype(np.uint8)
+        o = CBC(window, cbc_max)
+        g = S.BreachCounter(lib, window, cbc_max)
+        dev = torch.from_numpy(flags).cuda()
+        at = 0
+        while at < total:
+            n = int(rng.choice([1, 3, 64, 256, 300, 1024, 1500]))
+            n = min(n, total - at)
+            o.push(flags[at:at + n])
+            g.push(dev[at:at + n])
+            at += n
+            if rng.random() < 0.3:
+                r = g.read()
+                assert (r["count"], r["filled"], r["n_triggers"], r["tokens_seen"]) == \
+                       (o.count, len(o.recent), len(o.triggers), o.tokens_seen)
+        r = g.read()
+        assert (r["count"], r["filled"], r["n_triggers"], r["tokens_seen"]) == (o.count, len(o.recent), len(o.triggers), o.tokens_seen)
+        assert r["trigger_at"] == o.triggers[:64]
+
+
+def test_breach_counter_after_decode_steps_with_forced_breaches():
+    """Thresholds above 1 make every token a breach at the last resident layer, thresholds of 0 none:
+    flags that both sides agree on whatever the rounding."""
+    from oracle.ee_cbc import CBC
+    s = MHA.with_(steps=6)
+    _say(f"[case] cbc after decode steps {s.name}")
+    o, g = _fresh(s, jitter=0.0)
+    cb = S.BreachCounter(g.model.lib, 100, 50)
+    oc = CBC(100, 50)
+    for t, th in enumerate([(2.0, 2.0), (0.0, 0.0), (2.0, 2.0), (2.0, 2.0), (0.0, 0.0), (2.0, 2.0)]):
+        r = g.step(t, thresholds=th)
+        cb.push_step(g.batch)
+        oc.push([1 if th[0] > 1 else 0] * s.batch)
+        assert r["breach"].all() == (th[0] > 1)
+    got = cb.read()
+    assert (got["count"], got["filled"], got["n_triggers"], got["tokens_seen"]) == (oc.count, len(oc.recent), len(oc.triggers), oc.tokens_seen)
+    assert got["trigger_at"] == oc.triggers and got["n_triggers"] >= 1
+
+
+def test_breach_counter_rejects_bad_arguments():
+    lib = ee.load()
+    assert lib.ee_cbc_state_bytes(0) == 0 and lib.ee_cbc_state_bytes(4097) == 0 and lib.ee_cbc_state_bytes(100) >= 24 + 8 + 512 + 100
+    buf = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+    assert lib.ee_cbc_init(None, 100, 50, None) == ee.EE_ERR_INVALID_ARG
+    assert lib.ee_cbc_init(C.c_void_p(buf.data_ptr()), 0, 50, None) == ee.EE_ERR_INVALID_ARG
+    assert lib.ee_cbc_init(C.c_void_p(buf.data_ptr()), 100, -1, None) == ee.EE_ERR_INVALID_ARG
+    assert lib.ee_cbc_push(C.c_void_p(buf.data_ptr()), None, 5, None) == ee.EE_ERR_INVALID_ARG
+    assert lib.ee_cbc_push(C.c_void_p(buf.data_ptr()), None, 0, None) == 0
