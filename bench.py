@@ -156,13 +156,22 @@ def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
         return out
 
     # warmup from the start state, then rewind and time exactly `steps` steps.  Event pairs
-    # cost stream time, so the timed region brackets only the two kernels that can be the
-    # dominant one (their launch durations feed the roofline); the table of all kernel
-    # classes comes from a second, untimed pass over the same steps.
-    heavy = (1 << ee.KERNEL_CLASSES.index("attention")) | (1 << ee.KERNEL_CLASSES.index("gemm_gate_up"))
+    # cost stream time, so the timed region brackets only the dominant kernel (its launch
+    # durations feed the roofline; the warm-up steps decide between attention and the gate/up
+    # GEMM); the table of all kernel classes comes from a second, untimed pass over the same steps.
+    heavy_names = ["attention", "gemm_gate_up"]
+    heavy = sum(1 << ee.KERNEL_CLASSES.index(n) for n in heavy_names)
     batch.reset(tok0, ctx.astype(np.int32), None)
+    lib.ee_timing_reset()
+    lib.ee_timing_enable(heavy)          # the warm-up tells which of the two is the dominant kernel ...
     run(args.warmup, 0)
     torch.cuda.synchronize()
+    lib.ee_timing_enable(0)
+    dominant_heavy = None
+    if args.warmup > 0:
+        warm = read_classes()
+        dominant_heavy = max(heavy_names, key=lambda n: warm[n]["total_ms"])
+        heavy = 1 << ee.KERNEL_CLASSES.index(dominant_heavy)   # ... and only that one is bracketed below
     batch.reset(tok0, ctx.astype(np.int32), None)
     lib.ee_timing_reset()
     lib.ee_timing_enable(heavy)
@@ -193,8 +202,9 @@ def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
     lib.ee_timing_enable(0)
     cbc_state = cbc.read()
     kern = read_classes()
-    for name in ("attention", "gemm_gate_up"):
-        kern[name] = timed_kern[name]            # the durations measured inside the timed region
+    for name in heavy_names:
+        if timed_kern[name]["launches"] > 0:
+            kern[name] = timed_kern[name]        # the durations measured inside the timed region
 
     # rows that ran each layer, from the exit histogram (average per step)
     exits = s.resident_exits
@@ -216,7 +226,7 @@ def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
     at_bytes = rows_live * mean_pos * kv_bytes_token
     at_t = at["total_ms"] / max(1, at["launches"]) / max(live_frac, 1e-9) * 1e-3
     layer_kernels = ["norm", "gemm_qkv", "rope_append", "attention", "gemm_o", "gemm_gate_up", "gemm_down"]
-    dominant = max(layer_kernels, key=lambda k: kern[k]["total_ms"])
+    dominant = dominant_heavy or max(layer_kernels, key=lambda k: kern[k]["total_ms"])   # the kernel bracketed above
     if dominant == "attention":
         roof = dict(kernel="k_bf16_attn", bound="hbm", achieved=at_bytes / at_t / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
                     traffic=None)
