@@ -444,4 +444,29 @@ int orc_vanilla_step(const orc_model* m, orc_kv* kv, const int32_t* tok_in, int3
     return ORC_OK;
 }
 
+int orc_prefill(const orc_model* m, orc_kv* kv, int b, const int32_t* tok, int n, int32_t pos0,
+                float* h_out) {
+    if (!m || !kv || !tok || n < 0 || b < 0 || b >= kv->B || pos0 < 0) return ORC_ERR_ARG;
+    if (m->rope_theta == 0.0) return ORC_ERR_ARG;
+    int R = orc_model_resident_depth(m);
+    if (R < 1) return ORC_ERR_ARG;
+    if ((int64_t)pos0 + n > kv->cap || (int64_t)pos0 + n > m->max_pos) return ORC_ERR_ARG;
+    int d = m->cfg.d_model;
+    std::vector<float> H((size_t)n * d);
+    for (int t = 0; t < n; ++t) {
+        int rc = orc_embed(m, tok[t], &H[(size_t)t * d]);
+        if (rc != ORC_OK) return rc;
+    }
+    // all positions through layer l before any enters layer l + 1; within the layer in
+    // rising position order, so the cache holds exactly positions 0 .. pos0+t when
+    // position pos0+t attends: that is the causal mask
+    for (int l = 1; l <= R; ++l)
+        for (int t = 0; t < n; ++t) {
+            int rc = layer_forward_row(m, l, kv, b, pos0 + t, &H[(size_t)t * d]);
+            if (rc != ORC_OK) return rc;
+        }
+    if (h_out) std::memcpy(h_out, H.data(), sizeof(float) * H.size());
+    return ORC_OK;
+}
+
 }  // extern "C"

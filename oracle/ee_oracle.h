@@ -134,6 +134,17 @@ int orc_decode_step(const orc_model* m, orc_kv* kv, const int32_t* tok_in, int32
 int orc_vanilla_step(const orc_model* m, orc_kv* kv, const int32_t* tok_in, int32_t* pos,
                      const float* scale, int32_t* out_tok, float* out_conf, float* h_out);
 
+/* Context pass ("prefill", the work that bounds the time to first token: Sec. 4.4,
+ * Appendix E.1) of row b on the resident layers 1..R: the n tokens tok[0..n)
+ * take positions pos0 .. pos0+n-1 (positions below pos0 must already be
+ * cached).  Layer by layer over the whole context; within a layer position
+ * pos0+t attends to positions 0 .. pos0+t only (causal), and its K, V are
+ * appended.  No exit head runs: every context token passes all R layers, so
+ * that a later token at any depth finds complete keys and values (Sec. 2.2).
+ * h_out (nullable, [n][d]): hidden states after layer R. */
+int orc_prefill(const orc_model* m, orc_kv* kv, int b, const int32_t* tok, int n, int32_t pos0,
+                float* h_out);
+
 #ifdef __cplusplus
 }
 #endif

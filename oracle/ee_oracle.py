@@ -250,3 +250,13 @@ def vanilla_step(model, kv, tok_in, pos, scale, want_h=False):
     rc = lib().orc_vanilla_step(model.h, C.byref(s), _p(tok_in), _p(pos), _p(sc), _p(out_tok),
                                 _p(out_conf), _p(h_out))
     return dict(rc=rc, tok=out_tok, conf=out_conf, h=h_out)
+
+
+def prefill(model, kv, b, tokens, pos0=0, want_h=False):
+    """Context pass of row b: tokens take positions pos0 .. pos0+n-1; K, V of every resident
+    layer are appended.  Returns (rc, hidden states after the last resident layer or None)."""
+    tok = np.ascontiguousarray(tokens, dtype=np.int32)
+    h = np.zeros((tok.size, model.cfg.d_model), np.float32) if want_h else None
+    s = kv.struct()
+    rc = lib().orc_prefill(model.h, C.byref(s), int(b), _p(tok), tok.size, int(pos0), _p(h))
+    return rc, h

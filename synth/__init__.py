@@ -179,3 +179,9 @@ def row_scale(s: Shape, step: int, batch=None, lo=0.5, hi=50.0):
     u = g.random(size=B, dtype=np.float64)
     ln = np.log(lo) + u * (np.log(hi) - np.log(lo)) + s.log_scale_shift
     return np.exp(ln).astype(np.float32)
+
+
+def context_tokens(s: Shape, row: int, n: int):
+    """Token ids of the first n context positions of a row (uniform over the vocabulary)."""
+    g = stream(s.seed, f"ctx.tok.{row}")
+    return g.integers(0, s.vocab, size=n, dtype=np.int64).astype(np.int32)
