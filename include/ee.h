@@ -257,6 +257,27 @@ int ee_fill_skipped_kv(const ee_model* m, int from_layer_excl, int to_layer_incl
 int ee_decode_step(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_thresholds,
                    int n_thresholds, void* stream);
 
+/* Context pass ("prefill") on the resident layers 1..R: builds the keys and values that the
+ * decode step reads; its duration is what bounds the time to first token (Sec. 4.4,
+ * Appendix E.1), and with greedy partial loading it runs on R layers only (Sec. 3.3.3).
+ * Entry i < n (device arrays of n int32 each) is token dev_tok[i] at position dev_pos[i] of
+ * cache row dev_seq[i].  Every entry passes all R layers, no exit head runs (a later token
+ * at any depth must find complete keys and values, Sec. 2.2); in each layer the entry's K
+ * and V are appended at its position and it attends to positions 0 .. dev_pos[i] of its
+ * cache row (causal).  Those positions must be in the cache already or be entries of this
+ * same call; several cache rows may be mixed in one call, and a long context is passed in
+ * several calls on one stream, in rising position order.  Two entries with the same (cache
+ * row, position) race.  n <= B of the batch; the cache may have any number of rows.
+ * The call uses the batch's state and workspace: tok_in, pos, active_idx, n_active and h of
+ * rows < n are overwritten (h[i] = entry i's hidden state after layer R), so a batch that
+ * decodes is given its rows again with ee_batch_reset afterwards.  Refusals are reported in
+ * the batch's status word: 1 = a position outside its cache row's capacity or a cache row
+ * that does not exist, 2 = a token outside the vocabulary.  Enqueue-only, like the rest.
+ * Errors: EE_ERR_CAPACITY if n > B or the cache holds fewer than R layers,
+ * EE_ERR_LAYER_NOT_RESIDENT / EE_ERR_INVALID_ARG as for ee_decode_step. */
+int ee_prefill(const ee_model* m, ee_kv* kv, ee_batch* b, const int32_t* dev_tok,
+               const int32_t* dev_pos, const int32_t* dev_seq, int n, void* stream);
+
 /* ------------------------------------------------------------------ confidence-breach counter
  *
  * The serving loop above the decode step re-assesses its choice of model (load more

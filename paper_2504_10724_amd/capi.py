@@ -65,6 +65,7 @@ _SIGS = {
     "ee_compact_active": (_i, [_vp, _i, _i, _vp]),
     "ee_fill_skipped_kv": (_i, [_vp, _i, _i, _vp, _vp, _vp]),
     "ee_decode_step": (_i, [_vp, _vp, _vp, C.POINTER(C.c_float), _i, _vp]),
+    "ee_prefill": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _vp]),
     "ee_cbc_state_bytes": (C.c_size_t, [_i]),
     "ee_cbc_init": (_i, [_vp, _i, _i, _vp]),
     "ee_cbc_push": (_i, [_vp, _vp, _i, _vp]),

@@ -368,6 +368,7 @@ static void lay_workspace(const ee_model* m, int B, WsLayout* W) {
         W->attn_part_bytes = pairs < 512 + 32 * (size_t)c.n_kv_heads ? pairs * 16 * 16 * 130 * 4 : 0;
         W->attn_part = take(W->attn_part_bytes);
         W->attn_order = take(Mpad * 4);
+        W->kv_seq = take(Mpad * 4);
     } else {
         size_t wide = (size_t)c.vocab > 2 * (size_t)c.d_ffn ? (size_t)c.vocab : 2 * (size_t)c.d_ffn;
         W->x = take(Mpad * c.d_model * 4);
@@ -386,6 +387,7 @@ static void lay_workspace(const ee_model* m, int B, WsLayout* W) {
         W->gemm_cnt_ints = 0;   W->gemm_cnt = take(0);
         W->attn_part_bytes = 0; W->attn_part = take(0);
         W->attn_order = take(0);
+        W->kv_seq = take(Mpad * 4);
     }
     W->total = o;
 }
@@ -510,6 +512,37 @@ int ee_fill_skipped_kv(const ee_model* m, int from_layer_excl, int to_layer_incl
     if (from_layer_excl >= to_layer_incl) return EE_OK;
     return m->cfg.dtype == EE_BF16 ? bf16_fill_kv(m, from_layer_excl, to_layer_incl, kv, b, as_stream(stream))
                                    : f32_fill_kv(m, from_layer_excl, to_layer_incl, kv, b, as_stream(stream));
+}
+
+int ee_prefill(const ee_model* m, ee_kv* kv, ee_batch* b, const int32_t* dev_tok, const int32_t* dev_pos,
+               const int32_t* dev_seq, int n, void* stream) {
+    if (!m || !kv || !b) return ee_fail(EE_ERR_INVALID_ARG, "ee_prefill: null handle");
+    if (b->m != m) return ee_fail(EE_ERR_INVALID_ARG, "ee_prefill: batch not bound to this model");
+    if (n < 0 || n > b->B) return ee_fail(EE_ERR_CAPACITY, "ee_prefill: more entries than the batch has rows");
+    if (n == 0) return EE_OK;
+    if (!dev_tok || !dev_pos || !dev_seq) return ee_fail(EE_ERR_INVALID_ARG, "ee_prefill: null array");
+    int R = ee_model_resident_depth(m);
+    if (R < 0) return R;
+    if (R == 0) return ee_fail(EE_ERR_LAYER_NOT_RESIDENT, "ee_prefill: no layer is resident");
+    if (kv->n_layers < R) return ee_fail(EE_ERR_CAPACITY, "ee_prefill: cache was bound for fewer layers than are resident");
+    if (!m->emb) return ee_fail(EE_ERR_INVALID_ARG, "ee_prefill: embedding not set");
+    const ee_model_config& c = m->cfg;
+    hipStream_t s = as_stream(stream);
+    int rc = launch_prefill_begin(m, kv, b, dev_tok, dev_pos, dev_seq, n, s);
+    b->kv_seq = b->wsp<int32_t>(b->W.kv_seq);      // the layers address the cache through the entry's row
+    bool x_ready = false;
+    for (int l = 1; l <= R && rc == EE_OK; ++l) {
+        if (c.dtype == EE_BF16) {
+            const float* tail_gain = l < R ? (const float*)m->layers[l].g_attn : nullptr;
+            bool x_done = false;
+            rc = bf16_layer_forward(m, l, kv, b, s, x_ready, tail_gain, &x_done);
+            x_ready = x_done;
+        } else {
+            rc = f32_layer_forward(m, l, kv, b, s);
+        }
+    }
+    b->kv_seq = nullptr;
+    return rc;
 }
 
 size_t ee_cbc_state_bytes(int window) {

@@ -21,6 +21,9 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
 }
 
 // element offset (in elements of the model dtype) of the (layer, row, kv-head) block
+// cache row that batch row b reads and appends to
+__device__ __forceinline__ int kv_row(const KvView& kv, int b) { return kv.seq ? kv.seq[b] : b; }
+
 __device__ __forceinline__ int64_t kv_block(const KvView& kv, int b, int g, int cap_b) {
     return ((int64_t)kv.layer0 * kv.T + kv.off[b]) * (2LL * kv.n_kv_heads * kv.head_dim) +
            (int64_t)g * 2LL * cap_b * kv.head_dim;

@@ -47,6 +47,7 @@ struct WsLayout {
     size_t gemm_part, gemm_part_bytes, gemm_cnt, gemm_cnt_ints;   // K-slice partial planes
     size_t attn_part, attn_part_bytes;                            // attention position shares
     size_t attn_order;                                            // int32 [Mpad]: list entries, longest context first
+    size_t kv_seq;                                                // int32 [Mpad]: cache row of each entry (context pass)
 };
 
 struct ee_batch {
@@ -57,6 +58,7 @@ struct ee_batch {
     char* ws = nullptr;
     ee_batch_layout L;
     WsLayout W;
+    const int32_t* kv_seq = nullptr;        // device [Mpad], set only while a context pass runs: entry -> cache row
     template <class T> T* st(size_t off) const { return reinterpret_cast<T*>(state + off); }
     template <class T> T* wsp(size_t off) const { return reinterpret_cast<T*>(ws + off); }
 };
@@ -94,6 +96,7 @@ struct KvView {
     int32_t        n_kv_heads;
     int32_t        head_dim;
     int32_t        layer0;   // layer - 1
+    const int32_t* seq;      // device: cache row of a batch row, or null when batch row b owns cache row b
 };
 
 // ----------------------------------------------------------------- launchers
@@ -105,6 +108,8 @@ int launch_reset(ee_batch* b, const int32_t* tok, const int32_t* pos, const floa
 int launch_set_scale(ee_batch* b, const float* scale, hipStream_t s);
 int launch_compact(ee_batch* b, int exit_idx, int exit_layer, hipStream_t s);
 int launch_exit_decide(ee_batch* b, int n_part, float th, int force, hipStream_t s);
+int launch_prefill_begin(const ee_model* m, const ee_kv* kv, ee_batch* b, const int32_t* tok, const int32_t* pos,
+                         const int32_t* seq, int n, hipStream_t s);
 int launch_cbc_init(void* st, int window, int cbc_max, hipStream_t s);
 int launch_cbc_push(void* st, const uint8_t* flags, int n, hipStream_t s);
 int launch_pack_weight(const void* src, int n_out, int n_in, void* dst, int tile_off, int tile_stride,

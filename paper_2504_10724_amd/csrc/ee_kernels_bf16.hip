@@ -653,7 +653,8 @@ k_bf16_rope_append(const float* __restrict__ buf, int ld, int n_q, const int32_t
     }
     const int hd = 128, half = 64;
     int Hkv = kv.n_kv_heads;
-    int cap = kv.cap[b];
+    const int sq = kv_row(kv, b);
+    int cap = kv.cap[sq];
     if (p < 0 || p >= cap || p >= max_pos) {
         if (threadIdx.x == 0) atomicOr(status, 1);
         return;
@@ -687,13 +688,13 @@ k_bf16_rope_append(const float* __restrict__ buf, int ld, int n_q, const int32_t
         int g = t >> 6, j = t & 63;
         float c = cs[2 * j], s = cs[2 * j + 1];
         float a = rd(kin + g * hd + j), bb = rd(kin + g * hd + j + half);
-        bf16_t* base = reinterpret_cast<bf16_t*>(kv.pool) + kv_block(kv, b, g, cap);
+        bf16_t* base = reinterpret_cast<bf16_t*>(kv.pool) + kv_block(kv, sq, g, cap);
         base[k_bf16_offset(p, j)] = f32_to_bf16(a * c - bb * s);
         base[k_bf16_offset(p, j + half)] = f32_to_bf16(bb * c + a * s);
     }
     for (int t = t0; t < Hkv * hd; t += tstep) {
         int g = t >> 7, j = t & 127;
-        bf16_t* base = reinterpret_cast<bf16_t*>(kv.pool) + kv_block(kv, b, g, cap);
+        bf16_t* base = reinterpret_cast<bf16_t*>(kv.pool) + kv_block(kv, sq, g, cap);
         base[(int64_t)cap * hd + v_bf16_offset(p, j, hd)] = f32_to_bf16(rd(vin + g * hd + j));
     }
 }
@@ -722,12 +723,13 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
     if ((int)blockIdx.y >= n) return;
     const int i = order[blockIdx.y];       // longest contexts first
     const int b = idx[i];
-    const int cap = kv.cap[b];
+    const int sq = kv_row(kv, b);
+    const int cap = kv.cap[sq];
     const int n_pos = max(1, min(pos[b] + 1, cap));
     const int G = Hq / kv.n_kv_heads;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int n16 = lane & 15, gq = lane >> 4;
-    const bf16_t* Kb = reinterpret_cast<const bf16_t*>(kv.pool) + kv_block(kv, b, g, cap);
+    const bf16_t* Kb = reinterpret_cast<const bf16_t*>(kv.pool) + kv_block(kv, sq, g, cap);
     const bf16_t* Vb = Kb + (int64_t)cap * 128;
 
     bf16x8 qh[4], ql[4];
@@ -898,8 +900,8 @@ k_bf16_attn_merge(const float* __restrict__ part, int Hq, int Hkv, int n_splits,
 }
 
 // ------------------------------------------------------------------ host side
-static KvView make_view(const ee_model* m, const ee_kv* kv, int layer) {
-    return KvView{kv->pool, kv->d_cap, kv->d_off, kv->T, m->cfg.n_kv_heads, m->cfg.head_dim, layer - 1};
+static KvView make_view(const ee_model* m, const ee_kv* kv, int layer, const ee_batch* b) {
+    return KvView{kv->pool, kv->d_cap, kv->d_off, kv->T, m->cfg.n_kv_heads, m->cfg.head_dim, layer - 1, b->kv_seq};
 }
 
 template <int MS, int NS, int WK, int WN, int EPI>
@@ -1061,7 +1063,7 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
     float* qkv = b->wsp<float>(b->W.qkv);
     uint4* ao = b->wsp<uint4>(b->W.ao);
     bf16_t* act = b->wsp<bf16_t>(b->W.act);
-    KvView view = make_view(m, kv, layer);
+    KvView view = make_view(m, kv, layer, b);
 
     if (!x_ready) {
         TimedScope t(EE_K_NORM, s);
@@ -1183,7 +1185,7 @@ int bf16_fill_kv(const ee_model* m, int from_excl, int to_incl, ee_kv* kv, ee_ba
     if (!gemm_tiled<EPI_STORE>(b, x, nullptr, kv_n, d, NBs, nb_off, n_ptr, B, ep, s, zb, nl))
         gemm<1, EPI_STORE>(x, nullptr, kv_n, d, NBs, nb_off, n_ptr, B, ep, s, zb, nl);
     hipLaunchKernelGGL(k_bf16_rope_append, dim3(B, 1, nl), dim3(256), 0, s, kvb, kv_n, 0, idx, n_ptr, B,
-                       b->st<int32_t>(L.pos), m->d_rope, c.max_pos, make_view(m, kv, from_excl + 1),
+                       b->st<int32_t>(L.pos), m->d_rope, c.max_pos, make_view(m, kv, from_excl + 1, b),
                        (bf16_t*)nullptr, (bf16_t*)nullptr, b->st<int32_t>(L.status), zb.out_stride,
                        (int32_t*)nullptr, 1, (int64_t)0);
     EE_LAUNCH_CHECK();

@@ -63,6 +63,58 @@ int launch_begin_step(const ee_model* m, ee_batch* b, hipStream_t s) {
     return EE_OK;
 }
 
+// Context pass: entry i < n is token tok[i] at position pos[i] of cache row seq[i].  It becomes
+// batch row i: active, its residual stream the token's embedding.  An entry whose cache row
+// does not exist gets position -1, which the append kernel refuses (status bit 1), and cache
+// row 0, so that every later address stays inside the pool.
+__global__ void __launch_bounds__(256)
+k_prefill_begin(const int32_t* __restrict__ tok, const int32_t* __restrict__ pos, const int32_t* __restrict__ seq,
+                int n, int n_seq, const void* __restrict__ emb, int is_bf16, int d, int V, float* __restrict__ h,
+                int32_t* __restrict__ s_tok, int32_t* __restrict__ s_pos, int32_t* __restrict__ kv_seq,
+                int32_t* __restrict__ active_idx, int32_t* __restrict__ n_active, int32_t* __restrict__ n_exited,
+                int32_t* __restrict__ status) {
+    int i = blockIdx.x;
+    if (i >= n) return;
+    int t = tok[i], p = pos[i], sq = seq[i];
+    if (t < 0 || t >= V) {
+        if (threadIdx.x == 0) atomicOr(status, 2);
+        t = 0;
+    }
+    if (sq < 0 || sq >= n_seq) {
+        if (threadIdx.x == 0) atomicOr(status, 1);
+        sq = 0;
+        p = -1;
+    }
+    if (threadIdx.x == 0) {
+        s_tok[i] = t;
+        s_pos[i] = p;
+        kv_seq[i] = sq;
+        active_idx[i] = i;
+        if (i == 0) { *n_active = n; *n_exited = 0; }
+    }
+    float* hr = h + (int64_t)i * d;
+    if (is_bf16) {
+        const bf16_t* e = (const bf16_t*)emb + (int64_t)t * d;
+        for (int j = threadIdx.x; j < d; j += blockDim.x) hr[j] = bf16_to_f32(e[j]);
+    } else {
+        const float* e = (const float*)emb + (int64_t)t * d;
+        for (int j = threadIdx.x; j < d; j += blockDim.x) hr[j] = e[j];
+    }
+}
+
+int launch_prefill_begin(const ee_model* m, const ee_kv* kv, ee_batch* b, const int32_t* tok, const int32_t* pos,
+                         const int32_t* seq, int n, hipStream_t s) {
+    const ee_batch_layout& L = b->L;
+    TimedScope t(EE_K_EMBED, s);
+    hipLaunchKernelGGL(k_prefill_begin, dim3(n), dim3(256), 0, s, tok, pos, seq, n, kv->B, m->emb,
+                       m->cfg.dtype == EE_BF16 ? 1 : 0, m->cfg.d_model, m->cfg.vocab, b->st<float>(L.h),
+                       b->st<int32_t>(L.tok_in), b->st<int32_t>(L.pos), b->wsp<int32_t>(b->W.kv_seq),
+                       b->st<int32_t>(L.active_idx), b->st<int32_t>(L.n_active), b->st<int32_t>(L.n_exited),
+                       b->st<int32_t>(L.status));
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
 // every row advances one position, whatever layer it left at, and the token it
 // emitted is the input of the next step
 __global__ void k_end_step(int32_t* __restrict__ pos, int32_t* __restrict__ tok_in,
@@ -316,7 +368,7 @@ __global__ void k_kv_copy(KvView kv, int row, int pos0, int n_pos, T* __restrict
 
 int launch_kv_copy_context(const ee_model* m, const ee_kv* kv, int layer, int row, int pos0, int n_pos,
                            void* k, void* v, bool to_pool, hipStream_t s) {
-    KvView view{kv->pool, kv->d_cap, kv->d_off, kv->T, m->cfg.n_kv_heads, m->cfg.head_dim, layer - 1};
+    KvView view{kv->pool, kv->d_cap, kv->d_off, kv->T, m->cfg.n_kv_heads, m->cfg.head_dim, layer - 1, nullptr};
     int64_t total = (int64_t)m->cfg.n_kv_heads * n_pos * m->cfg.head_dim;
     if (total == 0) return EE_OK;
     dim3 grid((unsigned)((total + 255) / 256)), block(256);

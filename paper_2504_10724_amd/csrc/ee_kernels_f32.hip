@@ -73,7 +73,8 @@ k_f32_rope_append(float* __restrict__ buf, int ld, int n_q, const int32_t* __res
     int b = idx[i];
     int p = pos[b];
     int hd = kv.head_dim, half = hd >> 1, Hkv = kv.n_kv_heads;
-    int cap = kv.cap[b];
+    const int sq = kv_row(kv, b);
+    int cap = kv.cap[sq];
     bool ok = p >= 0 && p < cap && p < max_pos;
     if (!ok) {
         if (threadIdx.x == 0) atomicOr(status, 1);
@@ -94,13 +95,13 @@ k_f32_rope_append(float* __restrict__ buf, int ld, int n_q, const int32_t* __res
         int g = t / half, j = t % half;
         float c = cs[2 * j], s = cs[2 * j + 1];
         float a = kin[g * hd + j], bb = kin[g * hd + j + half];
-        float* base = reinterpret_cast<float*>(kv.pool) + kv_block(kv, b, g, cap);
+        float* base = reinterpret_cast<float*>(kv.pool) + kv_block(kv, sq, g, cap);
         base[(int64_t)p * hd + j] = a * c - bb * s;
         base[(int64_t)p * hd + j + half] = bb * c + a * s;
     }
     for (int t = threadIdx.x; t < Hkv * hd; t += 256) {
         int g = t / hd, j = t % hd;
-        float* base = reinterpret_cast<float*>(kv.pool) + kv_block(kv, b, g, cap);
+        float* base = reinterpret_cast<float*>(kv.pool) + kv_block(kv, sq, g, cap);
         base[(int64_t)cap * hd + (int64_t)p * hd + j] = vin[g * hd + j];
     }
 }
@@ -118,10 +119,11 @@ k_f32_attn(const float* __restrict__ qkv, int ld, int Hq, const int32_t* __restr
     if (i >= n) return;
     int b = idx[i];
     int hd = kv.head_dim;
-    int cap = kv.cap[b];
+    const int sq = kv_row(kv, b);
+    int cap = kv.cap[sq];
     int n_pos = min(pos[b] + 1, cap);
     int g = hq / (Hq / kv.n_kv_heads);
-    const float* Kb = reinterpret_cast<const float*>(kv.pool) + kv_block(kv, b, g, cap);
+    const float* Kb = reinterpret_cast<const float*>(kv.pool) + kv_block(kv, sq, g, cap);
     const float* Vb = Kb + (int64_t)cap * hd;
     float* q = sm;
     float* sc = sm + hd;
@@ -192,8 +194,8 @@ k_f32_row_stats(const float* __restrict__ logits, int V, const int32_t* __restri
 }
 
 // ------------------------------------------------------------------ host side
-static KvView make_view(const ee_model* m, const ee_kv* kv, int layer) {
-    return KvView{kv->pool, kv->d_cap, kv->d_off, kv->T, m->cfg.n_kv_heads, m->cfg.head_dim, layer - 1};
+static KvView make_view(const ee_model* m, const ee_kv* kv, int layer, const ee_batch* b) {
+    return KvView{kv->pool, kv->d_cap, kv->d_off, kv->T, m->cfg.n_kv_heads, m->cfg.head_dim, layer - 1, b->kv_seq};
 }
 
 template <int EPI>
@@ -217,7 +219,7 @@ int f32_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hipS
     float* ao = b->wsp<float>(b->W.ao);
     float* act = b->wsp<float>(b->W.act);
     float* gu = b->wsp<float>(b->W.logits);   // [B][2F] fits: checked when the workspace is laid out
-    KvView view = make_view(m, kv, layer);
+    KvView view = make_view(m, kv, layer, b);
 
     hipLaunchKernelGGL(k_f32_rmsnorm, dim3(B), dim3(256), 0, s, h, idx, n_ptr, B, w.g_attn, c.rms_eps, d, x);
     gemm<F32_EPI_STORE>(x, d, (const float*)w.w_qkv, qkv_n, d, n_ptr, B, qkv, qkv_n, idx, nullptr, s);
@@ -270,7 +272,7 @@ int f32_fill_kv(const ee_model* m, int from_excl, int to_incl, ee_kv* kv, ee_bat
         const float* Wkv = (const float*)w.w_qkv + (int64_t)c.n_q_heads * hd * d;
         gemm<F32_EPI_STORE>(x, d, Wkv, kv_n, d, n_ptr, B, kvb, kv_n, idx, nullptr, s);
         hipLaunchKernelGGL(k_f32_rope_append, dim3(B), dim3(256), 0, s, kvb, kv_n, 0, idx, n_ptr, B,
-                           b->st<int32_t>(L.pos), m->d_rope, c.max_pos, make_view(m, kv, l),
+                           b->st<int32_t>(L.pos), m->d_rope, c.max_pos, make_view(m, kv, l, b),
                            b->st<int32_t>(L.status));
     }
     EE_LAUNCH_CHECK();

@@ -243,6 +243,41 @@ def decode_step(model, kv, batch, thresholds):
     return model.lib.ee_decode_step(model.h, kv.h, batch.h, th, len(thresholds), _stream())
 
 
+def _i32_device(a):
+    if isinstance(a, torch.Tensor):
+        assert a.is_cuda and a.dtype == torch.int32 and a.is_contiguous()
+        return a
+    return torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def prefill(model, kv, batch, tok, pos, seq):
+    """One ee_prefill call: entry i is token tok[i] at position pos[i] of cache row seq[i]
+    (int32 arrays of equal length, numpy or device tensors)."""
+    t, p, q = _i32_device(tok), _i32_device(pos), _i32_device(seq)
+    assert t.numel() == p.numel() == q.numel()
+    return model.lib.ee_prefill(model.h, kv.h, batch.h, _ptr(t), _ptr(p), _ptr(q), int(t.numel()), _stream())
+
+
+def prefill_chunks(contexts, rows_per_call):
+    """Splits contexts {cache row: token ids} into the argument lists of successive ee_prefill
+    calls of at most rows_per_call entries: cache rows in the order given, positions rising, a
+    context that does not fit the call continues in the next one.  Yields (tok, pos, seq)."""
+    tok, pos, seq = [], [], []
+    for row, toks in contexts.items():
+        done = 0
+        while done < len(toks):
+            take = min(len(toks) - done, rows_per_call - len(tok))
+            tok.extend(int(x) for x in toks[done:done + take])
+            pos.extend(range(done, done + take))
+            seq.extend([int(row)] * take)
+            done += take
+            if len(tok) == rows_per_call:
+                yield (np.array(tok, np.int32), np.array(pos, np.int32), np.array(seq, np.int32))
+                tok, pos, seq = [], [], []
+    if tok:
+        yield (np.array(tok, np.int32), np.array(pos, np.int32), np.array(seq, np.int32))
+
+
 class BreachCounter:
     """Device-resident confidence-breach counter (window of the most recent tokens, re-assessment
     when more than cbc_max of them stopped below their threshold)."""
