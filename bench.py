@@ -259,6 +259,41 @@ def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
     return res
 
 
+def run_context_pass(s, model, torch, S, ee, synth, entries_per_call, n_ctx=8, ctx_len=1024):
+    """Context pass (ee_prefill) over n_ctx contexts of ctx_len tokens on the resident layers, in calls of
+    entries_per_call entries: tokens/s with the token, position and cache-row arrays resident in HBM.
+    Outside the timed decode region; reported in `detail` only."""
+    lib = model.lib
+    ctx_len = min(ctx_len, model.cfg.max_pos // 32 * 32)
+    kv = S.KVCache(model, s.resident, np.full(n_ctx, ctx_len, np.int32))
+    pb = S.Batch(model, entries_per_call)
+    zero = np.zeros(entries_per_call, np.int32)
+    pb.reset(zero, zero, None)
+    contexts = {r: synth.context_tokens(s, r, ctx_len) for r in range(n_ctx)}
+    calls = [tuple(torch.as_tensor(a).cuda() for a in c) for c in S.prefill_chunks(contexts, entries_per_call)]
+
+    def run():
+        for tok, pos, seq in calls:
+            rc = S.prefill(model, kv, pb, tok, pos, seq)
+            if rc != 0:
+                raise ee.EEError(rc, lib.ee_last_error().decode())
+    run()                                  # warm-up: the same pass once
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert int(pb.field("status").cpu()[0]) == 0, "device status flag set"
+    tokens = n_ctx * ctx_len
+    flops = 2.0 * tokens * s.resident * s.layer_params()      # the four products of each layer; attention not counted
+    res = dict(entries_per_call=entries_per_call, contexts=n_ctx, tokens_per_context=ctx_len, calls=len(calls),
+               ms=dt * 1e3, tokens_per_s=tokens / dt, gemm_tflops=flops / dt / 1e12,
+               mfma_frac=flops / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS)
+    del pb, kv
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -269,6 +304,9 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer resident layers (not a valid result)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the smaller batch sizes of the sweep")
+    ap.add_argument("--no-context-pass", action="store_true", help="skip the context-pass (ee_prefill) measurement")
+    ap.add_argument("--context-pass-only", type=int, nargs="*", default=None, metavar="ENTRIES",
+                    help="only time the context pass (ee_prefill) with these numbers of entries per call")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy 4 times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -304,6 +342,10 @@ def main():
     total_steps = args.steps + args.warmup
     max_cap = int(synth.capacity_for(np.array([s.ctx_hi]), max(total_steps, s.steps), 32)[0])
     model = build_device_model(s, S, torch, max_cap, s.seed)
+    if args.context_pass_only is not None:
+        for n in (args.context_pass_only or [256]):
+            print(json.dumps(run_context_pass(s, model, torch, S, ee, synth, n)), flush=True)
+        return
     head = run_workload(s, model, args, torch, S, ee, synth, C)
     sweep = {}
     if not args.no_sweep and not args.batch:
@@ -312,6 +354,7 @@ def main():
             sweep[str(b)] = {k: r[k] for k in ("tokens_per_s", "ms_per_step", "exit_fractions", "avg_layers_per_token",
                                                "gate_up_gemm", "attention", "layer_gemms",
                                                "exit_head_plus_compaction_us_per_step")}
+    context_pass = None if args.no_context_pass else run_context_pass(s, model, torch, S, ee, synth, 256)
     exits = s.resident_exits
     out = dict(metric="decoded tokens/s/GPU at Llama2-70B shape", value=head["tokens_per_s"], unit="tokens/s", n_gpus=1,
                steps=args.steps, warmup=args.warmup, ms_per_step=head["ms_per_step"], higher_is_better=True,
@@ -323,6 +366,7 @@ def main():
                detail={k: head[k] for k in ("avg_layers_per_token", "avg_active_rows", "live_layer_launches", "gate_up_gemm", "attention",
                                             "layer_gemms", "exit_head_plus_compaction_us_per_step", "breach_counter", "kernels_ms")},
                batch_sweep=sweep)
+    out["detail"]["context_pass"] = context_pass
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(s, head["counts"])
     print(json.dumps(out))
