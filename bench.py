@@ -194,13 +194,16 @@ def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
     lib.ee_timing_enable((1 << len(ee.KERNEL_CLASSES)) - 1)
     live_launches = 0          # layer launches that still had a row (the others return at once)
     cbc = S.BreachCounter(lib)  # the device-side confidence-breach counter, fed after every step
+    pht = S.PhtRow(model)       # and the Performance History Table row (exit profile, perplexity)
     for t in range(args.steps):
         run(1, t)
         cbc.push_step(batch)
+        pht.push_step(batch)
         torch.cuda.synchronize()
         live_launches += int(f("out_layer").max())
     lib.ee_timing_enable(0)
     cbc_state = cbc.read()
+    pht_row = pht.read()
     kern = read_classes()
     for name in heavy_names:
         if timed_kern[name]["launches"] > 0:
@@ -252,7 +255,10 @@ def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
                                                kern["compact"]["total_ms"]) * 1e3 / args.steps,
         kernels_ms=kern, roofline=roof, counts=counts.tolist(),
         breach_counter=dict(update_us_per_step=kern["cbc"]["total_ms"] * 1e3 / args.steps,
-                            reassessments=cbc_state["n_triggers"], tokens=cbc_state["tokens_seen"]))
+                            reassessments=cbc_state["n_triggers"], tokens=cbc_state["tokens_seen"]),
+        pht_row=dict(update_us_per_step=kern["pht"]["total_ms"] * 1e3 / args.steps, tokens=pht_row["tokens"],
+                     exits=pht_row["exits"][:len(exits)], breaches=pht_row["breaches"],
+                     perplexity=float(np.exp(pht_row["nll"] / max(1, pht_row["tokens"])))))
     res["layer_gemms"]["hbm_frac"] = res["layer_gemms"]["hbm_gbs"] / HBM_PEAK_GBS
     del batch, kv
     torch.cuda.empty_cache()
@@ -364,7 +370,7 @@ def main():
                            batch=s.batch, ctx=[s.ctx_lo, s.ctx_hi], valid_config=valid),
                exit_fractions=head["exit_fractions"], roofline=head["roofline"],
                detail={k: head[k] for k in ("avg_layers_per_token", "avg_active_rows", "live_layer_launches", "gate_up_gemm", "attention",
-                                            "layer_gemms", "exit_head_plus_compaction_us_per_step", "breach_counter", "kernels_ms")},
+                                            "layer_gemms", "exit_head_plus_compaction_us_per_step", "breach_counter", "pht_row", "kernels_ms")},
                batch_sweep=sweep)
     out["detail"]["context_pass"] = context_pass
     if not args.no_cpu_baseline:

@@ -316,6 +316,31 @@ int ee_cbc_push(void* dev_state, const uint8_t* dev_flags, int n, void* stream);
 /* Feeds the tokens of the decode step that just ran on this batch: out_breach[0 .. B). */
 int ee_cbc_push_step(void* dev_state, const ee_batch* b, void* stream);
 
+/* ------------------------------------------------------------------ Performance History Table row
+ *
+ * The serving loop keeps, per model, the early-exit profile (how many tokens left at each
+ * exit), the accuracy estimate and the throughput of the requests it served (Sec. 3.3.2,
+ * "Performance History Table"); accuracy is the perplexity of the generated tokens, taken from
+ * the token probabilities alone (Sec. 4.4, Appendix A).  This row accumulates the device-side
+ * part after each decode step, so that the host reads one small struct per window instead of
+ * the per-row outputs of every step: tokens, exits[e] (e indexes ee_model_config.exit_layers),
+ * breaches, and nll = sum of -ln p over the tokens, p = out_conf = the probability the exit head
+ * gave the emitted token; perplexity = exp(nll / tokens).  Throughput is tokens over the wall time
+ * the caller measures.  The sum runs in fp64 in a fixed order (bitwise repeatable).
+ * State: sizeof(ee_pht_row) bytes of device memory owned by the caller, 8-byte aligned. */
+typedef struct {
+    int64_t tokens;
+    int64_t breaches;
+    int64_t exits[EE_MAX_EXITS];
+    double  nll;
+} ee_pht_row;
+/* Zeroes the row (enqueue only). */
+int ee_pht_init(void* dev_row, void* stream);
+/* Adds the B tokens of the decode step that just ran on this batch (out_layer, out_conf,
+ * out_breach); a row whose out_layer is not an exit layer of the model (it has not left) is
+ * skipped.  Enqueue only.  EE_ERR_INVALID_ARG on a null pointer or a batch of another model. */
+int ee_pht_push_step(void* dev_row, const ee_model* m, const ee_batch* b, void* stream);
+
 /* ------------------------------------------------------------------ measurement aid */
 
 /* Kernel classes of the decode step, for ee_timing_read. */
@@ -333,7 +358,8 @@ typedef enum {
     EE_K_COMPACT = 10,
     EE_K_FILL_KV = 11,      /* all kernels of ee_fill_skipped_kv                      */
     EE_K_CBC = 12,          /* confidence-breach counter update                       */
-    EE_K_COUNT = 13
+    EE_K_PHT = 13,          /* Performance History Table row update                   */
+    EE_K_COUNT = 14
 } ee_kernel_class;
 
 /* class_mask: bit k set = every launch of kernel class k is bracketed by a pair of

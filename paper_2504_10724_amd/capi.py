@@ -35,6 +35,11 @@ class ee_batch_layout(C.Structure):
         "out_breach", "exit_counts", "breach_count", "status")]
 
 
+class ee_pht_row(C.Structure):
+    _fields_ = [("tokens", C.c_int64), ("breaches", C.c_int64), ("exits", C.c_int64 * EE_MAX_EXITS),
+                ("nll", C.c_double)]
+
+
 _vp, _i, _sz, _f = C.c_void_p, C.c_int, C.c_size_t, C.c_float
 _SIGS = {
     "ee_last_error": (C.c_char_p, []),
@@ -70,12 +75,14 @@ _SIGS = {
     "ee_cbc_init": (_i, [_vp, _i, _i, _vp]),
     "ee_cbc_push": (_i, [_vp, _vp, _i, _vp]),
     "ee_cbc_push_step": (_i, [_vp, _vp, _vp]),
+    "ee_pht_init": (_i, [_vp, _vp]),
+    "ee_pht_push_step": (_i, [_vp, _vp, _vp, _vp]),
     "ee_timing_enable": (_i, [_i]),
     "ee_timing_reset": (_i, []),
     "ee_timing_read": (_i, [_i, C.POINTER(_i), C.POINTER(_f)]),
 }
 KERNEL_CLASSES = ["embed", "norm", "gemm_qkv", "rope_append", "attention", "gemm_o", "gemm_gate_up", "gemm_down",
-                  "exit_gemm", "exit_decide", "compact", "fill_kv", "cbc"]
+                  "exit_gemm", "exit_decide", "compact", "fill_kv", "cbc", "pht"]
 
 _lib = None
 

@@ -569,6 +569,17 @@ int ee_cbc_push_step(void* dev_state, const ee_batch* b, void* stream) {
     return launch_cbc_push(dev_state, b->st<uint8_t>(b->L.out_breach), b->B, as_stream(stream));
 }
 
+int ee_pht_init(void* dev_row, void* stream) {
+    if (!dev_row) return ee_fail(EE_ERR_INVALID_ARG, "ee_pht_init: null row");
+    return launch_pht_init(dev_row, as_stream(stream));
+}
+
+int ee_pht_push_step(void* dev_row, const ee_model* m, const ee_batch* b, void* stream) {
+    if (!dev_row || !m || !b) return ee_fail(EE_ERR_INVALID_ARG, "ee_pht_push_step: null pointer");
+    if (b->m != m) return ee_fail(EE_ERR_INVALID_ARG, "ee_pht_push_step: batch not bound to this model");
+    return launch_pht_push(dev_row, m, b, as_stream(stream));
+}
+
 int ee_decode_step(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_thresholds, int n_thresholds,
                    void* stream) {
     int rc = check_pair("ee_decode_step", m, kv, b);

@@ -112,6 +112,8 @@ int launch_prefill_begin(const ee_model* m, const ee_kv* kv, ee_batch* b, const 
                          const int32_t* seq, int n, hipStream_t s);
 int launch_cbc_init(void* st, int window, int cbc_max, hipStream_t s);
 int launch_cbc_push(void* st, const uint8_t* flags, int n, hipStream_t s);
+int launch_pht_init(void* row, hipStream_t s);
+int launch_pht_push(void* row, const ee_model* m, const ee_batch* b, hipStream_t s);
 int launch_pack_weight(const void* src, int n_out, int n_in, void* dst, int tile_off, int tile_stride,
                        int dst_tile_rows, hipStream_t s);
 int launch_kv_copy_context(const ee_model* m, const ee_kv* kv, int layer, int row, int pos0, int n_pos,

@@ -316,6 +316,67 @@ int launch_cbc_push(void* st, const uint8_t* flags, int n, hipStream_t s) {
     return EE_OK;
 }
 
+// ------------------------------------------------------------------ Performance History Table row
+__global__ void k_pht_init(ee_pht_row* row) {
+    if (threadIdx.x == 0) { row->tokens = 0; row->breaches = 0; row->nll = 0.0; }
+    if (threadIdx.x < EE_MAX_EXITS) row->exits[threadIdx.x] = 0;
+}
+
+struct ExitLayers { int32_t n; int32_t layer[EE_MAX_EXITS]; };
+
+// One workgroup.  Thread t takes rows t, t + 256, ...; the -ln p partial sums are added in a
+// fixed tree order in fp64, so the result does not depend on scheduling.
+__global__ void __launch_bounds__(256)
+k_pht_push(ee_pht_row* row, const int32_t* __restrict__ out_layer, const float* __restrict__ out_conf,
+           const uint8_t* __restrict__ out_breach, int B, ExitLayers ex) {
+    __shared__ int s_cnt[EE_MAX_EXITS + 2];
+    __shared__ double s_sum[256];
+    if (threadIdx.x < EE_MAX_EXITS + 2) s_cnt[threadIdx.x] = 0;
+    __syncthreads();
+    double acc = 0.0;
+    for (int b = threadIdx.x; b < B; b += 256) {
+        const int l = out_layer[b];
+        int e = -1;
+        for (int j = 0; j < ex.n; ++j)
+            if (ex.layer[j] == l) e = j;
+        if (e < 0) continue;
+        atomicAdd(&s_cnt[e], 1);
+        atomicAdd(&s_cnt[EE_MAX_EXITS], 1);
+        if (out_breach[b]) atomicAdd(&s_cnt[EE_MAX_EXITS + 1], 1);
+        acc += -log((double)out_conf[b]);
+    }
+    s_sum[threadIdx.x] = acc;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) s_sum[threadIdx.x] += s_sum[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x < EE_MAX_EXITS) row->exits[threadIdx.x] += s_cnt[threadIdx.x];
+    if (threadIdx.x == 0) {
+        row->tokens += s_cnt[EE_MAX_EXITS];
+        row->breaches += s_cnt[EE_MAX_EXITS + 1];
+        row->nll += s_sum[0];
+    }
+}
+
+int launch_pht_init(void* row, hipStream_t s) {
+    hipLaunchKernelGGL(k_pht_init, dim3(1), dim3(64), 0, s, (ee_pht_row*)row);
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
+int launch_pht_push(void* row, const ee_model* m, const ee_batch* b, hipStream_t s) {
+    ExitLayers ex;
+    ex.n = m->cfg.n_exits;
+    for (int e = 0; e < EE_MAX_EXITS; ++e) ex.layer[e] = e < ex.n ? m->cfg.exit_layers[e] : -1;
+    const ee_batch_layout& L = b->L;
+    TimedScope t(EE_K_PHT, s);
+    hipLaunchKernelGGL(k_pht_push, dim3(1), dim3(256), 0, s, (ee_pht_row*)row, b->st<int32_t>(L.out_layer),
+                       b->st<float>(L.out_conf), b->st<uint8_t>(L.out_breach), b->B, ex);
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
 // ------------------------------------------------------------------ weight repacking
 // one thread per 8-value chunk of the packed matrix
 __global__ void k_pack_weight(const bf16_t* __restrict__ src, int n_out, int n_in, bf16_t* __restrict__ dst,

@@ -313,6 +313,44 @@ class BreachCounter:
                     tokens_seen=seen, trigger_at=[int(v) for v in log[:min(n, self.LOG)]])
 
 
+class PhtRow:
+    """Device-resident row of the Performance History Table: exit profile, breaches and the sum
+    of -ln p of the emitted tokens, accumulated after each decode step."""
+
+    def __init__(self, model):
+        self.model = model
+        self.state = torch.zeros(C.sizeof(ee.ee_pht_row), dtype=torch.uint8, device="cuda")
+        ee.check(model.lib.ee_pht_init(C.c_void_p(self.state.data_ptr()), _stream()))
+
+    def reset(self):
+        ee.check(self.model.lib.ee_pht_init(C.c_void_p(self.state.data_ptr()), _stream()))
+
+    def push_step(self, batch):
+        ee.check(self.model.lib.ee_pht_push_step(C.c_void_p(self.state.data_ptr()), self.model.h, batch.h, _stream()))
+
+    def read(self):
+        """synchronises; returns the struct's fields (exits: one count per exit head of the model)"""
+        torch.cuda.current_stream().synchronize()
+        row = ee.ee_pht_row.from_buffer_copy(self.state.cpu().numpy().tobytes())
+        n = self.model.cfg.n_exits
+        return dict(tokens=int(row.tokens), breaches=int(row.breaches), exits=[int(row.exits[e]) for e in range(n)],
+                    nll=float(row.nll))
+
+
+def load_or_switch(cost_full_chosen, cost_low_exit_others):
+    """The branch of Algorithm 1 taken when the breach counter fires: load the rest of the chosen
+    model if its figure (a cost, lower is better) is not above that of every other candidate's
+    low-exit version, else switch to the cheapest of those.  Returns ("load", None) or
+    ("switch", candidate)."""
+    best = None
+    for name in sorted(cost_low_exit_others, key=str):
+        if best is None or cost_low_exit_others[name] < cost_low_exit_others[best]:
+            best = name
+    if best is None or cost_full_chosen <= cost_low_exit_others[best]:
+        return ("load", None)
+    return ("switch", best)
+
+
 class WindowSwitcher:
     """Host-side routing of one batch between several resident (partially loaded) models in fixed
     windows of decode steps: each model serves one window first, afterwards every window goes to

@@ -87,3 +87,15 @@ def test_product_package_does_not_reach_for_the_oracle():
             if f.endswith((".py", ".cpp", ".hip", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower(), f"{f} mentions the oracle"
+
+
+def test_load_or_switch_matches_the_oracle():
+    """host logic above the library (no GPU): the branch of Algorithm 1"""
+    import numpy as np
+    from oracle.ee_pht import load_or_switch as want
+    from paper_2504_10724_amd import session as S
+    rng = np.random.default_rng(3)
+    for _ in range(200):
+        others = {f"m{j}": float(rng.integers(1, 6)) for j in range(int(rng.integers(0, 4)))}
+        full = float(rng.integers(1, 6))
+        assert S.load_or_switch(full, others) == want(full, others)

@@ -472,3 +472,58 @@ def test_breach_counter_rejects_bad_arguments():
     assert lib.ee_cbc_init(C.c_void_p(buf.data_ptr()), 100, -1, None) == ee.EE_ERR_INVALID_ARG
     assert lib.ee_cbc_push(C.c_void_p(buf.data_ptr()), None, 5, None) == ee.EE_ERR_INVALID_ARG
     assert lib.ee_cbc_push(C.c_void_p(buf.data_ptr()), None, 0, None) == 0
+
+
+# ---------------------------------------------------------------- Performance History Table row
+def test_pht_row_matches_the_oracle_on_synthetic_step_outputs():
+    """Counts bit-exact; the fp64 sum of -ln p within 1e-12 relative (both sides add fp64 logs of the
+    same fp32 probabilities, in different orders, over at most a few thousand terms)."""
+    from oracle.ee_pht import PHTRow
+    s = MID
+    _say(f"[case] pht row, synthetic step outputs, {s.name}")
+    o, g = _fresh(s, jitter=0.0)
+    f = g.batch.field
+    rng = np.random.default_rng(5)
+    row = S.PhtRow(g.model)
+    want = PHTRow(s.exit_layers)
+    B = s.batch
+    for step in range(9):
+        layer = rng.choice(s.exit_layers, size=B).astype(np.int32)
+        conf = rng.uniform(1e-6, 1.0, size=B).astype(np.float32)
+        if step == 3:
+            conf[:] = 1.0
+        breach = ((layer == s.exit_layers[-1]) & (conf < 0.5)).astype(np.uint8)
+        if step == 5:
+            layer[::7] = 0                       # rows that have not left: not tokens
+        f("out_layer").copy_(torch.from_numpy(layer))
+        f("out_conf").copy_(torch.from_numpy(conf))
+        f("out_breach").copy_(torch.from_numpy(breach))
+        row.push_step(g.batch)
+        keep = layer != 0
+        want.push(layer[keep], conf[keep], breach[keep])
+        r = row.read()
+        assert r["tokens"] == want.tokens and r["breaches"] == want.breaches
+        assert r["exits"][:len(s.exit_layers)] == want.exits
+        assert abs(r["nll"] - want.nll) <= 1e-12 * max(1.0, want.nll), (r["nll"], want.nll)
+    row.reset()
+    z = row.read()
+    assert z["tokens"] == 0 and z["nll"] == 0.0 and not any(z["exits"])
+
+
+def test_pht_row_after_decode_steps_agrees_with_the_step_counters():
+    s = MID
+    _say(f"[case] pht row after decode steps {s.name}")
+    o, g = _fresh(s, jitter=0.0)
+    row = S.PhtRow(g.model)
+    for t in range(s.steps):
+        r = g.step(t)
+        row.push_step(g.batch)
+    got = row.read()
+    f = g.batch.field
+    assert got["tokens"] == s.batch * s.steps
+    assert got["exits"][:len(s.resident_exits)] == f("exit_counts").cpu().numpy()[:len(s.resident_exits)].tolist()
+    assert got["breaches"] == int(f("breach_count").cpu()[0])
+    assert got["nll"] > 0.0 and np.isfinite(got["nll"])
+    lib = ee.load()
+    assert lib.ee_pht_push_step(None, g.model.h, g.batch.h, None) == ee.EE_ERR_INVALID_ARG
+    assert lib.ee_pht_init(None, None) == ee.EE_ERR_INVALID_ARG
