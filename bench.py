@@ -265,7 +265,7 @@ def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
     return res
 
 
-def run_context_pass(s, model, torch, S, ee, synth, entries_per_call, n_ctx=8, ctx_len=1024):
+def run_context_pass(s, model, torch, S, ee, synth, C, entries_per_call, n_ctx=8, ctx_len=1024):
     """Context pass (ee_prefill) over n_ctx contexts of ctx_len tokens on the resident layers, in calls of
     entries_per_call entries: tokens/s with the token, position and cache-row arrays resident in HBM.
     Outside the timed decode region; reported in `detail` only."""
@@ -290,11 +290,23 @@ def run_context_pass(s, model, torch, S, ee, synth, entries_per_call, n_ctx=8, c
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     assert int(pb.field("status").cpu()[0]) == 0, "device status flag set"
+    # per-class kernel times from a further pass of its own (event pairs cost stream time)
+    lib.ee_timing_reset()
+    lib.ee_timing_enable((1 << len(ee.KERNEL_CLASSES)) - 1)
+    run()
+    torch.cuda.synchronize()
+    lib.ee_timing_enable(0)
+    kern = {}
+    for k, name in enumerate(ee.KERNEL_CLASSES):
+        n, ms = C.c_int(), C.c_float()
+        lib.ee_timing_read(k, C.byref(n), C.byref(ms))
+        if n.value:
+            kern[name] = dict(launches=n.value, total_ms=round(ms.value, 3))
     tokens = n_ctx * ctx_len
     flops = 2.0 * tokens * s.resident * s.layer_params()      # the four products of each layer; attention not counted
     res = dict(entries_per_call=entries_per_call, contexts=n_ctx, tokens_per_context=ctx_len, calls=len(calls),
                ms=dt * 1e3, tokens_per_s=tokens / dt, gemm_tflops=flops / dt / 1e12,
-               mfma_frac=flops / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS)
+               mfma_frac=flops / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS, kernels_ms=kern)
     del pb, kv
     torch.cuda.empty_cache()
     return res
@@ -350,7 +362,7 @@ def main():
     model = build_device_model(s, S, torch, max_cap, s.seed)
     if args.context_pass_only is not None:
         for n in (args.context_pass_only or [256]):
-            print(json.dumps(run_context_pass(s, model, torch, S, ee, synth, n)), flush=True)
+            print(json.dumps(run_context_pass(s, model, torch, S, ee, synth, C, n)), flush=True)
         return
     head = run_workload(s, model, args, torch, S, ee, synth, C)
     sweep = {}
@@ -360,7 +372,7 @@ def main():
             sweep[str(b)] = {k: r[k] for k in ("tokens_per_s", "ms_per_step", "exit_fractions", "avg_layers_per_token",
                                                "gate_up_gemm", "attention", "layer_gemms",
                                                "exit_head_plus_compaction_us_per_step")}
-    context_pass = None if args.no_context_pass else run_context_pass(s, model, torch, S, ee, synth, 256)
+    context_pass = None if args.no_context_pass else run_context_pass(s, model, torch, S, ee, synth, C, 256)
     exits = s.resident_exits
     out = dict(metric="decoded tokens/s/GPU at Llama2-70B shape", value=head["tokens_per_s"], unit="tokens/s", n_gpus=1,
                steps=args.steps, warmup=args.warmup, ms_per_step=head["ms_per_step"], higher_is_better=True,
