@@ -260,3 +260,17 @@ def prefill(model, kv, b, tokens, pos0=0, want_h=False):
     s = kv.struct()
     rc = lib().orc_prefill(model.h, C.byref(s), int(b), _p(tok), tok.size, int(pos0), _p(h))
     return rc, h
+
+
+def backfill_kv(model, kv, from_excl, to_incl, exit_states):
+    """Keys and values of newly resident layers (from_excl, to_incl] for tokens that are cached
+    already (Sec. 3.3.3: more layers of the current model are loaded while it serves; Sec. 2.2:
+    every layer needs the keys and values of every earlier token).  exit_states maps
+    (row, position) to the hidden state the token had where it left the layer stack; a layer
+    it did not run leaves that state unchanged, so each new layer takes its K, V from it,
+    exactly as orc_fill_skipped_kv does inside a decode step."""
+    for (b, p), h in exit_states.items():
+        rc = fill_skipped_kv(model, from_excl, to_incl, kv, b, p, h)
+        if rc != ORC_OK:
+            return rc
+    return ORC_OK
