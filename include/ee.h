@@ -278,6 +278,46 @@ int ee_decode_step(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_
 int ee_prefill(const ee_model* m, ee_kv* kv, ee_batch* b, const int32_t* dev_tok,
                const int32_t* dev_pos, const int32_t* dev_seq, int n, void* stream);
 
+/* ------------------------------------------------------------------ loading more layers while serving
+ *
+ * With greedy partial loading only layers 1..R are resident; when too many tokens stop at R below
+ * their threshold the serving loop may load further layers of the same model (Sec. 3.3.3, "Load More
+ * Layers Or Another Candidate Model?").  Two things are needed besides the weights: the new layers'
+ * table entries must change without stopping the steps in flight, and the tokens that are cached
+ * already need keys and values in the new layers (Sec. 2.2).  Those come from each token's hidden
+ * state where it left the stack (a layer it did not run leaves that state unchanged), the same
+ * rule as ee_fill_skipped_kv, so the states are kept in a store beside the cache.
+ *
+ * Store: device memory owned by the caller, fp32 [T][d_model], T = sum of the cache rows'
+ * capacities; the state of position p of cache row r is at row (positions of rows before r) + p. */
+
+/* As ee_model_set_layer, but the device-side table entries are written by a kernel on `stream`:
+ * nothing waits on the host.  The caller orders the arrival of the weights before this call's
+ * stream position (an event of the copy stream, say); steps enqueued on `stream` afterwards see
+ * the layer. */
+int ee_model_set_layer_on(ee_model* m, int layer, const ee_layer_weights* dev_w, void* stream);
+
+/* Bytes of the exit-state store for this cache; 0 on a null handle. */
+size_t ee_hstore_bytes(const ee_model* m, const ee_kv* kv);
+/* After ee_decode_step: keeps h of every row (its state where it left) at the position the step
+ * served (pos - 1 after the step).  Enqueue only.  A position outside the capacity sets status bit 1. */
+int ee_hstore_put_step(const ee_model* m, const ee_kv* kv, const ee_batch* b, float* dev_store, void* stream);
+/* After ee_prefill of n entries on this batch: keeps h of entry i (its state after layer R) at
+ * (cache row, position) of the entry. */
+int ee_hstore_put_prefill(const ee_model* m, const ee_kv* kv, const ee_batch* b, int n, float* dev_store,
+                          void* stream);
+/* K and V of layers (from_layer_excl, to_layer_incl] for n cached tokens, entry i = position
+ * dev_pos[i] of cache row dev_seq[i], from their states in the store:
+ * x = RMSNorm(state; g_attn of the layer), K = RoPE(x W_k, position), V = x W_v, written at the
+ * token's position.  n <= B of the batch; the batch's h, pos, exited_idx and n_exited are
+ * overwritten (use a batch that is not in the middle of a step, or reset it afterwards).
+ * The layers' table entries are read on the device: enqueue this on the stream ee_model_set_layer_on
+ * was given (or order it after that stream).
+ * Errors as ee_fill_skipped_kv; EE_ERR_CAPACITY if n > B.  Refusals (no such cache row, position
+ * outside its capacity) set status bit 1 and write nothing for that entry. */
+int ee_backfill_kv(const ee_model* m, int from_layer_excl, int to_layer_incl, ee_kv* kv, ee_batch* b,
+                   const float* dev_store, const int32_t* dev_pos, const int32_t* dev_seq, int n, void* stream);
+
 /* ------------------------------------------------------------------ confidence-breach counter
  *
  * The serving loop above the decode step re-assesses its choice of model (load more

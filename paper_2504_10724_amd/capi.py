@@ -71,6 +71,11 @@ _SIGS = {
     "ee_fill_skipped_kv": (_i, [_vp, _i, _i, _vp, _vp, _vp]),
     "ee_decode_step": (_i, [_vp, _vp, _vp, C.POINTER(C.c_float), _i, _vp]),
     "ee_prefill": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _vp]),
+    "ee_model_set_layer_on": (_i, [_vp, _i, C.POINTER(ee_layer_weights), _vp]),
+    "ee_hstore_bytes": (_sz, [_vp, _vp]),
+    "ee_hstore_put_step": (_i, [_vp, _vp, _vp, _vp, _vp]),
+    "ee_hstore_put_prefill": (_i, [_vp, _vp, _vp, _i, _vp, _vp]),
+    "ee_backfill_kv": (_i, [_vp, _i, _i, _vp, _vp, _vp, _vp, _vp, _i, _vp]),
     "ee_cbc_state_bytes": (C.c_size_t, [_i]),
     "ee_cbc_init": (_i, [_vp, _i, _i, _vp]),
     "ee_cbc_push": (_i, [_vp, _vp, _i, _vp]),

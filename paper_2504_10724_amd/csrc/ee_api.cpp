@@ -198,6 +198,18 @@ int ee_model_set_layer(ee_model* m, int layer, const ee_layer_weights* w) {
     return EE_OK;
 }
 
+int ee_model_set_layer_on(ee_model* m, int layer, const ee_layer_weights* w, void* stream) {
+    if (!m || !w) return ee_fail(EE_ERR_INVALID_ARG, "ee_model_set_layer_on: null pointer");
+    if (layer < 1 || layer > m->cfg.n_layers) return ee_fail(EE_ERR_INVALID_ARG, "ee_model_set_layer_on: layer out of range");
+    if (!w->g_attn || !w->w_qkv || !w->w_o || !w->g_ffn || !w->w_gate_up || !w->w_down)
+        return ee_fail(EE_ERR_INVALID_ARG, "ee_model_set_layer_on: null weight pointer");
+    int rc = launch_set_layer_ptrs(m, layer, w->w_qkv, (const float*)w->g_attn, as_stream(stream));
+    if (rc != EE_OK) return rc;
+    m->layers[layer - 1] = *w;
+    m->resident[layer - 1] = 1;
+    return EE_OK;
+}
+
 int ee_model_set_exit(ee_model* m, int exit_idx, const float* gain, const void* w) {
     if (!m || !gain || !w) return ee_fail(EE_ERR_INVALID_ARG, "ee_model_set_exit: null pointer");
     if (exit_idx < 0 || exit_idx >= m->cfg.n_exits) return ee_fail(EE_ERR_INVALID_ARG, "ee_model_set_exit: exit index out of range");
@@ -541,6 +553,48 @@ int ee_prefill(const ee_model* m, ee_kv* kv, ee_batch* b, const int32_t* dev_tok
             rc = f32_layer_forward(m, l, kv, b, s);
         }
     }
+    b->kv_seq = nullptr;
+    return rc;
+}
+
+size_t ee_hstore_bytes(const ee_model* m, const ee_kv* kv) {
+    if (!m || !kv) return 0;
+    return (size_t)kv->T * (size_t)m->cfg.d_model * sizeof(float);
+}
+
+int ee_hstore_put_step(const ee_model* m, const ee_kv* kv, const ee_batch* b, float* dev_store, void* stream) {
+    int rc = check_pair("ee_hstore_put_step", m, kv, b);
+    if (rc != EE_OK) return rc;
+    if (!dev_store) return ee_fail(EE_ERR_INVALID_ARG, "ee_hstore_put_step: null store");
+    return launch_hstore_put(m, kv, b, b->B, false, dev_store, as_stream(stream));
+}
+
+int ee_hstore_put_prefill(const ee_model* m, const ee_kv* kv, const ee_batch* b, int n, float* dev_store, void* stream) {
+    if (!m || !kv || !b || !dev_store) return ee_fail(EE_ERR_INVALID_ARG, "ee_hstore_put_prefill: null pointer");
+    if (b->m != m) return ee_fail(EE_ERR_INVALID_ARG, "ee_hstore_put_prefill: batch not bound to this model");
+    if (n < 0 || n > b->B) return ee_fail(EE_ERR_CAPACITY, "ee_hstore_put_prefill: more entries than the batch has rows");
+    if (n == 0) return EE_OK;
+    return launch_hstore_put(m, kv, b, n, true, dev_store, as_stream(stream));
+}
+
+int ee_backfill_kv(const ee_model* m, int from_layer_excl, int to_layer_incl, ee_kv* kv, ee_batch* b,
+                   const float* dev_store, const int32_t* dev_pos, const int32_t* dev_seq, int n, void* stream) {
+    if (!m || !kv || !b) return ee_fail(EE_ERR_INVALID_ARG, "ee_backfill_kv: null handle");
+    if (b->m != m) return ee_fail(EE_ERR_INVALID_ARG, "ee_backfill_kv: batch not bound to this model");
+    if (n < 0 || n > b->B) return ee_fail(EE_ERR_CAPACITY, "ee_backfill_kv: more entries than the batch has rows");
+    if (from_layer_excl < 0 || to_layer_incl > m->cfg.n_layers)
+        return ee_fail(EE_ERR_INVALID_ARG, "ee_backfill_kv: layer range out of the model");
+    for (int l = from_layer_excl + 1; l <= to_layer_incl; ++l)
+        if (!m->resident[l - 1]) return ee_fail(EE_ERR_LAYER_NOT_RESIDENT, "ee_backfill_kv: layer is not resident");
+    if (to_layer_incl > kv->n_layers) return ee_fail(EE_ERR_CAPACITY, "ee_backfill_kv: cache holds fewer layers");
+    if (from_layer_excl >= to_layer_incl || n == 0) return EE_OK;
+    if (!dev_store || !dev_pos || !dev_seq) return ee_fail(EE_ERR_INVALID_ARG, "ee_backfill_kv: null array");
+    hipStream_t s = as_stream(stream);
+    int rc = launch_backfill_begin(m, kv, b, dev_store, dev_pos, dev_seq, n, s);
+    if (rc != EE_OK) return rc;
+    b->kv_seq = b->wsp<int32_t>(b->W.kv_seq);
+    rc = m->cfg.dtype == EE_BF16 ? bf16_fill_kv(m, from_layer_excl, to_layer_incl, kv, b, s)
+                                 : f32_fill_kv(m, from_layer_excl, to_layer_incl, kv, b, s);
     b->kv_seq = nullptr;
     return rc;
 }

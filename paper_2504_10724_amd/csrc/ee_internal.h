@@ -110,6 +110,11 @@ int launch_compact(ee_batch* b, int exit_idx, int exit_layer, hipStream_t s);
 int launch_exit_decide(ee_batch* b, int n_part, float th, int force, hipStream_t s);
 int launch_prefill_begin(const ee_model* m, const ee_kv* kv, ee_batch* b, const int32_t* tok, const int32_t* pos,
                          const int32_t* seq, int n, hipStream_t s);
+int launch_set_layer_ptrs(ee_model* m, int layer, const void* w_qkv, const float* g_attn, hipStream_t s);
+int launch_hstore_put(const ee_model* m, const ee_kv* kv, const ee_batch* b, int n, bool entries, float* store,
+                      hipStream_t s);
+int launch_backfill_begin(const ee_model* m, const ee_kv* kv, ee_batch* b, const float* store, const int32_t* pos,
+                          const int32_t* seq, int n, hipStream_t s);
 int launch_cbc_init(void* st, int window, int cbc_max, hipStream_t s);
 int launch_cbc_push(void* st, const uint8_t* flags, int n, hipStream_t s);
 int launch_pht_init(void* row, hipStream_t s);

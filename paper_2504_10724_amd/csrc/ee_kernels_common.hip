@@ -115,6 +115,92 @@ int launch_prefill_begin(const ee_model* m, const ee_kv* kv, ee_batch* b, const 
     return EE_OK;
 }
 
+// ------------------------------------------------------------------ loading more layers while serving
+__global__ void k_set_layer_ptrs(const void** wqkv_tab, const float** gattn_tab, int at, const void* w_qkv,
+                                 const float* g_attn) {
+    if (threadIdx.x == 0) { wqkv_tab[at] = w_qkv; gattn_tab[at] = g_attn; }
+}
+
+int launch_set_layer_ptrs(ee_model* m, int layer, const void* w_qkv, const float* g_attn, hipStream_t s) {
+    hipLaunchKernelGGL(k_set_layer_ptrs, dim3(1), dim3(64), 0, s, m->d_wqkv_tab, m->d_gattn_tab, layer - 1, w_qkv, g_attn);
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
+// store[(positions of cache rows before r) + p][:] = h[i][:].  After a decode step (seq == null):
+// batch row i is cache row i and p = pos[i] + delta with delta = -1; after a context pass: entry i
+// is cache row seq[i] at p = pos[i].
+__global__ void __launch_bounds__(256)
+k_hstore_put(const float* __restrict__ h, int d, int n, const int32_t* __restrict__ pos, int delta,
+             const int32_t* __restrict__ seq, int n_seq, const int64_t* __restrict__ off,
+             const int32_t* __restrict__ cap, float* __restrict__ store, int32_t* __restrict__ status) {
+    int i = blockIdx.x;
+    if (i >= n) return;
+    int sq = seq ? seq[i] : i;
+    int p = pos[i] + delta;
+    if (sq < 0 || sq >= n_seq || p < 0 || p >= cap[sq]) {
+        if (threadIdx.x == 0) atomicOr(status, 1);
+        return;
+    }
+    const float4* src = reinterpret_cast<const float4*>(h + (int64_t)i * d);
+    float4* dst = reinterpret_cast<float4*>(store + (off[sq] + p) * (int64_t)d);
+    for (int j = threadIdx.x; j < d / 4; j += 256) dst[j] = src[j];
+}
+
+int launch_hstore_put(const ee_model* m, const ee_kv* kv, const ee_batch* b, int n, bool entries, float* store,
+                      hipStream_t s) {
+    const ee_batch_layout& L = b->L;
+    hipLaunchKernelGGL(k_hstore_put, dim3(n), dim3(256), 0, s, b->st<float>(L.h), m->cfg.d_model, n,
+                       b->st<int32_t>(L.pos), entries ? 0 : -1, entries ? b->wsp<int32_t>(b->W.kv_seq) : (const int32_t*)nullptr,
+                       kv->B, kv->d_off, kv->d_cap, store, b->st<int32_t>(L.status));
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
+// Entry i < n = position pos[i] of cache row seq[i]: it becomes batch row i of the list of rows that
+// left (the list the skipped-layer fill works on), with its stored state as h.  An entry that names
+// no cache row or a position outside the capacity gets position -1 (refused by the append kernel,
+// status bit 1) and cache row 0, so that every later address stays inside the pool and the store.
+__global__ void __launch_bounds__(256)
+k_backfill_begin(const float* __restrict__ store, int d, int n, const int32_t* __restrict__ pos,
+                 const int32_t* __restrict__ seq, int n_seq, const int64_t* __restrict__ off,
+                 const int32_t* __restrict__ cap, float* __restrict__ h, int32_t* __restrict__ s_pos,
+                 int32_t* __restrict__ kv_seq, int32_t* __restrict__ exited_idx, int32_t* __restrict__ n_exited,
+                 int32_t* __restrict__ status) {
+    int i = blockIdx.x;
+    if (i >= n) return;
+    int sq = seq[i], p = pos[i];
+    bool ok = sq >= 0 && sq < n_seq && p >= 0 && p < cap[sq];
+    if (!ok) {
+        if (threadIdx.x == 0) atomicOr(status, 1);
+        sq = 0;
+        p = -1;
+    }
+    if (threadIdx.x == 0) {
+        s_pos[i] = p;
+        kv_seq[i] = sq;
+        exited_idx[i] = i;
+        if (i == 0) *n_exited = n;
+    }
+    float4* dst = reinterpret_cast<float4*>(h + (int64_t)i * d);
+    if (ok) {
+        const float4* src = reinterpret_cast<const float4*>(store + (off[sq] + p) * (int64_t)d);
+        for (int j = threadIdx.x; j < d / 4; j += 256) dst[j] = src[j];
+    } else {
+        for (int j = threadIdx.x; j < d / 4; j += 256) dst[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+
+int launch_backfill_begin(const ee_model* m, const ee_kv* kv, ee_batch* b, const float* store, const int32_t* pos,
+                          const int32_t* seq, int n, hipStream_t s) {
+    const ee_batch_layout& L = b->L;
+    hipLaunchKernelGGL(k_backfill_begin, dim3(n), dim3(256), 0, s, store, m->cfg.d_model, n, pos, seq, kv->B, kv->d_off,
+                       kv->d_cap, b->st<float>(L.h), b->st<int32_t>(L.pos), b->wsp<int32_t>(b->W.kv_seq),
+                       b->st<int32_t>(L.exited_idx), b->st<int32_t>(L.n_exited), b->st<int32_t>(L.status));
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
 // every row advances one position, whatever layer it left at, and the token it
 // emitted is the input of the next step
 __global__ void k_end_step(int32_t* __restrict__ pos, int32_t* __restrict__ tok_in,

@@ -278,6 +278,96 @@ def prefill_chunks(contexts, rows_per_call):
         yield (np.array(tok, np.int32), np.array(pos, np.int32), np.array(seq, np.int32))
 
 
+class HiddenStore:
+    """The exit hidden state of every cached token (fp32 [positions][d_model], laid out like the
+    cache rows): what the keys and values of layers loaded later are computed from."""
+
+    def __init__(self, model, kv):
+        self.model, self.kv = model, kv
+        nbytes = model.lib.ee_hstore_bytes(model.h, kv.h)
+        self.buf = torch.zeros(nbytes // 4, dtype=torch.float32, device="cuda")
+
+    def put_step(self, batch):
+        return self.model.lib.ee_hstore_put_step(self.model.h, self.kv.h, batch.h, _ptr(self.buf), _stream())
+
+    def put_prefill(self, batch, n):
+        return self.model.lib.ee_hstore_put_prefill(self.model.h, self.kv.h, batch.h, int(n), _ptr(self.buf), _stream())
+
+
+def backfill_kv(model, from_excl, to_incl, kv, batch, store, pos, seq):
+    """One ee_backfill_kv call: K, V of layers (from_excl, to_incl] for the cached tokens
+    (seq[i], pos[i]) from their states in `store` (a HiddenStore)."""
+    p, q = _i32_device(pos), _i32_device(seq)
+    assert p.numel() == q.numel()
+    return model.lib.ee_backfill_kv(model.h, from_excl, to_incl, kv.h, batch.h, _ptr(store.buf), _ptr(p), _ptr(q),
+                                    int(p.numel()), _stream())
+
+
+class LayerLoader:
+    """Brings further layers of a model into HBM while decode steps keep running: the copies from
+    pinned host memory and the repacking run on a stream of their own; a layer becomes resident
+    (ee_model_set_layer_on, on the caller's current stream) once its event has completed."""
+
+    def __init__(self, model):
+        self.model = model
+        self.stream = torch.cuda.Stream()
+        self.pending = []
+
+    @staticmethod
+    def pin(weights):
+        """host copies in pinned memory of one layer's tensors (numpy float32 / uint16 bf16 bits, or torch)"""
+        out = {}
+        for k, a in weights.items():
+            if isinstance(a, torch.Tensor):
+                t = a.detach().to("cpu")
+            else:
+                a = np.ascontiguousarray(a)
+                t = torch.from_numpy(a.view(np.int16)).view(torch.bfloat16) if a.dtype == np.uint16 else torch.from_numpy(a)
+            p = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
+            p.copy_(t)
+            out[k] = p
+        return out
+
+    def start(self, layer, pinned):
+        """enqueue the copy and repacking of one layer (dict as for Model.set_layer, pinned host tensors)"""
+        m = self.model
+        with torch.cuda.stream(self.stream):
+            dev = {k: v.to("cuda", non_blocking=True) for k, v in pinned.items()}
+
+            def pack(t, off=0, stride=1, out=None):
+                if not m.bf16:
+                    return t
+                rows = t.shape[0] * stride
+                o = out if out is not None else torch.empty((rows, t.shape[1]), dtype=m.tdtype, device="cuda")
+                ee.check(m.lib.ee_pack_weight(_ptr(t), t.shape[0], t.shape[1], _ptr(o), off, stride, rows // 32, _stream()))
+                return o
+            if m.bf16:
+                gu = pack(dev["W_gate"], 0, 2)
+                pack(dev["W_up"], 1, 2, gu)
+            else:
+                gu = torch.cat([dev["W_gate"], dev["W_up"]], dim=0).contiguous()
+            t = dict(g_attn=dev["g_attn"], w_qkv=pack(dev["W_qkv"]), w_o=pack(dev["W_o"]), g_ffn=dev["g_ffn"],
+                     w_gate_up=gu, w_down=pack(dev["W_down"]))
+            ev = torch.cuda.Event()
+            ev.record(self.stream)
+        self.pending.append((layer, t, ev, dev))
+
+    def poll(self, wait=False):
+        """makes the layers whose transfer has completed resident, in the order they were started;
+        returns their numbers"""
+        done = []
+        while self.pending and (wait or self.pending[0][2].query()):
+            layer, t, ev, dev = self.pending.pop(0)
+            if wait:
+                ev.synchronize()
+            w = ee.ee_layer_weights(_ptr(t["g_attn"]), _ptr(t["w_qkv"]), _ptr(t["w_o"]), _ptr(t["g_ffn"]),
+                                    _ptr(t["w_gate_up"]), _ptr(t["w_down"]))
+            ee.check(self.model.lib.ee_model_set_layer_on(self.model.h, layer, C.byref(w), _stream()))
+            self.model._keep[("layer", layer)] = tuple(t.values())
+            done.append(layer)
+        return done
+
+
 class BreachCounter:
     """Device-resident confidence-breach counter (window of the most recent tokens, re-assessment
     when more than cbc_max of them stopped below their threshold)."""
