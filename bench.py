@@ -123,7 +123,69 @@ def cpu_baseline(s, exit_hist, n_rows=8):
                        f"with the measured exit histogram over {s.resident} layers")
 
 
-def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
+def measure_layer_load(s, model, args, torch, S, ee, kv, batch, run, reset):
+    """The load-more-layers path at the workload's shape (Sec. 3.3.3), outside the timed region: one
+    layer's weights (pinned host memory -> HBM on a stream of their own, repacked there) alone and
+    under running decode steps, and the keys/values of new layers for cached tokens."""
+    d, F, qd = s.d_model, s.d_ffn, s.n_q_heads * s.head_dim
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(s.seed + 7)
+    mat = lambda o, i: (torch.randn((o, i), generator=gen, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+    ones = torch.ones(d, dtype=torch.float32)
+    pinned = S.LayerLoader.pin(dict(g_attn=ones, W_qkv=mat(s.qkv_rows, d), W_o=mat(d, qd), g_ffn=ones,
+                                    W_gate=mat(F, d), W_up=mat(F, d), W_down=mat(d, F)))
+    layer_bytes = sum(t.numel() * t.element_size() for t in pinned.values())
+    shell = S.Model.from_shape(s, max_pos=model.cfg.max_pos)      # same shape, no weights: the layers land here
+    loader = S.LayerLoader(shell)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    loader.start(1, pinned)
+    loader.poll(wait=True)
+    torch.cuda.synchronize()
+    t_alone = time.perf_counter() - t0
+    # three more layers while decode steps run on the main stream
+    reset()
+    torch.cuda.synchronize()
+    n_load = 3
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    l0, l1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    l0.record(loader.stream)
+    e0.record()
+    for l in range(2, 2 + n_load):
+        loader.start(l, pinned)
+    l1.record(loader.stream)
+    run(args.steps, 0)
+    e1.record()
+    torch.cuda.synchronize()
+    loader.poll(wait=True)
+    res = dict(layer_bytes=layer_bytes, alone_ms=t_alone * 1e3, alone_gbs=layer_bytes / t_alone / 1e9,
+               under_decode_gbs=n_load * layer_bytes / (l0.elapsed_time(l1) * 1e-3) / 1e9,
+               decode_ms_per_step_while_loading=e0.elapsed_time(e1) / args.steps)
+    # keys and values of layers R-3..R for 256 cached tokens per call from an exit-state store
+    store = S.HiddenStore(model, kv)
+    store.buf.normal_(0.0, 0.02 * float(np.sqrt(d)), generator=gen)
+    R = s.resident
+    nl = min(4, R - 1)
+    n = min(256, s.batch)
+    seq = torch.arange(n, dtype=torch.int32, device="cuda")
+    calls = 8
+    S.backfill_kv(model, R - nl, R, kv, batch, store, torch.zeros(n, dtype=torch.int32, device="cuda"), seq)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for c in range(calls):
+        rc = S.backfill_kv(model, R - nl, R, kv, batch, store, torch.full((n,), 1 + c, dtype=torch.int32, device="cuda"), seq)
+        if rc != 0:
+            raise ee.EEError(rc, model.lib.ee_last_error().decode())
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    res["backfill"] = dict(tokens_per_call=n, layers=nl, calls=calls, ms_per_call=dt / calls * 1e3,
+                           token_layers_per_s=n * nl * calls / dt)
+    del store, loader, shell, pinned
+    torch.cuda.empty_cache()
+    return res
+
+
+def run_workload(s, model, args, torch, S, ee, synth, C, timed=True, with_load=False):
     """One batch size: bind cache and batch state, warm up, rewind, time `steps` decode steps."""
     lib = model.lib
     total_steps = args.steps + args.warmup
@@ -260,6 +322,9 @@ def run_workload(s, model, args, torch, S, ee, synth, C, timed=True):
                      exits=pht_row["exits"][:len(exits)], breaches=pht_row["breaches"],
                      perplexity=float(np.exp(pht_row["nll"] / max(1, pht_row["tokens"])))))
     res["layer_gemms"]["hbm_frac"] = res["layer_gemms"]["hbm_gbs"] / HBM_PEAK_GBS
+    if with_load:
+        res["layer_load"] = measure_layer_load(s, model, args, torch, S, ee, kv, batch, run,
+                                               lambda: batch.reset(tok0, ctx.astype(np.int32), None))
     del batch, kv
     torch.cuda.empty_cache()
     return res
@@ -322,6 +387,7 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer resident layers (not a valid result)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the smaller batch sizes of the sweep")
+    ap.add_argument("--no-layer-load", action="store_true", help="skip the layer-load and backfill measurement")
     ap.add_argument("--no-context-pass", action="store_true", help="skip the context-pass (ee_prefill) measurement")
     ap.add_argument("--context-pass-only", type=int, nargs="*", default=None, metavar="ENTRIES",
                     help="only time the context pass (ee_prefill) with these numbers of entries per call")
@@ -364,7 +430,7 @@ def main():
         for n in (args.context_pass_only or [256]):
             print(json.dumps(run_context_pass(s, model, torch, S, ee, synth, C, n)), flush=True)
         return
-    head = run_workload(s, model, args, torch, S, ee, synth, C)
+    head = run_workload(s, model, args, torch, S, ee, synth, C, with_load=not args.no_layer_load)
     sweep = {}
     if not args.no_sweep and not args.batch:
         for b in (64, 16, 1):
@@ -385,6 +451,7 @@ def main():
                                             "layer_gemms", "exit_head_plus_compaction_us_per_step", "breach_counter", "pht_row", "kernels_ms")},
                batch_sweep=sweep)
     out["detail"]["context_pass"] = context_pass
+    out["detail"]["layer_load"] = head.get("layer_load")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(s, head["counts"])
     print(json.dumps(out))
