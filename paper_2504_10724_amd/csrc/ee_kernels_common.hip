@@ -506,9 +506,9 @@ __global__ void k_kv_copy(KvView kv, int row, int pos0, int n_pos, T* __restrict
     int cap = kv.cap[row];
     if (pos0 + p >= cap) return;
     T* base = reinterpret_cast<T*>(kv.pool) + kv_block(kv, row, g, cap);
-    T* kp = base + (BF16_LAYOUT ? k_bf16_offset(pos0 + p, i) : ((int64_t)(pos0 + p) * hd + i));
-    T* vp = base + (int64_t)cap * hd +
-            (BF16_LAYOUT ? v_bf16_offset(pos0 + p, i, hd) : ((int64_t)(pos0 + p) * hd + i));
+    T* kp = base + (BF16_LAYOUT ? k_bf16_offset(pos0 + p, i, hd) : ((int64_t)(pos0 + p) * hd + i));
+    T* vp = base + (BF16_LAYOUT ? v_bf16_offset(pos0 + p, i, hd)
+                                : ((int64_t)cap * hd + (int64_t)(pos0 + p) * hd + i));
     if (to_pool) { *kp = k[idx]; *vp = v[idx]; }
     else         { k[idx] = *kp; v[idx] = *vp; }
 }
