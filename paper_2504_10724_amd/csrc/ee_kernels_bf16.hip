@@ -288,11 +288,56 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
 struct Half { uint4 v[4]; };   // A operands of one K half: 4 row tiles
 struct Oct { uint4 v[8]; };    // A operands of one K half: 8 row tiles
 
+// One 32x32x16 step of a result tile.  A and B operands have the same register layout, so handing
+// them over in the other order gives the transposed tile at no cost.  The exit head wants that: a
+// lane then holds 16 vocabulary columns of ONE batch row, and the row statistics (maximum, its
+// column, sum of exponentials) need one exchange between the two half-waves instead of a
+// 32-lane butterfly per accumulator register (measured: 83 of 230 us of the exit-head product).
+template <int EPI>
+__device__ __forceinline__ floatx16 tile_mfma(const uint4& x, const uint4& w, const floatx16& acc) {
+    if constexpr (EPI == EPI_EXIT) return __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(w), as_bf16x8(x), acc, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(x), as_bf16x8(w), acc, 0, 0, 0);
+}
+
 template <int EPI>
 __device__ __forceinline__ void epilogue_tile(const EpiArgs& ep, const floatx16& v0, const floatx16& v1, int row0,
                                               int n, int nb, int lane) {
     // v0 / v1: the 32x32 results of tile-rows nb and nb+1 for rows row0 .. row0+31
     const int cl = lane & 31;
+    if constexpr (EPI == EPI_EXIT) {
+        // transposed tiles (tile_mfma): this lane holds batch row row0 + cl and, of each tile-row's 32
+        // vocabulary columns, the 16 at 8 (r / 4) + 4 (lane / 32) + r % 4; lane ^ 32 holds the others
+        const int row = row0 + cl;
+        const bool live = row < n;
+        const float sc = live ? ep.row_scale[ep.idx[row]] : 0.f;
+#pragma unroll
+        for (int ns = 0; ns < 2; ++ns) {
+            const floatx16& v = ns == 0 ? v0 : v1;
+            const int col0 = 32 * (nb + ns) + 4 * (lane >> 5);
+            float z[16];
+            float mx = -FLT_MAX;
+            int arg = col0;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int col = col0 + 8 * (r >> 2) + (r & 3);        // rising with r: > keeps the lowest column
+                z[r] = v[r] * sc;
+                if (live && ep.dbg_logits) ep.dbg_logits[(int64_t)row * ep.ldo + col] = z[r];
+                if (z[r] > mx) { mx = z[r]; arg = col; }
+            }
+            const float m2 = __shfl_xor(mx, 32, 64);
+            const int a2 = __shfl_xor(arg, 32, 64);
+            if (m2 > mx || (m2 == mx && a2 < arg)) { mx = m2; arg = a2; }
+            float se = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) se += expf(z[r] - mx);
+            se += __shfl_xor(se, 32, 64);
+            if (live && lane < 32) {
+                const int64_t at = (int64_t)row * ep.n_part + nb + ns;
+                ep.part_max[at] = mx; ep.part_sum[at] = se; ep.part_arg[at] = arg;
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int row = row0 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
@@ -314,31 +359,6 @@ __device__ __forceinline__ void epilogue_tile(const EpiArgs& ep, const floatx16&
                 float a = (gt / (1.0f + expf(-gt))) * up;
                 int col = 32 * (nb >> 1) + cl;
                 ep.act[afrag_chunk(row, col & ~7, ep.KB_act) * 8 + (col & 7)] = f32_to_bf16(a);
-            }
-        } else {
-            float sc = live ? ep.row_scale[ep.idx[row]] : 0.f;
-#pragma unroll
-            for (int ns = 0; ns < 2; ++ns) {
-                int col = 32 * (nb + ns) + cl;
-                float z = (ns == 0 ? v0[r] : v1[r]) * sc;
-                if (live && ep.dbg_logits) ep.dbg_logits[(int64_t)row * ep.ldo + col] = z;
-                // the 32 lanes of a half-wave hold the 32 columns of this row: maximum and its
-                // lowest column first, then one exponential per logit
-                float mx = z;
-                int arg = col;
-#pragma unroll
-                for (int o = 16; o > 0; o >>= 1) {
-                    float m2 = __shfl_xor(mx, o, 64);
-                    int a2 = __shfl_xor(arg, o, 64);
-                    if (m2 > mx || (m2 == mx && a2 < arg)) { mx = m2; arg = a2; }
-                }
-                float se = expf(z - mx);
-#pragma unroll
-                for (int o = 16; o > 0; o >>= 1) se += __shfl_xor(se, o, 64);
-                if (live && cl == 0) {
-                    int64_t at = (int64_t)row * ep.n_part + nb + ns;
-                    ep.part_max[at] = mx; ep.part_sum[at] = se; ep.part_arg[at] = arg;
-                }
             }
         }
     }
@@ -453,10 +473,8 @@ k_bf16_gemm_dma(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int 
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             if (i + r < MBS) {
-                acc[i + r][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[i + r]), as_bf16x8(bw.v[0]),
-                                                                        acc[i + r][0], 0, 0, 0);
-                acc[i + r][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[i + r]), as_bf16x8(bw.v[1]),
-                                                                        acc[i + r][1], 0, 0, 0);
+                acc[i + r][0] = tile_mfma<EPI>(a.v[i + r], bw.v[0], acc[i + r][0]);
+                acc[i + r][1] = tile_mfma<EPI>(a.v[i + r], bw.v[1], acc[i + r][1]);
             }
         }
     };
@@ -581,8 +599,8 @@ k_bf16_gemm_dma2(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
         o.v[1] = p[(16 + (2 * wn + 1) * 2 + kk) * 64];
     };
     auto mf_all = [&](const Half& a, const BHalf& bw, int i) {
-        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[i]), as_bf16x8(bw.v[0]), acc[i][0], 0, 0, 0);
-        acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a.v[i]), as_bf16x8(bw.v[1]), acc[i][1], 0, 0, 0);
+        acc[i][0] = tile_mfma<EPI>(a.v[i], bw.v[0], acc[i][0]);
+        acc[i][1] = tile_mfma<EPI>(a.v[i], bw.v[1], acc[i][1]);
     };
     auto mf_some = [&](const Half& a, const BHalf& bw, int i) {
         if (i < cnt) mf_all(a, bw, i);
