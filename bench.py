@@ -296,7 +296,7 @@ def run_workload(s, model, args, torch, S, ee, synth, C, timed=True, with_load=F
         roof = dict(kernel="k_bf16_attn", bound="hbm", achieved=at_bytes / at_t / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
                     traffic=None)
     else:
-        roof = dict(kernel="k_bf16_gemm_dma<SWIGLU> (gate/up + SwiGLU)", bound="hbm", achieved=gu_bytes / gu_t / 1e9,
+        roof = dict(kernel="k_bf16_gemm_dma8<SWIGLU> (gate/up + SwiGLU)", bound="hbm", achieved=gu_bytes / gu_t / 1e9,
                     peak=HBM_PEAK_GBS, unit="GB/s", traffic=measured_traffic(s.batch))
     roof["frac"] = roof["achieved"] / roof["peak"]
     weights_per_layer = s.layer_params() * 2

@@ -281,12 +281,11 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
 
 // ------------------------------------------------------------------ large-batch MFMA GEMM
 // 256-row tiles (up to 256 rows per row group), 128 or 256 columns wide, one K slice per
-// workgroup, operands fed by LDS-DMA loads (k_bf16_gemm_dma, k_bf16_gemm_dma2 below).  When K
+// workgroup, operands fed by LDS-DMA loads (k_bf16_gemm_dma8, k_bf16_gemm_dma2 below).  When K
 // is sliced, every slice writes an fp32 partial tile into its own plane and a later kernel adds
 // the planes in slice order, so the result does not depend on timing and needs no atomics.
 #define BIG_THREADS 256
 struct Half { uint4 v[4]; };   // A operands of one K half: 4 row tiles
-struct Oct { uint4 v[8]; };    // A operands of one K half: 8 row tiles
 
 // One 32x32x16 step of a result tile.  A and B operands have the same register layout, so handing
 // them over in the other order gives the transposed tile at no cost.  The exit head wants that: a
@@ -364,28 +363,16 @@ __device__ __forceinline__ void epilogue_tile(const EpiArgs& ep, const floatx16&
     }
 }
 
-// ------------------------------------------------------------------ 256-column tile fed by LDS-DMA loads
-// 256 rows x 256 columns per workgroup, the four waves side by side along N: wave w owns columns
-// 64 w .. 64 w + 63 for all eight row tiles (8 x 2 MFMA tiles of 32x32, 256 accumulator
-// registers).  No operand passes through registers on its way in: every wave sends its four X
-// tiles and its own four W tiles of a 32-wide K stage straight from global memory into LDS (64
+// ------------------------------------------------------------------ tile GEMMs fed by LDS-DMA loads
+// No operand passes through registers on its way in: the waves of a workgroup send the X and W
+// tiles of a 32-wide K stage straight from global memory into LDS (global_load_lds_dwordx4: 64
 // lanes x 16 B per instruction, lane l lands at byte 16 l of the slot), and all MFMA operands are
 // read from LDS.  A load that returns into registers holds up the matrix pipe of its SIMD while
 // it writes back (measured: streaming time and MFMA time add up, even across waves); a load
-// into LDS does not, so here the weight stream runs under the MFMAs.
-//   LDS: 4 stage buffers x 32 slots of 1 KiB: slots 0..15 X tile (row tile m, K half kk) at
-//        2 m + kk, slots 16..31 W tile (wave w, K half kk, column tile ns) at 16 + 4 w + 2 kk + ns
-//   stage t: MFMAs of stage t; LDS reads of its second K half, then of the first K half of
-//        stage t+1; the 8 loads of stage t+3 into the buffer stage t-1 used, one behind each
-//        MFMA group (a burst would queue up in the vector-memory path and hold the wave); at
-//        the end wait until only those 8 are in flight (stage t+2 has landed), then the barrier
-//        that makes stage t+2 readable by all waves.
-// The loop exists once per number of live row tiles (1..8), so the steady state has no branch.
-// T is a multiple of 4 and the loop is unrolled by 4: every buffer is named statically.  Loads
-// past the end re-read the last stage.  The compiler does not see these loads, so it adds no
-// wait of its own; the waits are written out here.
-struct BPair { uint4 v[2]; };   // W operands of one K half: 2 column tiles
-
+// into LDS does not, so here the weight stream runs under the MFMAs.  The loads of a stage are
+// issued one behind each MFMA group (a burst would queue up in the vector-memory path and hold the
+// wave).  The compiler does not see these loads, so it adds no wait of its own; the waits are
+// written out.  Loads past the end of the K slice re-read its last stage.
 // tile and lds_byte are the same in all lanes; going through readfirstlane makes that explicit, so
 // that both end up in scalar registers whatever the optimiser did to the address arithmetic
 // NT: the tile is read once per launch (weights): a non-temporal load, which does not hold a line of
@@ -404,135 +391,9 @@ __device__ __forceinline__ void dma_tile(const uint4* tile, unsigned lane_bytes,
                      : "memory");
 }
 
-template <int EPI>
-__global__ void __launch_bounds__(BIG_THREADS, 1)
-k_bf16_gemm_dma(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int NBs, int nb_off,
-                int n_tiles, int splits, const int32_t* __restrict__ n_ptr, int B, float* __restrict__ partial,
-                int64_t part_plane, int part_ld, EpiArgs ep, ZBatch zb) {
-    __shared__ uint4 lds[4][32][64];
-    const int n = min(*n_ptr, B);
-    const int rg = blockIdx.y;
-    const int row_base = rg * 256;
-    if (row_base >= n) return;
-    if (zb.w_tab) Wp = reinterpret_cast<const uint4*>(zb.w_tab[zb.z0 + blockIdx.z]);
-    Xp += (int64_t)blockIdx.z * zb.x_stride;
-    ep.out += (int64_t)blockIdx.z * zb.out_stride;
-    const int mbs = min(8, (n - row_base + 31) >> 5);
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int tile = blockIdx.x / splits, sp = blockIdx.x % splits;
-    const int nbw = (tile * 4 + wave) * 2;                   // this wave's two tile-rows of W
-    const int KS4 = KB >> 3;                                 // groups of four 32-wide K stages
-    const int ks_lo = 4 * (int)(((int64_t)KS4 * sp) / splits), ks_hi = 4 * (int)(((int64_t)KS4 * (sp + 1)) / splits);
-    const int T = ks_hi - ks_lo;                             // stages of this slice: a positive multiple of 4
-    const uint4* xg = Xp + ((int64_t)rg * 8 * KB) * 64;      // uniform bases; the lane offset goes in a register
-    const uint4* wg = Wp + (int64_t)(nb_off + nbw) * 64;
-    const unsigned lane_bytes = (unsigned)lane * 16u;
-    const unsigned lds0 = (unsigned)(size_t)&lds[0][0][0];
-
-    floatx16 acc[8][2];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    // j-th load of stage t into buffer buf.  j = 0..3: W tiles (K half j/2, column tile j%2).
-    // j = 4..: X slots; only the 2 MBS slots of live row tiles are needed, dealt out round-robin:
-    // this wave takes slots wave, wave + 4, ... (ceil(MBS / 2) of them; a slot past the live ones
-    // re-reads a live tile, so that every wave issues the same number of loads per stage and
-    // one wait count fits all).  Stages past the end re-read the last.
-    auto issue = [&](auto mbs_c, int t, int buf, int j) {
-        constexpr int MBS = decltype(mbs_c)::value;
-        const int kb0 = 2 * (ks_lo + min(t, T - 1));
-        if (j < 4) {
-            const int kk = j >> 1, ns = j & 1;
-            dma_tile<true>(wg + ((int64_t)(kb0 + kk) * NBs + ns) * 64, lane_bytes,
-                     lds0 + (unsigned)((buf * 32 + 16 + wave * 4 + kk * 2 + ns) << 10));
-        } else if (j - 4 < (MBS + 1) / 2) {
-            const int slot = wave + 4 * (j - 4);             // = 2 m + kk
-            const int src = min(slot, 2 * MBS - 1);
-            dma_tile(xg + ((int64_t)(src >> 1) * KB + kb0 + (src & 1)) * 64, lane_bytes,
-                     lds0 + (unsigned)((buf * 32 + slot) << 10));
-        }
-    };
-    Oct a0, a1;
-    BPair b0, b1;
-    auto rd_a = [&](auto mbs_c, Oct& o, int buf, int kk, int i) {      // row tiles i, i+1
-        constexpr int MBS = decltype(mbs_c)::value;
-        if (i < MBS) o.v[i] = lds[buf][i * 2 + kk][lane];
-        if (i + 1 < MBS) o.v[i + 1] = lds[buf][(i + 1) * 2 + kk][lane];
-    };
-    auto rd_b = [&](BPair& o, int buf, int kk) {
-        o.v[0] = lds[buf][16 + wave * 4 + kk * 2][lane];
-        o.v[1] = lds[buf][16 + wave * 4 + kk * 2 + 1][lane];
-    };
-    auto mf_d = [&](auto mbs_c, const Oct& a, const BPair& bw, int i) {   // 4 MFMAs: row tiles i, i+1
-        constexpr int MBS = decltype(mbs_c)::value;
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            if (i + r < MBS) {
-                acc[i + r][0] = tile_mfma<EPI>(a.v[i + r], bw.v[0], acc[i + r][0]);
-                acc[i + r][1] = tile_mfma<EPI>(a.v[i + r], bw.v[1], acc[i + r][1]);
-            }
-        }
-    };
-#define SB __builtin_amdgcn_sched_barrier(0);
-// at most N_LOADS loads in flight = everything older than the stage just issued has landed
-#define STAGE_END(N_LOADS) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N_LOADS) : "memory");
-#define DMA_STAGE(U)                                                                          \
-    mf_d(MC, a0, b0, 0); SB issue(MC, t0 + (U) + 3, ((U) + 3) & 3, 0); rd_a(MC, a1, (U), 1, 0); rd_a(MC, a1, (U), 1, 2); rd_b(b1, (U), 1); SB \
-    mf_d(MC, a0, b0, 2); SB issue(MC, t0 + (U) + 3, ((U) + 3) & 3, 1); rd_a(MC, a1, (U), 1, 4); rd_a(MC, a1, (U), 1, 6); SB \
-    mf_d(MC, a0, b0, 4); SB issue(MC, t0 + (U) + 3, ((U) + 3) & 3, 2); SB                         \
-    mf_d(MC, a0, b0, 6); SB issue(MC, t0 + (U) + 3, ((U) + 3) & 3, 3); SB                         \
-    mf_d(MC, a1, b1, 0); SB issue(MC, t0 + (U) + 3, ((U) + 3) & 3, 4); rd_a(MC, a0, ((U) + 1) & 3, 0, 0); rd_a(MC, a0, ((U) + 1) & 3, 0, 2); rd_b(b0, ((U) + 1) & 3, 0); SB \
-    mf_d(MC, a1, b1, 2); SB issue(MC, t0 + (U) + 3, ((U) + 3) & 3, 5); rd_a(MC, a0, ((U) + 1) & 3, 0, 4); rd_a(MC, a0, ((U) + 1) & 3, 0, 6); SB \
-    mf_d(MC, a1, b1, 4); SB issue(MC, t0 + (U) + 3, ((U) + 3) & 3, 6); SB                         \
-    mf_d(MC, a1, b1, 6); SB issue(MC, t0 + (U) + 3, ((U) + 3) & 3, 7); SB                         \
-    STAGE_END(4 + (decltype(MC)::value + 1) / 2)
-#define DMA_LOOP(N)                                                                           \
-    case N: {                                                                                 \
-        const std::integral_constant<int, N> MC{};                                            \
-        /* stages 0, 1, 2 on their way; 0 and 1 must have landed before the first reads */    \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) issue(MC, 0, 0, j);                     \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) issue(MC, 1, 1, j);                     \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) issue(MC, 2, 2, j);                     \
-        STAGE_END(4 + (N + 1) / 2)                                                            \
-        rd_b(b0, 0, 0);                                                                       \
-        rd_a(MC, a0, 0, 0, 0); rd_a(MC, a0, 0, 0, 2); rd_a(MC, a0, 0, 0, 4); rd_a(MC, a0, 0, 0, 6); \
-        for (int t0 = 0; t0 < T; t0 += 4) { DMA_STAGE(0) DMA_STAGE(1) DMA_STAGE(2) DMA_STAGE(3) } \
-    } break;
-
-    a0 = Oct{}; a1 = Oct{};
-    b1 = BPair{};
-    switch (mbs) {
-        DMA_LOOP(1) DMA_LOOP(2) DMA_LOOP(3) DMA_LOOP(4) DMA_LOOP(5) DMA_LOOP(6) DMA_LOOP(7) DMA_LOOP(8)
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the re-reads past the end have landed before the block ends
-#undef DMA_LOOP
-#undef DMA_STAGE
-#undef STAGE_END
-#undef SB
-#define EPI_ROW(E, ARGS, I) \
-    if ((I) < mbs) epilogue_tile<E>(ARGS, acc[I][0], acc[I][1], row_base + 32 * (I), n, nbw, lane);
-    if (splits > 1) {   // K slices: fp32 partial planes, added up by a later kernel
-        EpiArgs pe = ep;
-        pe.out = partial + (int64_t)sp * part_plane;
-        pe.ldo = part_ld;
-        EPI_ROW(EPI_STORE, pe, 0) EPI_ROW(EPI_STORE, pe, 1) EPI_ROW(EPI_STORE, pe, 2) EPI_ROW(EPI_STORE, pe, 3)
-        EPI_ROW(EPI_STORE, pe, 4) EPI_ROW(EPI_STORE, pe, 5) EPI_ROW(EPI_STORE, pe, 6) EPI_ROW(EPI_STORE, pe, 7)
-        return;
-    }
-    EPI_ROW(EPI, ep, 0) EPI_ROW(EPI, ep, 1) EPI_ROW(EPI, ep, 2) EPI_ROW(EPI, ep, 3)
-    EPI_ROW(EPI, ep, 4) EPI_ROW(EPI, ep, 5) EPI_ROW(EPI, ep, 6) EPI_ROW(EPI, ep, 7)
-#undef EPI_ROW
-}
-
 // ------------------------------------------------------------------ 128-column tile fed by LDS-DMA loads
 // 256 rows x 128 columns per workgroup, waves 2 x 2: wave (wm, wn) owns rows 128 wm .. +127
-// and columns 64 wn .. +63 (4 x 2 MFMA tiles, 128 accumulator registers); the operand path
-// is that of k_bf16_gemm_dma.  LDS: 6 stage buffers x 24 slots: X tile (row tile m, K half kk)
+// and columns 64 wn .. +63 (4 x 2 MFMA tiles, 128 accumulator registers).  LDS: 6 stage buffers x 24 slots: X tile (row tile m, K half kk)
 // at 2 m + kk, W tile (column tile nb of the 4, K half kk) at 16 + 2 nb + kk.  A wave sends 4 X
 // tiles and 2 W tiles per stage and reads the 8 + 4 it needs.  For products with few columns
 // (QKV, O projection, exit head) it gives twice as many workgroups per K slice as the 256-column tile.
@@ -638,6 +499,128 @@ k_bf16_gemm_dma2(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #undef DMA2_LOOP
 #undef DMA2_STAGE
+#undef STAGE_END
+#undef SB
+#define EPI_ROW(E, ARGS, I) \
+    if (4 * wm + (I) < mbs) epilogue_tile<E>(ARGS, acc[I][0], acc[I][1], row_base + 32 * (4 * wm + (I)), n, nbw, lane);
+    if (splits > 1) {
+        EpiArgs pe = ep;
+        pe.out = partial + (int64_t)sp * part_plane;
+        pe.ldo = part_ld;
+        EPI_ROW(EPI_STORE, pe, 0) EPI_ROW(EPI_STORE, pe, 1) EPI_ROW(EPI_STORE, pe, 2) EPI_ROW(EPI_STORE, pe, 3)
+        return;
+    }
+    EPI_ROW(EPI, ep, 0) EPI_ROW(EPI, ep, 1) EPI_ROW(EPI, ep, 2) EPI_ROW(EPI, ep, 3)
+#undef EPI_ROW
+}
+
+// ------------------------------------------------------------------ 256-column tile, two waves per SIMD
+// 256 rows x 256 columns per workgroup, eight waves (2 x 4): wave (wm, wn) owns rows
+// 128 wm .. +127 and columns 64 wn .. +63 (4 x 2 MFMA tiles, 128 accumulator registers), so two waves
+// share a SIMD and one computes while the other waits at a barrier or for LDS (an MFMA-only
+// kernel issues 10 % more per SIMD with two waves than with one; against four waves that own
+// 8 x 2 tiles each, gate/up is 4-6 % faster at 160 to 512 rows and the same at 64).  Used for the
+// products with many columns (gate/up with the SwiGLU epilogue, down, the K/V of skipped layers).  LDS: 5 stage buffers x 32 slots
+// (X tile (row tile m, K half kk) at 2 m + kk, W tile (column tile nb of 8, K half kk) at
+// 16 + 2 nb + kk) = all 160 KiB.  A wave sends 2 X and 2 W tiles per stage, four stages ahead, and
+// may leave two stages in flight at the barrier: a load has two to three stages to land.
+template <int EPI>
+__global__ void __launch_bounds__(512, 2)
+k_bf16_gemm_dma8(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int NBs, int nb_off,
+                 int n_tiles, int splits, const int32_t* __restrict__ n_ptr, int B, float* __restrict__ partial,
+                 int64_t part_plane, int part_ld, EpiArgs ep, ZBatch zb) {
+    __shared__ uint4 lds[5][32][64];
+    const int n = min(*n_ptr, B);
+    const int rg = blockIdx.y;
+    const int row_base = rg * 256;
+    if (row_base >= n) return;
+    if (zb.w_tab) Wp = reinterpret_cast<const uint4*>(zb.w_tab[zb.z0 + blockIdx.z]);
+    Xp += (int64_t)blockIdx.z * zb.x_stride;
+    ep.out += (int64_t)blockIdx.z * zb.out_stride;
+    const int mbs = min(8, (n - row_base + 31) >> 5);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+    const int cnt = max(0, min(4, mbs - 4 * wm));            // live 32-row tiles of this wave
+    const int tile = blockIdx.x / splits, sp = blockIdx.x % splits;
+    const int nbw = (tile * 4 + wn) * 2;                     // first of this wave's two tile-rows of W
+    const int KS4 = KB >> 3;
+    const int ks_lo = 4 * (int)(((int64_t)KS4 * sp) / splits), ks_hi = 4 * (int)(((int64_t)KS4 * (sp + 1)) / splits);
+    const int T = ks_hi - ks_lo;                             // stages of this slice: a positive multiple of 4
+    const uint4* xg = Xp + ((int64_t)rg * 8 * KB) * 64;
+    const uint4* wg = Wp + (int64_t)(nb_off + tile * 8) * 64;   // the tile's eight tile-rows of W
+    const unsigned lane_bytes = (unsigned)lane * 16u;
+    const unsigned lds0 = (unsigned)(size_t)&lds[0][0][0];
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // j-th load of stage t: j = 0, 1 the X tile of row tile `wave`, K half j (a dead row tile re-reads
+    // a live one: every wave issues the same number of loads); j = 2, 3 the W tile of column tile
+    // `wave`, K half j - 2
+    auto issue = [&](int t, int buf, int j) {
+        const int kb0 = 2 * (ks_lo + min(t, T - 1));
+        if (j < 2) {
+            const int m = min(wave, mbs - 1);
+            dma_tile(xg + ((int64_t)m * KB + kb0 + j) * 64, lane_bytes, lds0 + (unsigned)((buf * 32 + wave * 2 + j) << 10));
+        } else {
+            const int kk = j - 2;
+            dma_tile<true>(wg + ((int64_t)(kb0 + kk) * NBs + wave) * 64, lane_bytes,
+                           lds0 + (unsigned)((buf * 32 + 16 + wave * 2 + kk) << 10));
+        }
+    };
+    Half a0, a1;
+    BHalf b0, b1;
+    auto rd_a = [&](Half& o, int buf, int kk, int i) { o.v[i] = (&lds[0][0][lane] + buf * (32 * 64))[((4 * wm + i) * 2 + kk) * 64]; };
+    auto rd_b = [&](BHalf& o, int buf, int kk) {
+        const uint4* p = &lds[0][0][lane] + buf * (32 * 64);
+        o.v[0] = p[(16 + (2 * wn) * 2 + kk) * 64];
+        o.v[1] = p[(16 + (2 * wn + 1) * 2 + kk) * 64];
+    };
+    auto mf_all = [&](const Half& a, const BHalf& bw, int i) {
+        acc[i][0] = tile_mfma<EPI>(a.v[i], bw.v[0], acc[i][0]);
+        acc[i][1] = tile_mfma<EPI>(a.v[i], bw.v[1], acc[i][1]);
+    };
+    auto mf_some = [&](const Half& a, const BHalf& bw, int i) {
+        if (i < cnt) mf_all(a, bw, i);
+    };
+#define SB __builtin_amdgcn_sched_barrier(0);
+// 8 loads (two stages) may stay in flight: everything up to stage t+2 has landed
+#define STAGE_END asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // bc / bn / bi: buffers of the current stage, the next one and the one being requested (stage + 4)
+#define DMA8_STAGE(MF, U)                                                                     \
+    MF(a0, b0, 0); SB issue(t0 + (U) + 4, bi, 0); rd_a(a1, bc, 1, 0); rd_a(a1, bc, 1, 1); rd_b(b1, bc, 1); SB \
+    MF(a0, b0, 1); SB issue(t0 + (U) + 4, bi, 1); rd_a(a1, bc, 1, 2); rd_a(a1, bc, 1, 3); SB  \
+    MF(a0, b0, 2); SB                                                                         \
+    MF(a0, b0, 3); SB                                                                         \
+    MF(a1, b1, 0); SB issue(t0 + (U) + 4, bi, 2); rd_a(a0, bn, 0, 0); rd_a(a0, bn, 0, 1); rd_b(b0, bn, 0); SB \
+    MF(a1, b1, 1); SB issue(t0 + (U) + 4, bi, 3); rd_a(a0, bn, 0, 2); rd_a(a0, bn, 0, 3); SB  \
+    MF(a1, b1, 2); SB                                                                         \
+    MF(a1, b1, 3); SB                                                                         \
+    STAGE_END                                                                                 \
+    bc = bn; bn = bn == 4 ? 0 : bn + 1; bi = bi == 4 ? 0 : bi + 1;
+#define DMA8_LOOP(MF) \
+    for (int t0 = 0; t0 < T; t0 += 4) { DMA8_STAGE(MF, 0) DMA8_STAGE(MF, 1) DMA8_STAGE(MF, 2) DMA8_STAGE(MF, 3) }
+
+#pragma unroll
+    for (int st = 0; st < 4; ++st)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) issue(st, st, j);
+    int bc = 0, bn = 1, bi = 4;
+    STAGE_END                                  // stages 0 and 1 have landed
+    a1 = Half{};
+    b1 = BHalf{};
+    rd_a(a0, 0, 0, 0); rd_a(a0, 0, 0, 1); rd_a(a0, 0, 0, 2); rd_a(a0, 0, 0, 3);
+    rd_b(b0, 0, 0);
+    if (cnt == 4) { DMA8_LOOP(mf_all) } else { DMA8_LOOP(mf_some) }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#undef DMA8_LOOP
+#undef DMA8_STAGE
 #undef STAGE_END
 #undef SB
 #define EPI_ROW(E, ARGS, I) \
@@ -1045,8 +1028,9 @@ static bool gemm_tiled(const ee_batch* b, const void* X, const void* W, int N, i
     int row_groups = (B + 255) / 256;
     int Mpad = (B + 31) / 32 * 32;
     int KS = K / 32;
-    // the 256-column tile reads less from LDS per MFMA; worth it when it still gives every CU a
-    // workgroup, or when K is long enough that a deeper K slicing costs little
+    // the 256-column tile loads each activation tile once per 256 columns instead of once per 128;
+    // worth it when it still gives every CU a workgroup, or when K is long enough that a deeper K
+    // slicing costs little
     bool wide = (N % 256 == 0) && ((N / 256) * row_groups * nz >= 200 || (EPI == EPI_RESID && K >= 2 * N));
     int n_tiles = wide ? N / 256 : N / 128;
     int splits = 1;
@@ -1057,7 +1041,7 @@ static bool gemm_tiled(const ee_batch* b, const void* X, const void* W, int N, i
     }
     dim3 grid(n_tiles * splits, row_groups, nz);
     if (wide)
-        hipLaunchKernelGGL((k_bf16_gemm_dma<EPI>), grid, dim3(BIG_THREADS), 0, s, (const uint4*)X, (const uint4*)W,
+        hipLaunchKernelGGL((k_bf16_gemm_dma8<EPI>), grid, dim3(512), 0, s, (const uint4*)X, (const uint4*)W,
                            K / 16, NBs, nb_off, n_tiles, splits, n_ptr, B, b->wsp<float>(b->W.gemm_part),
                            (int64_t)Mpad * N, N, ep, zb);
     else
