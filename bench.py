@@ -427,7 +427,7 @@ def main():
     max_cap = int(synth.capacity_for(np.array([s.ctx_hi]), max(total_steps, s.steps), 32)[0])
     model = build_device_model(s, S, torch, max_cap, s.seed)
     if args.context_pass_only is not None:
-        for n in (args.context_pass_only or [256]):
+        for n in (args.context_pass_only or [1024]):
             print(json.dumps(run_context_pass(s, model, torch, S, ee, synth, C, n)), flush=True)
         return
     head = run_workload(s, model, args, torch, S, ee, synth, C, with_load=not args.no_layer_load)
@@ -438,7 +438,7 @@ def main():
             sweep[str(b)] = {k: r[k] for k in ("tokens_per_s", "ms_per_step", "exit_fractions", "avg_layers_per_token",
                                                "gate_up_gemm", "attention", "layer_gemms",
                                                "exit_head_plus_compaction_us_per_step")}
-    context_pass = None if args.no_context_pass else run_context_pass(s, model, torch, S, ee, synth, C, 256)
+    context_pass = None if args.no_context_pass else run_context_pass(s, model, torch, S, ee, synth, C, 1024)
     exits = s.resident_exits
     out = dict(metric="decoded tokens/s/GPU at Llama2-70B shape", value=head["tokens_per_s"], unit="tokens/s", n_gpus=1,
                steps=args.steps, warmup=args.warmup, ms_per_step=head["ms_per_step"], higher_is_better=True,
