@@ -14,6 +14,13 @@
  * Llama-family layer (RMSNorm, rotary embedding, grouped-query attention,
  * SwiGLU).
  *
+ * Around the step, in the order of this file: the context pass that builds the
+ * cache a step reads (ee_prefill); loading further layers while steps run and
+ * giving the cached tokens keys and values in them (ee_model_set_layer_on,
+ * ee_hstore_*, ee_backfill_kv); and the two device-side records the serving
+ * loop reads instead of per-row outputs, the confidence-breach counter
+ * (ee_cbc_*) and the Performance History Table row (ee_pht_*).
+ *
  * Conventions
  *   - Plain C ABI.  Every call returns EE_OK (0) or a negative ee_status;
  *     ee_last_error() gives a thread-local message for the last failure.
