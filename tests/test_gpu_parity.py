@@ -38,6 +38,12 @@ PARTIAL = synth.CONFIGS["codellama_34b_r32"].with_(name="partial_bf16", n_layers
                                                    ctx_lo=30, ctx_hi=100, steps=2)
 
 
+# 27 skipped layers filled in one launch: the multi-layer path of the 256-column tile kernel
+DEEP = synth.CONFIGS["llama2_7b"].with_(name="deep_bf16", n_layers=28, resident=28, d_model=512, n_q_heads=8,
+                                        n_kv_heads=8, d_ffn=1024, vocab=2048, exit_layers=(1, 28),
+                                        thresholds=(0.6, 0.0), batch=70, ctx_lo=5, ctx_hi=70, steps=2)
+
+
 @pytest.fixture(scope="module")
 def sides():
     cache = {}
@@ -151,7 +157,7 @@ def test_calls_one_by_one(s):
 
 
 # ---------------------------------------------------------------- whole steps
-@pytest.mark.parametrize("s", [TINY, MHA, MID, BIG_M, PARTIAL], ids=lambda s: s.name)
+@pytest.mark.parametrize("s", [TINY, MHA, MID, BIG_M, PARTIAL, DEEP], ids=lambda s: s.name)
 def test_decode_steps(s):
     _say(f"[case] decode_steps {s.name} seed={s.seed} B={s.batch} steps={s.steps}")
     o, g = _fresh(s, jitter=0.0)
@@ -170,15 +176,18 @@ def test_decode_steps(s):
     assert sticky.sum() <= max(3, s.batch * s.steps // 10), f"{sticky.sum()} of {s.batch} rows excluded"
     if len(s.resident_exits) > 1:
         assert len(layers_seen) > 1, "workload must use more than one exit"
-    # cache after the steps: all positions of sampled rows, every resident layer
+    # cache after the steps: all positions of sampled rows, every resident layer.  bf16: 1e-2 normwise
+    # for the models of up to 6 layers; the 28-layer model gets the 2e-2 of the hidden states, its
+    # deepest keys come from a state that has been through 27 layers of operand rounding
+    kv_tol = (1e-2 if s.resident <= 8 else TOL["bf16"]) if s.dtype == "bf16" else 1e-5
     for b in range(0, s.batch, max(1, s.batch // 4)):
         if sticky[b]:
             continue
         n = int(o.pos[b])
         for l in range(1, s.resident + 1):
             K, V = g.kv.read_context(l, b, n)
-            wk, okk = rows_close(K.reshape(1, -1), o.kv.K[l - 1, b, :, :n].reshape(1, -1), 1e-2 if s.dtype == "bf16" else 1e-5)
-            wv, okv = rows_close(V.reshape(1, -1), o.kv.V[l - 1, b, :, :n].reshape(1, -1), 1e-2 if s.dtype == "bf16" else 1e-5)
+            wk, okk = rows_close(K.reshape(1, -1), o.kv.K[l - 1, b, :, :n].reshape(1, -1), kv_tol)
+            wv, okv = rows_close(V.reshape(1, -1), o.kv.V[l - 1, b, :, :n].reshape(1, -1), kv_tol)
             assert okk and okv, (b, l, wk, wv)
 
 
