@@ -1032,6 +1032,13 @@ static bool gemm_tiled(const ee_batch* b, const void* X, const void* W, int N, i
     // worth it when it still gives every CU a workgroup, or when K is long enough that a deeper K
     // slicing costs little
     bool wide = (N % 256 == 0) && ((N / 256) * row_groups * nz >= 200 || (EPI == EPI_RESID && K >= 2 * N));
+    if (!wide && N % 256 == 0 && row_groups >= 2 && nz == 1) {
+        // several row groups (context pass): the products are MFMA bound and the 256-column tile does
+        // more per MFMA issued; take it when its workgroups fill their rounds of 256 CUs no worse
+        const int ww = (N / 256) * row_groups, wn = (N / 128) * row_groups;
+        const float fill_w = (float)ww / (float)((ww + 255) / 256 * 256), fill_n = (float)wn / (float)((wn + 255) / 256 * 256);
+        wide = fill_w >= fill_n;
+    }
     int n_tiles = wide ? N / 256 : N / 128;
     int splits = 1;
     if ((EPI == EPI_STORE || EPI == EPI_RESID) && nz == 1 && n_tiles * row_groups < 200) {
