@@ -679,40 +679,67 @@ k_bf16_rope_append(const float* __restrict__ buf, int ld, int n_q, const int32_t
     // buf holds `splits` K-slice planes of the product (plane floats apart): their sum in slice
     // order is the value; splits = 1 is a finished matrix
     const float* r0 = buf + (int64_t)i * ld;
-    auto rd = [&](int x) -> float {
-        float v = r0[x];
-        for (int q = 1; q < splits; ++q) v += r0[x + (int64_t)q * plane];
+    // four consecutive values at once (x is a multiple of 4: 16-byte loads from every plane)
+    auto rd4 = [&](int x) -> float4 {
+        float4 v = *reinterpret_cast<const float4*>(r0 + x);
+        for (int q = 1; q < splits; ++q) {
+            const float4 u = *reinterpret_cast<const float4*>(r0 + x + (int64_t)q * plane);
+            v.x += u.x; v.y += u.y; v.z += u.z; v.w += u.w;
+        }
         return v;
     };
+    auto pack4 = [](float a, float b, float c, float d) -> uint2 {
+        return make_uint2(f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16), f32_to_bf16(c) | ((uint32_t)f32_to_bf16(d) << 16));
+    };
     const float* cs = rope + (int64_t)p * half * 2;
-    // the work of a row is dealt out over the gridDim.y blocks that share it
-    const int t0 = blockIdx.y * 256 + threadIdx.x, tstep = 256 * gridDim.y;
-#pragma unroll 4
-    for (int t = t0; t < n_q * half; t += tstep) {
-        int hh = t >> 6, j = t & 63;
-        float c = cs[2 * j], s = cs[2 * j + 1];
-        float a = rd(hh * hd + j), bb = rd(hh * hd + j + half);
-        float x0 = a * c - bb * s, x1 = bb * c + a * s;
-        bf16_t h0 = f32_to_bf16(x0), h1 = f32_to_bf16(x1);
-        int64_t o = ((int64_t)i * n_q + hh) * hd + j;
-        q_hi[o] = h0; q_hi[o + half] = h1;
-        q_lo[o] = f32_to_bf16(x0 - bf16_to_f32(h0));
-        q_lo[o + half] = f32_to_bf16(x1 - bf16_to_f32(h1));
-    }
+    // The work of a row, in items of four rotation pairs (q, k) or four values (v), is dealt out over
+    // the threads of the gridDim.y blocks that share the row: items [0, nq4) rotate queries, the next
+    // nk4 rotate and append keys, the last nv4 append values.
+    const int nq4 = n_q * (half / 4), nk4 = Hkv * (half / 4), nv4 = Hkv * (hd / 4);
     const int kin = n_q * hd;
     const int vin = kin + Hkv * hd;
-    for (int t = t0; t < Hkv * half; t += tstep) {
-        int g = t >> 6, j = t & 63;
-        float c = cs[2 * j], s = cs[2 * j + 1];
-        float a = rd(kin + g * hd + j), bb = rd(kin + g * hd + j + half);
-        bf16_t* base = reinterpret_cast<bf16_t*>(kv.pool) + kv_block(kv, sq, g, cap);
-        base[k_bf16_offset(p, j, hd)] = f32_to_bf16(a * c - bb * s);
-        base[k_bf16_offset(p, j + half, hd)] = f32_to_bf16(bb * c + a * s);
-    }
-    for (int t = t0; t < Hkv * hd; t += tstep) {
-        int g = t >> 7, j = t & 127;
-        bf16_t* base = reinterpret_cast<bf16_t*>(kv.pool) + kv_block(kv, sq, g, cap);
-        base[v_bf16_offset(p, j, hd)] = f32_to_bf16(rd(vin + g * hd + j));
+    for (int t = blockIdx.y * 256 + threadIdx.x; t < nq4 + nk4 + nv4; t += 256 * gridDim.y) {
+        if (t < nq4 + nk4) {
+            const bool is_q = t < nq4;
+            const int u = is_q ? t : t - nq4;
+            const int hh = u >> 4, j0 = (u & 15) * 4;                 // head, first of the four pairs
+            const int x = (is_q ? 0 : kin) + hh * hd + j0;
+            const float4 a = rd4(x), bb = rd4(x + half);
+            const float4 cs0 = *reinterpret_cast<const float4*>(cs + 2 * j0);       // c0 s0 c1 s1
+            const float4 cs1 = *reinterpret_cast<const float4*>(cs + 2 * j0 + 4);   // c2 s2 c3 s3
+            const float x0[4] = {a.x * cs0.x - bb.x * cs0.y, a.y * cs0.z - bb.y * cs0.w,
+                                 a.z * cs1.x - bb.z * cs1.y, a.w * cs1.z - bb.w * cs1.w};
+            const float x1[4] = {bb.x * cs0.x + a.x * cs0.y, bb.y * cs0.z + a.y * cs0.w,
+                                 bb.z * cs1.x + a.z * cs1.y, bb.w * cs1.z + a.w * cs1.w};
+            if (is_q) {
+                const int64_t o = ((int64_t)i * n_q + hh) * hd + j0;
+                const uint2 h0 = pack4(x0[0], x0[1], x0[2], x0[3]), h1 = pack4(x1[0], x1[1], x1[2], x1[3]);
+                *reinterpret_cast<uint2*>(q_hi + o) = h0;
+                *reinterpret_cast<uint2*>(q_hi + o + half) = h1;
+                float l0[4], l1[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    l0[k] = x0[k] - bf16_to_f32(f32_to_bf16(x0[k]));
+                    l1[k] = x1[k] - bf16_to_f32(f32_to_bf16(x1[k]));
+                }
+                *reinterpret_cast<uint2*>(q_lo + o) = pack4(l0[0], l0[1], l0[2], l0[3]);
+                *reinterpret_cast<uint2*>(q_lo + o + half) = pack4(l1[0], l1[1], l1[2], l1[3]);
+            } else {
+                // four consecutive features of a key sit side by side in the cache (same octet)
+                bf16_t* base = reinterpret_cast<bf16_t*>(kv.pool) + kv_block(kv, sq, hh, cap);
+                *reinterpret_cast<uint2*>(base + k_bf16_offset(p, j0, hd)) = pack4(x0[0], x0[1], x0[2], x0[3]);
+                *reinterpret_cast<uint2*>(base + k_bf16_offset(p, j0 + half, hd)) = pack4(x1[0], x1[1], x1[2], x1[3]);
+            }
+        } else {
+            const int u = t - nq4 - nk4;
+            const int g = u >> 5, j0 = (u & 31) * 4;
+            const float4 v = rd4(vin + g * hd + j0);
+            bf16_t* base = reinterpret_cast<bf16_t*>(kv.pool) + kv_block(kv, sq, g, cap);
+            base[v_bf16_offset(p, j0, hd)] = f32_to_bf16(v.x);
+            base[v_bf16_offset(p, j0 + 1, hd)] = f32_to_bf16(v.y);
+            base[v_bf16_offset(p, j0 + 2, hd)] = f32_to_bf16(v.z);
+            base[v_bf16_offset(p, j0 + 3, hd)] = f32_to_bf16(v.w);
+        }
     }
 }
 
@@ -980,6 +1007,45 @@ k_splitk_resid_norm(const float* __restrict__ partial, int64_t plane, int ld, in
     if (i >= n) return;
     float* hrow = h + (int64_t)idx[i] * ldh;
     const float* prow = partial + (int64_t)i * ld;
+    if ((N >> 3) <= NORM_THREADS) {
+        // at most one 8-float chunk per thread (d <= 8192): the updated chunk stays in registers for
+        // the norm instead of being read back twice; same arithmetic, same bits as the general path
+        const int c = threadIdx.x;
+        const bool has = c < (N >> 3);
+        float4 o0 = make_float4(0.f, 0.f, 0.f, 0.f), o1 = o0;
+        if (has) {
+            const float* p = prow + c * 8;
+            float4 s0 = *reinterpret_cast<const float4*>(p), s1 = *reinterpret_cast<const float4*>(p + 4);
+#pragma unroll 4
+            for (int q = 1; q < splits; ++q) {
+                const float4 v0 = *reinterpret_cast<const float4*>(p + (int64_t)q * plane);
+                const float4 v1 = *reinterpret_cast<const float4*>(p + (int64_t)q * plane + 4);
+                s0.x += v0.x; s0.y += v0.y; s0.z += v0.z; s0.w += v0.w;
+                s1.x += v1.x; s1.y += v1.y; s1.z += v1.z; s1.w += v1.w;
+            }
+            float4* hp = reinterpret_cast<float4*>(hrow + c * 8);
+            o0 = hp[0]; o1 = hp[1];
+            o0.x += s0.x; o0.y += s0.y; o0.z += s0.z; o0.w += s0.w;
+            o1.x += s1.x; o1.y += s1.y; o1.z += s1.z; o1.w += s1.w;
+            hp[0] = o0; hp[1] = o1;
+        }
+        if (gain == nullptr) return;
+        float ss = 0.f;
+        if (has) ss += o0.x * o0.x + o0.y * o0.y + o0.z * o0.z + o0.w * o0.w + o1.x * o1.x + o1.y * o1.y + o1.z * o1.z + o1.w * o1.w;
+        ss = block_sum<NORM_THREADS>(ss, red);
+        const float inv = 1.0f / sqrtf(ss / (float)N + eps);
+        if (has) {
+            const float4* g4 = reinterpret_cast<const float4*>(gain);
+            const float4 ga = g4[2 * c], gb = g4[2 * c + 1];
+            uint4 o;
+            o.x = pack2((o0.x * inv) * ga.x, (o0.y * inv) * ga.y);
+            o.y = pack2((o0.z * inv) * ga.z, (o0.w * inv) * ga.w);
+            o.z = pack2((o1.x * inv) * gb.x, (o1.y * inv) * gb.y);
+            o.w = pack2((o1.z * inv) * gb.z, (o1.w * inv) * gb.w);
+            xout[afrag_chunk(i, c * 8, N >> 4)] = o;
+        }
+        return;
+    }
     for (int c = threadIdx.x; c < (N >> 3); c += NORM_THREADS) {
         const float* p = prow + c * 8;
         float4 s0 = *reinterpret_cast<const float4*>(p), s1 = *reinterpret_cast<const float4*>(p + 4);
