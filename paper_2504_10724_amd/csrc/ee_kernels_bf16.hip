@@ -437,19 +437,26 @@ k_bf16_gemm_dma2(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // j-th load of stage t: j = 0..3 X tiles (row tile 2 wave + j/2, K half j%2); j = 4, 5 the W
-    // slots 2 wave + (j - 4) of the stage's eight (column tile q/2, K half q%2)
-    auto issue = [&](int t, int buf, int j) {
-        const int kb0 = 2 * (ks_lo + min(t, T - 1));
-        if (j < 4) {
-            const int mt = 2 * wave + (j >> 1);
-            const int m = min(mt, mbs - 1);
-            dma_tile(xg + ((int64_t)m * KB + kb0 + (j & 1)) * 64, lane_bytes,
-                     lds0 + (unsigned)((buf * 24 + mt * 2 + (j & 1)) << 10));
-        } else {
-            const int q = 2 * wave + (j - 4), nb = q >> 1, kk = q & 1;
-            dma_tile<true>(wg + ((int64_t)(kb0 + kk) * NBs + nb) * 64, lane_bytes, lds0 + (unsigned)((buf * 24 + 16 + q) << 10));
-        }
+    // j-th load of a stage: j = 0..3 X tiles (row tile 2 wave + j/2, K half j%2; a dead row tile
+    // re-reads a live one); j = 4, 5 the W slots 2 wave + (j - 4) of the stage's eight (column tile
+    // q/2, K half q%2).  A tile's address is the stage's base pointer (scalar, computed once per
+    // stage) plus a lane offset that is the same in every stage, so a load costs few instructions.
+    unsigned voff[6];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int m = min(2 * wave + (j >> 1), mbs - 1);
+        voff[j] = lane_bytes + ((unsigned)(m * KB + (j & 1)) << 10);
+    }
+#pragma unroll
+    for (int j = 4; j < 6; ++j) {
+        const int q = 2 * wave + (j - 4), nb = q >> 1, kk = q & 1;
+        voff[j] = lane_bytes + ((unsigned)(kk * NBs + nb) << 10);
+    }
+    auto x_base = [&](int t) { return xg + (int64_t)(2 * (ks_lo + min(t, T - 1))) * 64; };
+    auto w_base = [&](int t) { return wg + (int64_t)(2 * (ks_lo + min(t, T - 1))) * NBs * 64; };
+    auto issue = [&](const uint4* xs, const uint4* ws, int buf, int j) {
+        if (j < 4) dma_tile(xs, voff[j], lds0 + (unsigned)((buf * 24 + (2 * wave + (j >> 1)) * 2 + (j & 1)) << 10));
+        else dma_tile<true>(ws, voff[j], lds0 + (unsigned)((buf * 24 + 16 + 2 * wave + (j - 4)) << 10));
     };
     Half a0, a1;
     BHalf b0, b1;
@@ -472,15 +479,16 @@ k_bf16_gemm_dma2(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
     // bc / bn / bi: buffers of the current stage, the next one and the one being requested (stage + 5);
     // six buffers and an unroll of four do not divide, so the indices are counted at run time
 #define DMA2_STAGE(MF, U)                                                                     \
-    MF(a0, b0, 0); SB issue(t0 + (U) + 5, bi, 0); rd_a(a1, bc, 1, 0); rd_a(a1, bc, 1, 1); rd_b(b1, bc, 1); SB \
-    MF(a0, b0, 1); SB issue(t0 + (U) + 5, bi, 1); rd_a(a1, bc, 1, 2); rd_a(a1, bc, 1, 3); SB  \
-    MF(a0, b0, 2); SB issue(t0 + (U) + 5, bi, 2); SB                                          \
-    MF(a0, b0, 3); SB issue(t0 + (U) + 5, bi, 3); SB                                          \
-    MF(a1, b1, 0); SB issue(t0 + (U) + 5, bi, 4); rd_a(a0, bn, 0, 0); rd_a(a0, bn, 0, 1); rd_b(b0, bn, 0); SB \
-    MF(a1, b1, 1); SB issue(t0 + (U) + 5, bi, 5); rd_a(a0, bn, 0, 2); rd_a(a0, bn, 0, 3); SB  \
+    { const uint4* xs_ = x_base(t0 + (U) + 5); const uint4* ws_ = w_base(t0 + (U) + 5);       \
+    MF(a0, b0, 0); SB issue(xs_, ws_, bi, 0); rd_a(a1, bc, 1, 0); rd_a(a1, bc, 1, 1); rd_b(b1, bc, 1); SB \
+    MF(a0, b0, 1); SB issue(xs_, ws_, bi, 1); rd_a(a1, bc, 1, 2); rd_a(a1, bc, 1, 3); SB      \
+    MF(a0, b0, 2); SB issue(xs_, ws_, bi, 2); SB                                              \
+    MF(a0, b0, 3); SB issue(xs_, ws_, bi, 3); SB                                              \
+    MF(a1, b1, 0); SB issue(xs_, ws_, bi, 4); rd_a(a0, bn, 0, 0); rd_a(a0, bn, 0, 1); rd_b(b0, bn, 0); SB \
+    MF(a1, b1, 1); SB issue(xs_, ws_, bi, 5); rd_a(a0, bn, 0, 2); rd_a(a0, bn, 0, 3); SB      \
     MF(a1, b1, 2); SB                                                                         \
     MF(a1, b1, 3); SB                                                                         \
-    STAGE_END                                                                                 \
+    STAGE_END }                                                                               \
     bc = bn; bn = bn == 5 ? 0 : bn + 1; bi = bi == 5 ? 0 : bi + 1;
 #define DMA2_LOOP(MF) \
     for (int t0 = 0; t0 < T; t0 += 4) { DMA2_STAGE(MF, 0) DMA2_STAGE(MF, 1) DMA2_STAGE(MF, 2) DMA2_STAGE(MF, 3) }
@@ -488,7 +496,7 @@ k_bf16_gemm_dma2(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
 #pragma unroll
     for (int st = 0; st < 5; ++st)
 #pragma unroll
-        for (int j = 0; j < 6; ++j) issue(st, st, j);
+        for (int j = 0; j < 6; ++j) issue(x_base(st), w_base(st), st, j);
     int bc = 0, bn = 1, bi = 5;
     STAGE_END                                  // stages 0 and 1 have landed
     a1 = Half{};
@@ -560,19 +568,20 @@ k_bf16_gemm_dma8(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // j-th load of stage t: j = 0, 1 the X tile of row tile `wave`, K half j (a dead row tile re-reads
+    // j-th load of a stage: j = 0, 1 the X tile of row tile `wave`, K half j (a dead row tile re-reads
     // a live one: every wave issues the same number of loads); j = 2, 3 the W tile of column tile
-    // `wave`, K half j - 2
-    auto issue = [&](int t, int buf, int j) {
-        const int kb0 = 2 * (ks_lo + min(t, T - 1));
-        if (j < 2) {
-            const int m = min(wave, mbs - 1);
-            dma_tile(xg + ((int64_t)m * KB + kb0 + j) * 64, lane_bytes, lds0 + (unsigned)((buf * 32 + wave * 2 + j) << 10));
-        } else {
-            const int kk = j - 2;
-            dma_tile<true>(wg + ((int64_t)(kb0 + kk) * NBs + wave) * 64, lane_bytes,
-                           lds0 + (unsigned)((buf * 32 + 16 + wave * 2 + kk) << 10));
-        }
+    // `wave`, K half j - 2.  Address = the stage's base pointer (scalar, once per stage) plus a lane
+    // offset that is the same in every stage.
+    unsigned voff[4];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) voff[j] = lane_bytes + ((unsigned)(min(wave, mbs - 1) * KB + j) << 10);
+#pragma unroll
+    for (int j = 2; j < 4; ++j) voff[j] = lane_bytes + ((unsigned)((j - 2) * NBs + wave) << 10);
+    auto x_base = [&](int t) { return xg + (int64_t)(2 * (ks_lo + min(t, T - 1))) * 64; };
+    auto w_base = [&](int t) { return wg + (int64_t)(2 * (ks_lo + min(t, T - 1))) * NBs * 64; };
+    auto issue = [&](const uint4* xs, const uint4* ws, int buf, int j) {
+        if (j < 2) dma_tile(xs, voff[j], lds0 + (unsigned)((buf * 32 + wave * 2 + j) << 10));
+        else dma_tile<true>(ws, voff[j], lds0 + (unsigned)((buf * 32 + 16 + wave * 2 + (j - 2)) << 10));
     };
     Half a0, a1;
     BHalf b0, b1;
@@ -594,15 +603,16 @@ k_bf16_gemm_dma8(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
 #define STAGE_END asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     // bc / bn / bi: buffers of the current stage, the next one and the one being requested (stage + 4)
 #define DMA8_STAGE(MF, U)                                                                     \
-    MF(a0, b0, 0); SB issue(t0 + (U) + 4, bi, 0); rd_a(a1, bc, 1, 0); rd_a(a1, bc, 1, 1); rd_b(b1, bc, 1); SB \
-    MF(a0, b0, 1); SB issue(t0 + (U) + 4, bi, 1); rd_a(a1, bc, 1, 2); rd_a(a1, bc, 1, 3); SB  \
+    { const uint4* xs_ = x_base(t0 + (U) + 4); const uint4* ws_ = w_base(t0 + (U) + 4);       \
+    MF(a0, b0, 0); SB issue(xs_, ws_, bi, 0); rd_a(a1, bc, 1, 0); rd_a(a1, bc, 1, 1); rd_b(b1, bc, 1); SB \
+    MF(a0, b0, 1); SB issue(xs_, ws_, bi, 1); rd_a(a1, bc, 1, 2); rd_a(a1, bc, 1, 3); SB      \
     MF(a0, b0, 2); SB                                                                         \
     MF(a0, b0, 3); SB                                                                         \
-    MF(a1, b1, 0); SB issue(t0 + (U) + 4, bi, 2); rd_a(a0, bn, 0, 0); rd_a(a0, bn, 0, 1); rd_b(b0, bn, 0); SB \
-    MF(a1, b1, 1); SB issue(t0 + (U) + 4, bi, 3); rd_a(a0, bn, 0, 2); rd_a(a0, bn, 0, 3); SB  \
+    MF(a1, b1, 0); SB issue(xs_, ws_, bi, 2); rd_a(a0, bn, 0, 0); rd_a(a0, bn, 0, 1); rd_b(b0, bn, 0); SB \
+    MF(a1, b1, 1); SB issue(xs_, ws_, bi, 3); rd_a(a0, bn, 0, 2); rd_a(a0, bn, 0, 3); SB      \
     MF(a1, b1, 2); SB                                                                         \
     MF(a1, b1, 3); SB                                                                         \
-    STAGE_END                                                                                 \
+    STAGE_END }                                                                               \
     bc = bn; bn = bn == 4 ? 0 : bn + 1; bi = bi == 4 ? 0 : bi + 1;
 #define DMA8_LOOP(MF) \
     for (int t0 = 0; t0 < T; t0 += 4) { DMA8_STAGE(MF, 0) DMA8_STAGE(MF, 1) DMA8_STAGE(MF, 2) DMA8_STAGE(MF, 3) }
@@ -610,7 +620,7 @@ k_bf16_gemm_dma8(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
 #pragma unroll
     for (int st = 0; st < 4; ++st)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) issue(st, st, j);
+        for (int j = 0; j < 4; ++j) issue(x_base(st), w_base(st), st, j);
     int bc = 0, bn = 1, bi = 4;
     STAGE_END                                  // stages 0 and 1 have landed
     a1 = Half{};
