@@ -764,6 +764,7 @@ k_bf16_rope_append(const float* __restrict__ buf, int ld, int n_q, const int32_t
 // The result registers of the score MFMAs are, lane for lane, the P operand
 // of the value MFMAs (the grouped V layout is chosen to make that so).
 // q and P enter as bf16 (hi, lo) pairs: two MFMAs each, fp32-grade products.
+template <bool PAIR>
 __global__ void __launch_bounds__(256, 3)
 k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, int Hq,
             const int32_t* __restrict__ idx, const int32_t* __restrict__ n_ptr, int B,
@@ -774,25 +775,47 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
     __shared__ float sm_o[4][16][128];
     const int g = blockIdx.x;
     const int n = min(*n_ptr, B);
-    if ((int)blockIdx.y >= n) return;
-    const int i = order[blockIdx.y];       // longest contexts first
-    const int b = idx[i];
-    const int sq = kv_row(kv, b);
-    const int cap = kv.cap[sq];
-    const int n_pos = max(1, min(pos[b] + 1, cap));
     const int G = Hq / kv.n_kv_heads;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int n16 = lane & 15, gq = lane >> 4;
+    // PAIR (context pass, 2 G <= 16): the workgroup serves list entries 2 y and 2 y + 1.  If both
+    // read the same cache row they share its K/V stream: entry A's heads are MFMA columns
+    // 0 .. G-1, entry B's G .. 2G-1, each column masked at its own entry's position.  Otherwise
+    // the entries are served one after the other.
+    int iA, iB = -1;
+    if (PAIR) {
+        iA = 2 * (int)blockIdx.y;
+        if (iA >= n) return;
+        if (iA + 1 < n) iB = iA + 1;
+    } else {
+        if ((int)blockIdx.y >= n) return;
+        iA = order[blockIdx.y];            // longest contexts first
+    }
+    bool joint = false;
+    if (PAIR && iB >= 0) joint = kv_row(kv, idx[iA]) == kv_row(kv, idx[iB]);
+    const int n_pass = (PAIR && iB >= 0 && !joint) ? 2 : 1;
+    for (int pass = 0; pass < n_pass; ++pass) {
+    const int e0 = pass == 0 ? iA : iB;                    // entry of columns 0 .. G-1
+    const int e1 = joint ? iB : -1;                        // entry of columns G .. 2G-1, if any
+    const int n_col = e1 >= 0 ? 2 * G : G;                 // live MFMA columns
+    const int sq = kv_row(kv, idx[e0]);
+    const int cap = kv.cap[sq];
+    const int np0 = max(1, min(pos[idx[e0]] + 1, cap));
+    const int np1 = e1 >= 0 ? max(1, min(pos[idx[e1]] + 1, cap)) : 0;
+    const int n_pos = max(np0, np1);                       // positions read
+    const int my_e = n16 < G ? e0 : e1;                    // this lane's column: entry, head, positions
+    const int my_head = n16 < G ? n16 : n16 - G;
+    const int my_np = n16 < G ? np0 : np1;
     const bf16_t* Kb = reinterpret_cast<const bf16_t*>(kv.pool) + kv_block(kv, sq, g, cap);
 
     bf16x8 qh[4], ql[4];
     {
         uint4 z = make_uint4(0, 0, 0, 0);
-        const int64_t qo = ((int64_t)i * Hq + (int64_t)g * G + n16) * 128 + 8 * gq;
+        const int64_t qo = ((int64_t)max(my_e, 0) * Hq + (int64_t)g * G + my_head) * 128 + 8 * gq;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            qh[c] = as_bf16x8(n16 < G ? *reinterpret_cast<const uint4*>(q_hi + qo + 32 * c) : z);
-            ql[c] = as_bf16x8(n16 < G ? *reinterpret_cast<const uint4*>(q_lo + qo + 32 * c) : z);
+            qh[c] = as_bf16x8(n16 < n_col ? *reinterpret_cast<const uint4*>(q_hi + qo + 32 * c) : z);
+            ql[c] = as_bf16x8(n16 < n_col ? *reinterpret_cast<const uint4*>(q_lo + qo + 32 * c) : z);
         }
     }
     const float inv_sqrt = 1.0f / sqrtf(128.0f);
@@ -842,8 +865,8 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
         float mx = NEG;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            s[r]     = (p0 + 4 * gq + r < n_pos) ? S0[r] * inv_sqrt : NEG;
-            s[4 + r] = (p0 + 16 + 4 * gq + r < n_pos) ? S1[r] * inv_sqrt : NEG;
+            s[r]     = (p0 + 4 * gq + r < my_np) ? S0[r] * inv_sqrt : NEG;
+            s[4 + r] = (p0 + 16 + 4 * gq + r < my_np) ? S1[r] * inv_sqrt : NEG;
             mx = fmaxf(mx, fmaxf(s[r], s[4 + r]));
         }
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
@@ -896,8 +919,10 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
         for (int r = 0; r < 4; ++r) sm_o[w][n16][16 * hb + 4 * gq + r] = O[hb][r];
     __syncthreads();
     {
-        const int head = threadIdx.x >> 4, c0 = (threadIdx.x & 15) * 8;
-        if (head < G) {
+        const int head = threadIdx.x >> 4, c0 = (threadIdx.x & 15) * 8;     // head = MFMA column
+        if (head < n_col) {
+            const int i = head < G ? e0 : e1;
+            const int hq = head < G ? head : head - G;
             float M = fmaxf(fmaxf(sm_m[0][head], sm_m[1][head]), fmaxf(sm_m[2][head], sm_m[3][head]));
             float wgt[4], Lsum = 0.f;
 #pragma unroll
@@ -913,16 +938,18 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
             if (n_splits == 1) {
                 uint4 pk = make_uint4(pack2(o[0] / Lsum, o[1] / Lsum), pack2(o[2] / Lsum, o[3] / Lsum),
                                       pack2(o[4] / Lsum, o[5] / Lsum), pack2(o[6] / Lsum, o[7] / Lsum));
-                int col = (g * G + head) * 128 + c0;
+                int col = (g * G + hq) * 128 + c0;
                 ao[afrag_chunk(i, col, KB_ao)] = pk;
             } else {
                 // unnormalised share: [i][kv head][split][head][130] = 128 features, max, sum
-                float* p = part + ((((int64_t)i * kv.n_kv_heads + g) * n_splits + blockIdx.z) * 16 + head) * 130;
+                float* p = part + ((((int64_t)i * kv.n_kv_heads + g) * n_splits + blockIdx.z) * 16 + hq) * 130;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) p[c0 + j] = o[j];
                 if (c0 == 0) { p[128] = M; p[129] = Lsum; }
             }
         }
+    }
+    if (n_pass > 1) __syncthreads();       // the merge has read the shared arrays before the next entry writes them
     }
 }
 
@@ -1194,9 +1221,16 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
         int n_splits = pairs >= 512 ? 1 : (1024 + pairs - 1) / pairs;
         if (n_splits > 16) n_splits = 16;
         while (n_splits > 1 && (size_t)b->Mpad * c.n_kv_heads * n_splits * 16 * 130 * 4 > b->W.attn_part_bytes) --n_splits;
-        hipLaunchKernelGGL(k_bf16_attn, dim3(c.n_kv_heads, B, n_splits), dim3(256), 0, s, b->wsp<bf16_t>(b->W.q_hi),
-                           b->wsp<bf16_t>(b->W.q_lo), c.n_q_heads, idx, n_ptr, B, b->st<int32_t>(L.pos), view, ao,
-                           qd / 16, n_splits, b->wsp<float>(b->W.attn_part), b->wsp<int32_t>(b->W.attn_order));
+        // context pass: two entries per workgroup, which share the K/V stream when they sit in the same cache row
+        const bool pair = b->kv_seq != nullptr && n_splits == 1 && 2 * (c.n_q_heads / c.n_kv_heads) <= 16;
+        if (pair)
+            hipLaunchKernelGGL(k_bf16_attn<true>, dim3(c.n_kv_heads, (B + 1) / 2, 1), dim3(256), 0, s, b->wsp<bf16_t>(b->W.q_hi),
+                               b->wsp<bf16_t>(b->W.q_lo), c.n_q_heads, idx, n_ptr, B, b->st<int32_t>(L.pos), view, ao,
+                               qd / 16, 1, b->wsp<float>(b->W.attn_part), b->wsp<int32_t>(b->W.attn_order));
+        else
+            hipLaunchKernelGGL(k_bf16_attn<false>, dim3(c.n_kv_heads, B, n_splits), dim3(256), 0, s, b->wsp<bf16_t>(b->W.q_hi),
+                               b->wsp<bf16_t>(b->W.q_lo), c.n_q_heads, idx, n_ptr, B, b->st<int32_t>(L.pos), view, ao,
+                               qd / 16, n_splits, b->wsp<float>(b->W.attn_part), b->wsp<int32_t>(b->W.attn_order));
         if (n_splits > 1)
             hipLaunchKernelGGL(k_bf16_attn_merge, dim3(c.n_kv_heads, B), dim3(256), 0, s, b->wsp<float>(b->W.attn_part),
                                c.n_q_heads, c.n_kv_heads, n_splits, n_ptr, B, ao, qd / 16);
