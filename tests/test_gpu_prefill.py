@@ -35,6 +35,11 @@ MID = synth.CONFIGS["llama2_7b"].with_(name="mid_bf16_ctx", n_layers=6, resident
 WIDE = synth.CONFIGS["llama2_7b"].with_(name="wide_bf16_ctx", n_layers=2, resident=2, d_model=512, n_q_heads=8,
                                         n_kv_heads=1, d_ffn=1536, vocab=4096, exit_layers=(1, 2),
                                         thresholds=(0.8, 0.0), batch=40, ctx_lo=5, ctx_hi=70, steps=1)
+# enough (kv head, entry) pairs per call that the attention kernel serves two entries per workgroup
+# (shared K/V stream when they sit in the same cache row), G = 4 query heads per kv head
+PAIRS = synth.CONFIGS["llama2_7b"].with_(name="pairs_bf16_ctx", n_layers=2, resident=2, d_model=512, n_q_heads=32,
+                                         n_kv_heads=8, d_ffn=1024, vocab=2048, exit_layers=(1, 2),
+                                         thresholds=(0.8, 0.0), batch=10, ctx_lo=1, ctx_hi=150, steps=1)
 # partially loaded model: the pass stops at the last resident layer
 PARTIAL = synth.CONFIGS["codellama_34b_r32"].with_(name="partial_bf16_ctx", n_layers=6, resident=4, d_model=512,
                                                    n_q_heads=8, n_kv_heads=1, d_ffn=1024, vocab=2048,
@@ -96,7 +101,7 @@ def _compare_cache(s, o, g, tol):
     return worst
 
 
-@pytest.mark.parametrize("s,rows_per_call", [(TINY, 13), (MHA, 50), (MID, 72), (WIDE, 300), (PARTIAL, 33)],
+@pytest.mark.parametrize("s,rows_per_call", [(TINY, 13), (MHA, 50), (MID, 72), (WIDE, 300), (PARTIAL, 33), (PAIRS, 72)],
                          ids=lambda v: v.name if hasattr(v, "name") else None)
 def test_context_pass_cache_and_hidden_states(s, rows_per_call):
     _say(f"[case] context_pass {s.name} seed={s.seed} cache rows={s.batch} entries per call={rows_per_call}")
