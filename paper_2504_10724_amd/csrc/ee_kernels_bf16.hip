@@ -373,6 +373,25 @@ __device__ __forceinline__ void epilogue_tile(const EpiArgs& ep, const floatx16&
 // issued one behind each MFMA group (a burst would queue up in the vector-memory path and hold the
 // wave).  The compiler does not see these loads, so it adds no wait of its own; the waits are
 // written out.  Loads past the end of the K slice re-read its last stage.
+// Which (row group, column tile x K slice) a workgroup takes.  One row group: blockIdx.x is the
+// unit.  Several row groups (context pass; the grid is then one-dimensional with gridDim.x =
+// 8 ceil(units / 8) x row groups): workgroups are handed to the 8 XCDs round-robin, each XCD has
+// its own L2, and the row groups of a unit read the same weight tiles, so they get block numbers
+// 8 apart: same XCD, started one after the other, and the tiles come from HBM once, not once
+// per row group.  unit = -1: a block past the last unit.
+__device__ __forceinline__ void tile_of_block(int units, int& rg, int& unit) {
+    if (gridDim.y == 1 && (int)gridDim.x > units) {
+        const int u8 = (units + 7) / 8 * 8, R = gridDim.x / u8;
+        const int x = blockIdx.x & 7, q = blockIdx.x >> 3;
+        rg = q % R;
+        unit = (q / R) * 8 + x;
+        if (unit >= units) unit = -1;
+    } else {
+        rg = blockIdx.y;
+        unit = blockIdx.x;
+    }
+}
+
 // tile and lds_byte are the same in all lanes; going through readfirstlane makes that explicit, so
 // that both end up in scalar registers whatever the optimiser did to the address arithmetic
 // NT: the tile is read once per launch (weights): a non-temporal load, which does not hold a line of
@@ -408,7 +427,9 @@ k_bf16_gemm_dma2(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
                  int64_t part_plane, int part_ld, EpiArgs ep, ZBatch zb) {
     __shared__ uint4 lds[6][24][64];          // six stage buffers: a stage is requested five stages ahead
     const int n = min(*n_ptr, B);
-    const int rg = blockIdx.y;
+    int rg, unit;
+    tile_of_block(n_tiles * splits, rg, unit);
+    if (unit < 0) return;
     const int row_base = rg * 256;
     if (row_base >= n) return;
     if (zb.w_tab) Wp = reinterpret_cast<const uint4*>(zb.w_tab[zb.z0 + blockIdx.z]);
@@ -419,7 +440,7 @@ k_bf16_gemm_dma2(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int cnt = max(0, min(4, mbs - 4 * wm));            // live 32-row tiles of this wave
-    const int tile = blockIdx.x / splits, sp = blockIdx.x % splits;
+    const int tile = unit / splits, sp = unit % splits;
     const int nbw = (tile * 2 + wn) * 2;                     // first of this wave's two tile-rows of W
     const int KS4 = KB >> 3;
     const int ks_lo = 4 * (int)(((int64_t)KS4 * sp) / splits), ks_hi = 4 * (int)(((int64_t)KS4 * (sp + 1)) / splits);
@@ -539,7 +560,9 @@ k_bf16_gemm_dma8(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
                  int64_t part_plane, int part_ld, EpiArgs ep, ZBatch zb) {
     __shared__ uint4 lds[5][32][64];
     const int n = min(*n_ptr, B);
-    const int rg = blockIdx.y;
+    int rg, unit;
+    tile_of_block(n_tiles * splits, rg, unit);
+    if (unit < 0) return;
     const int row_base = rg * 256;
     if (row_base >= n) return;
     if (zb.w_tab) Wp = reinterpret_cast<const uint4*>(zb.w_tab[zb.z0 + blockIdx.z]);
@@ -550,7 +573,7 @@ k_bf16_gemm_dma8(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave >> 2, wn = wave & 3;
     const int cnt = max(0, min(4, mbs - 4 * wm));            // live 32-row tiles of this wave
-    const int tile = blockIdx.x / splits, sp = blockIdx.x % splits;
+    const int tile = unit / splits, sp = unit % splits;
     const int nbw = (tile * 4 + wn) * 2;                     // first of this wave's two tile-rows of W
     const int KS4 = KB >> 3;
     const int ks_lo = 4 * (int)(((int64_t)KS4 * sp) / splits), ks_hi = 4 * (int)(((int64_t)KS4 * (sp + 1)) / splits);
@@ -1150,6 +1173,7 @@ static bool gemm_tiled(const ee_batch* b, const void* X, const void* W, int N, i
         while (splits > 1 && (size_t)splits * Mpad * N * sizeof(float) > b->W.gemm_part_bytes) --splits;
     }
     dim3 grid(n_tiles * splits, row_groups, nz);
+    if (row_groups > 1) grid = dim3((n_tiles * splits + 7) / 8 * 8 * row_groups, 1, nz);   // see tile_of_block
     if (wide)
         hipLaunchKernelGGL((k_bf16_gemm_dma8<EPI>), grid, dim3(512), 0, s, (const uint4*)X, (const uint4*)W,
                            K / 16, NBs, nb_off, n_tiles, splits, n_ptr, B, b->wsp<float>(b->W.gemm_part),
