@@ -395,7 +395,7 @@ def main():
                     help="only run a plain 1 GiB device-to-device copy 4 times (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; nothing shards across GPUs (run with --gpus 1)", file=sys.stderr)
+        print("bench.py: this library runs on one GPU; nothing shards across GPUs (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -7,7 +7,7 @@ the confidence threshold; when it exceeds CBC_max the serving loop re-assesses
 (load more layers or switch model) and the counter starts again from zero; by
 default at most 50 breaches are tolerated in a window of 100 consecutive tokens.
 
-Reading taken where the text is silent (listed in the design doc): tokens are ordered
+Reading taken where the text is silent: tokens are ordered
 by (decode step, row id); the window is the most recent `window` tokens emitted
 since the last re-assessment, so a re-assessment empties it; the test is made
 after every token; "exceeds" is strictly greater.

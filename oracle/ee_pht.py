@@ -11,7 +11,7 @@ perplexity of the generated tokens, computed from the token probabilities alone
 chosen model is taken if its PHT figure is below that of every other candidate's
 low-exit version, otherwise the next best candidate's low-exit version (Algorithm 1).
 
-Readings taken where the text is silent (listed in the design doc): perplexity of a
+Readings taken where the text is silent: perplexity of a
 window = exp of the mean of -ln p over its emitted tokens, p being the probability
 the exit head gave the emitted token (the standard definition; the paper prints no
 formula); the PHT figure compared in Algorithm 1 is a cost (lower is better) and a
