@@ -372,7 +372,7 @@ static void lay_workspace(const ee_model* m, int B, WsLayout* W) {
         size_t fill_layers = c.n_layers > 1 ? (size_t)c.n_layers - 1 : 1;   // all skipped layers in one launch
         W->fill_x = take(fill_layers * Mpad * c.d_model * 2);
         W->fill_kv = take(fill_layers * Mpad * kvn * 4);
-        W->gemm_part_bytes = B > 32 ? Mpad * ((size_t)384 << 10) : 0;   // K-slice planes: 96 MiB at 256 rows
+        W->gemm_part_bytes = Mpad * ((size_t)384 << 10);   // K-slice planes: 96 MiB at 256 rows
         W->gemm_part = take(W->gemm_part_bytes);
         W->gemm_cnt_ints = 4096;
         W->gemm_cnt = take(W->gemm_cnt_ints * 4);

@@ -119,6 +119,7 @@ __global__ void __launch_bounds__(64 * WK * WN)
 k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int NB_total, int NBs, int nb_off,
             const int32_t* __restrict__ n_ptr, int B, EpiArgs ep, ZBatch zb) {
     constexpr int IPW = 16 / WK;   // accumulator registers each wave finishes after the reduction
+    constexpr int GD = 4;          // K tiles per load group
     __shared__ float red[(WK > 1) ? (WK * WN * NS * 16 * 64) : 1];
     const int n = min(*n_ptr, B);
     const int row_base = blockIdx.y * (32 * MS);
@@ -144,13 +145,14 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
             for (int r = 0; r < 16; ++r) acc[ms][ns][r] = 0.f;
 
     if (has_cols) {
-        // groups of 4 K tiles, the next group's W and X tiles in flight while the current one is
-        // multiplied (dead row tiles re-read a live one, so the loads need no branch)
-        struct Group { uint4 w[4][NS]; uint4 x[4][MS]; };
+        // groups of GD K tiles, the next group's W and X tiles in flight while the current one is
+        // multiplied (dead row tiles re-read a live one, so the loads need no branch); groups twice
+        // as deep change nothing: with one row tile per wave half of what a CU requests is X
+        struct Group { uint4 w[GD][NS]; uint4 x[GD][MS]; };
         auto load_group = [&](int kb) -> Group {
             Group g;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < GD; ++u) {
 #pragma unroll
                 for (int ns = 0; ns < NS; ++ns) g.w[u][ns] = load_nt(ww + ((int64_t)(kb + u) * NBs + ns) * 64);
 #pragma unroll
@@ -160,7 +162,7 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
         };
         auto mul_group = [&](const Group& g) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < GD; ++u)
 #pragma unroll
                 for (int ms = 0; ms < MS; ++ms) {
                     if (ms < mbs) {
@@ -172,17 +174,17 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
                 }
         };
         int kb = kb_lo;
-        const int n_groups = (kb_hi - kb_lo) >> 2;
+        const int n_groups = (kb_hi - kb_lo) / GD;
         if (n_groups > 0) {
             Group cur = load_group(kb);
             for (int gi = 1; gi < n_groups; ++gi) {
-                Group nxt = load_group(kb + 4);
+                Group nxt = load_group(kb + GD);
                 mul_group(cur);
                 cur = nxt;
-                kb += 4;
+                kb += GD;
             }
             mul_group(cur);
-            kb += 4;
+            kb += GD;
         }
         for (; kb < kb_hi; ++kb) {
 #pragma unroll
@@ -591,9 +593,8 @@ k_bf16_gemm_dma8(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // j-th load of a stage: j = 0, 1 the X tile of row tile `wave`, K half j (a dead row tile re-reads
-    // a live one: every wave issues the same number of loads); j = 2, 3 the W tile of column tile
-    // `wave`, K half j - 2.  Address = the stage's base pointer (scalar, once per stage) plus a lane
+    // j-th load of a stage: j = 0, 1 the X tile of row tile `wave`, K half j (sent only if that row
+    // tile is live); j = 2, 3 the W tile of column tile `wave`, K half j - 2.  Address = the stage's base pointer (scalar, once per stage) plus a lane
     // offset that is the same in every stage.
     unsigned voff[4];
 #pragma unroll
@@ -622,35 +623,41 @@ k_bf16_gemm_dma8(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
         if (i < cnt) mf_all(a, bw, i);
     };
 #define SB __builtin_amdgcn_sched_barrier(0);
-// 8 loads (two stages) may stay in flight: everything up to stage t+2 has landed
-#define STAGE_END asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+// two stages of this wave's loads (VM of them) may stay in flight: everything up to stage t+2 has landed
+#define STAGE_END(VM) asm volatile("s_waitcnt vmcnt(" #VM ") lgkmcnt(0)\n\ts_barrier" ::: "memory");
     // bc / bn / bi: buffers of the current stage, the next one and the one being requested (stage + 4)
-#define DMA8_STAGE(MF, U)                                                                     \
+#define DMA8_STAGE(MF, XL, VM, U)                                                             \
     { const uint4* xs_ = x_base(t0 + (U) + 4); const uint4* ws_ = w_base(t0 + (U) + 4);       \
-    MF(a0, b0, 0); SB issue(xs_, ws_, bi, 0); rd_a(a1, bc, 1, 0); rd_a(a1, bc, 1, 1); rd_b(b1, bc, 1); SB \
-    MF(a0, b0, 1); SB issue(xs_, ws_, bi, 1); rd_a(a1, bc, 1, 2); rd_a(a1, bc, 1, 3); SB      \
+    MF(a0, b0, 0); SB if (XL) issue(xs_, ws_, bi, 0); rd_a(a1, bc, 1, 0); rd_a(a1, bc, 1, 1); rd_b(b1, bc, 1); SB \
+    MF(a0, b0, 1); SB if (XL) issue(xs_, ws_, bi, 1); rd_a(a1, bc, 1, 2); rd_a(a1, bc, 1, 3); SB \
     MF(a0, b0, 2); SB                                                                         \
     MF(a0, b0, 3); SB                                                                         \
     MF(a1, b1, 0); SB issue(xs_, ws_, bi, 2); rd_a(a0, bn, 0, 0); rd_a(a0, bn, 0, 1); rd_b(b0, bn, 0); SB \
     MF(a1, b1, 1); SB issue(xs_, ws_, bi, 3); rd_a(a0, bn, 0, 2); rd_a(a0, bn, 0, 3); SB      \
     MF(a1, b1, 2); SB                                                                         \
     MF(a1, b1, 3); SB                                                                         \
-    STAGE_END }                                                                               \
+    STAGE_END(VM) }                                                                           \
     bc = bn; bn = bn == 4 ? 0 : bn + 1; bi = bi == 4 ? 0 : bi + 1;
-#define DMA8_LOOP(MF) \
-    for (int t0 = 0; t0 < T; t0 += 4) { DMA8_STAGE(MF, 0) DMA8_STAGE(MF, 1) DMA8_STAGE(MF, 2) DMA8_STAGE(MF, 3) }
+#define DMA8_LOOP(MF, XL, VM) \
+    for (int t0 = 0; t0 < T; t0 += 4) { DMA8_STAGE(MF, XL, VM, 0) DMA8_STAGE(MF, XL, VM, 1) DMA8_STAGE(MF, XL, VM, 2) DMA8_STAGE(MF, XL, VM, 3) }
 
+    // only live row tiles are fetched: wave w sends the X tiles of row tile w if there is one, and
+    // the count of loads it may leave in flight follows (the counter is per wave)
+    const bool sends_x = wave < mbs;
 #pragma unroll
     for (int st = 0; st < 4; ++st)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) issue(x_base(st), w_base(st), st, j);
+        for (int j = 0; j < 4; ++j)
+            if (j >= 2 || sends_x) issue(x_base(st), w_base(st), st, j);
     int bc = 0, bn = 1, bi = 4;
-    STAGE_END                                  // stages 0 and 1 have landed
+    if (sends_x) { STAGE_END(8) } else { STAGE_END(4) }   // stages 0 and 1 have landed
     a1 = Half{};
     b1 = BHalf{};
     rd_a(a0, 0, 0, 0); rd_a(a0, 0, 0, 1); rd_a(a0, 0, 0, 2); rd_a(a0, 0, 0, 3);
     rd_b(b0, 0, 0);
-    if (cnt == 4) { DMA8_LOOP(mf_all) } else { DMA8_LOOP(mf_some) }
+    if (!sends_x) { DMA8_LOOP(mf_some, false, 4) }         // such a wave has fewer than 4 live tiles
+    else if (cnt == 4) { DMA8_LOOP(mf_all, true, 8) }
+    else { DMA8_LOOP(mf_some, true, 8) }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #undef DMA8_LOOP
 #undef DMA8_STAGE
@@ -1142,15 +1149,12 @@ static bool gemm_tiled(const ee_batch* b, const void* X, const void* W, int N, i
                      const int32_t* n_ptr, int B, const EpiArgs& ep, hipStream_t s, const ZBatch& zb = ZBatch{},
                      int nz = 1, const SliceTail& tail = SliceTail{}) {
     if (N % 128 != 0 || K % 128 != 0) return false;
-    // smallest batch capacity from which the tile kernels beat the weight-streaming kernel
-    // (measured per product on the 70B shapes): the gate/up product always, QKV and the down
-    // projection above 32 rows, the O projection, the exit head and multi-layer launches above 64
-    int min_rows = 65;
-    if (nz == 1) {
-        if (EPI == EPI_SWIGLU) min_rows = 1;
-        else if (EPI == EPI_STORE || (EPI == EPI_RESID && K >= 2 * N)) min_rows = 33;
-    }
-    if (B < min_rows) return false;
+    // One product at a time: the tile kernels at every batch size (at 1 to 32 rows, measured on the
+    // 70B shapes against the weight-streaming kernel plus the normalisation launch that the finish of
+    // a sliced product saves: QKV 36 against 46 us, O 34 against 37, down 84 against 87, exit head 94
+    // against 95-100, and 99 against 149 at 64 rows).  Several layers in one launch (K/V of skipped
+    // layers): from 65 rows up.
+    if (nz > 1 && B < 65) return false;
     int row_groups = (B + 255) / 256;
     int Mpad = (B + 31) / 32 * 32;
     int KS = K / 32;
