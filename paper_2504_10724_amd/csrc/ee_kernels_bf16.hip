@@ -415,8 +415,9 @@ __device__ __forceinline__ void dma_tile(const uint4* tile, unsigned lane_bytes,
 // ------------------------------------------------------------------ 128-column tile fed by LDS-DMA loads
 // 256 rows x 128 columns per workgroup, waves 2 x 2: wave (wm, wn) owns rows 128 wm .. +127
 // and columns 64 wn .. +63 (4 x 2 MFMA tiles, 128 accumulator registers).  LDS: 6 stage buffers x 24 slots: X tile (row tile m, K half kk)
-// at 2 m + kk, W tile (column tile nb of the 4, K half kk) at 16 + 2 nb + kk.  A wave sends 4 X
-// tiles and 2 W tiles per stage and reads the 8 + 4 it needs.  For products with few columns
+// at 2 m + kk, W tile (column tile nb of the 4, K half kk) at 16 + 2 nb + kk.  A wave sends up to 4 X
+// tiles (those of its live row tiles: against re-reading a live tile in place of a dead one, the
+// exit head takes 7-10 % less up to 64 rows and QKV 3-5 %) and 2 W tiles per stage and reads the 8 + 4 it needs.  For products with few columns
 // (QKV, O projection, exit head) it gives twice as many workgroups per K slice as the 256-column tile.
 // Its stages are short (16 MFMAs per wave), so a stage is requested five stages ahead, not three:
 // measured against three it takes 5 % off the QKV product at 256 rows and 14 % at 64.
@@ -460,8 +461,8 @@ k_bf16_gemm_dma2(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // j-th load of a stage: j = 0..3 X tiles (row tile 2 wave + j/2, K half j%2; a dead row tile
-    // re-reads a live one); j = 4, 5 the W slots 2 wave + (j - 4) of the stage's eight (column tile
+    // j-th load of a stage: j = 0..3 X tiles (row tile 2 wave + j/2, K half j%2; sent only if that
+    // row tile is live); j = 4, 5 the W slots 2 wave + (j - 4) of the stage's eight (column tile
     // q/2, K half q%2).  A tile's address is the stage's base pointer (scalar, computed once per
     // stage) plus a lane offset that is the same in every stage, so a load costs few instructions.
     unsigned voff[6];
@@ -497,36 +498,45 @@ k_bf16_gemm_dma2(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
         if (i < cnt) mf_all(a, bw, i);
     };
 #define SB __builtin_amdgcn_sched_barrier(0);
-// 18 loads (three stages) may stay in flight: everything up to stage t+2 has landed
-#define STAGE_END asm volatile("s_waitcnt vmcnt(18) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+// three stages of this wave's loads (VM of them) may stay in flight: everything up to stage t+2 has landed
+#define STAGE_END(VM) asm volatile("s_waitcnt vmcnt(" #VM ") lgkmcnt(0)\n\ts_barrier" ::: "memory");
     // bc / bn / bi: buffers of the current stage, the next one and the one being requested (stage + 5);
-    // six buffers and an unroll of four do not divide, so the indices are counted at run time
-#define DMA2_STAGE(MF, U)                                                                     \
+    // six buffers and an unroll of four do not divide, so the indices are counted at run time.
+    // XL: how many of this wave's two row tiles are live and fetched
+#define DMA2_STAGE(MF, XL, VM, U)                                                             \
     { const uint4* xs_ = x_base(t0 + (U) + 5); const uint4* ws_ = w_base(t0 + (U) + 5);       \
-    MF(a0, b0, 0); SB issue(xs_, ws_, bi, 0); rd_a(a1, bc, 1, 0); rd_a(a1, bc, 1, 1); rd_b(b1, bc, 1); SB \
-    MF(a0, b0, 1); SB issue(xs_, ws_, bi, 1); rd_a(a1, bc, 1, 2); rd_a(a1, bc, 1, 3); SB      \
-    MF(a0, b0, 2); SB issue(xs_, ws_, bi, 2); SB                                              \
-    MF(a0, b0, 3); SB issue(xs_, ws_, bi, 3); SB                                              \
+    MF(a0, b0, 0); SB if (XL >= 1) issue(xs_, ws_, bi, 0); rd_a(a1, bc, 1, 0); rd_a(a1, bc, 1, 1); rd_b(b1, bc, 1); SB \
+    MF(a0, b0, 1); SB if (XL >= 1) issue(xs_, ws_, bi, 1); rd_a(a1, bc, 1, 2); rd_a(a1, bc, 1, 3); SB \
+    MF(a0, b0, 2); SB if (XL >= 2) issue(xs_, ws_, bi, 2); SB                                 \
+    MF(a0, b0, 3); SB if (XL >= 2) issue(xs_, ws_, bi, 3); SB                                 \
     MF(a1, b1, 0); SB issue(xs_, ws_, bi, 4); rd_a(a0, bn, 0, 0); rd_a(a0, bn, 0, 1); rd_b(b0, bn, 0); SB \
     MF(a1, b1, 1); SB issue(xs_, ws_, bi, 5); rd_a(a0, bn, 0, 2); rd_a(a0, bn, 0, 3); SB      \
     MF(a1, b1, 2); SB                                                                         \
     MF(a1, b1, 3); SB                                                                         \
-    STAGE_END }                                                                               \
+    STAGE_END(VM) }                                                                           \
     bc = bn; bn = bn == 5 ? 0 : bn + 1; bi = bi == 5 ? 0 : bi + 1;
-#define DMA2_LOOP(MF) \
-    for (int t0 = 0; t0 < T; t0 += 4) { DMA2_STAGE(MF, 0) DMA2_STAGE(MF, 1) DMA2_STAGE(MF, 2) DMA2_STAGE(MF, 3) }
+#define DMA2_LOOP(MF, XL, VM) \
+    for (int t0 = 0; t0 < T; t0 += 4) { DMA2_STAGE(MF, XL, VM, 0) DMA2_STAGE(MF, XL, VM, 1) DMA2_STAGE(MF, XL, VM, 2) DMA2_STAGE(MF, XL, VM, 3) }
 
+    // only live row tiles are fetched; the count of loads a wave may leave in flight is per wave
+    // and follows from how many X tiles it sends
+    const int xl = max(0, min(2, mbs - 2 * wave));
 #pragma unroll
     for (int st = 0; st < 5; ++st)
 #pragma unroll
-        for (int j = 0; j < 6; ++j) issue(x_base(st), w_base(st), st, j);
+        for (int j = 0; j < 6; ++j)
+            if (j >= 4 || (j >> 1) < xl) issue(x_base(st), w_base(st), st, j);
     int bc = 0, bn = 1, bi = 5;
-    STAGE_END                                  // stages 0 and 1 have landed
+    if (xl == 2) { STAGE_END(18) } else if (xl == 1) { STAGE_END(12) } else { STAGE_END(6) }   // stages 0 and 1 have landed
     a1 = Half{};
     b1 = BHalf{};
     rd_a(a0, 0, 0, 0); rd_a(a0, 0, 0, 1); rd_a(a0, 0, 0, 2); rd_a(a0, 0, 0, 3);
     rd_b(b0, 0, 0);
-    if (cnt == 4) { DMA2_LOOP(mf_all) } else { DMA2_LOOP(mf_some) }
+    // a wave that does not send both of its X tiles has fewer than 4 live row tiles
+    if (xl == 0) { DMA2_LOOP(mf_some, 0, 6) }
+    else if (xl == 1) { DMA2_LOOP(mf_some, 1, 12) }
+    else if (cnt == 4) { DMA2_LOOP(mf_all, 2, 18) }
+    else { DMA2_LOOP(mf_some, 2, 18) }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #undef DMA2_LOOP
 #undef DMA2_STAGE
