@@ -44,6 +44,14 @@ DEEP = synth.CONFIGS["llama2_7b"].with_(name="deep_bf16", n_layers=28, resident=
                                         thresholds=(0.6, 0.0), batch=70, ctx_lo=5, ctx_hi=70, steps=2)
 
 
+# few rows on the tile kernels: one live 32-row tile (ragged), K long enough to be sliced (d = 2048:
+# two to four slices per product), the finish kernels do the residual update and the next RMSNorm
+SMALL_SLICED = synth.CONFIGS["llama2_7b"].with_(name="small_sliced_bf16", n_layers=3, resident=3, d_model=2048,
+                                                n_q_heads=16, n_kv_heads=4, d_ffn=5632, vocab=4096,
+                                                exit_layers=(1, 3), thresholds=(0.7, 0.0), batch=11, ctx_lo=3,
+                                                ctx_hi=140, steps=3)
+
+
 @pytest.fixture(scope="module")
 def sides():
     cache = {}
@@ -157,7 +165,7 @@ def test_calls_one_by_one(s):
 
 
 # ---------------------------------------------------------------- whole steps
-@pytest.mark.parametrize("s", [TINY, MHA, MID, BIG_M, PARTIAL, DEEP], ids=lambda s: s.name)
+@pytest.mark.parametrize("s", [TINY, MHA, MID, BIG_M, PARTIAL, DEEP, SMALL_SLICED], ids=lambda s: s.name)
 def test_decode_steps(s):
     _say(f"[case] decode_steps {s.name} seed={s.seed} B={s.batch} steps={s.steps}")
     o, g = _fresh(s, jitter=0.0)
