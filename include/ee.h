@@ -254,7 +254,10 @@ int ee_fill_skipped_kv(const ee_model* m, int from_layer_excl, int to_layer_incl
 /* One whole early-exit decode step: embed tok_in; for l = 1..R run the layer on
  * the active rows and, where l carries an exit, the exit head, the compaction
  * and the fill of skipped layers; then pos += 1 and tok_in = out_tok for every
- * row.  host_thresholds holds one value per resident exit; values <= 0 always
+ * row.  When the step returns, every row has its K and V in all R layers, as if
+ * ee_fill_skipped_kv(l, R) had run at each exit layer l; the bf16 step gets there
+ * in segments (after the compaction at l: layers l+1 .. next exit layer, for all
+ * rows that have left so far in this step), which reads each layer's W_k, W_v once.  host_thresholds holds one value per resident exit; values <= 0 always
  * exit, values > 1 never do (except at R).
  * Errors: EE_ERR_EXIT_NOT_RESIDENT if layer R carries no (set) exit head,
  * EE_ERR_INVALID_ARG if the resident layers are not exactly 1..R, if

@@ -381,6 +381,8 @@ static void lay_workspace(const ee_model* m, int B, WsLayout* W) {
         W->attn_part = take(W->attn_part_bytes);
         W->attn_order = take(Mpad * 4);
         W->kv_seq = take(Mpad * 4);
+        W->gone_idx = take(Mpad * 4);
+        W->n_gone = take(4);
     } else {
         size_t wide = (size_t)c.vocab > 2 * (size_t)c.d_ffn ? (size_t)c.vocab : 2 * (size_t)c.d_ffn;
         W->x = take(Mpad * c.d_model * 4);
@@ -400,6 +402,8 @@ static void lay_workspace(const ee_model* m, int B, WsLayout* W) {
         W->attn_part_bytes = 0; W->attn_part = take(0);
         W->attn_order = take(0);
         W->kv_seq = take(Mpad * 4);
+        W->gone_idx = take(Mpad * 4);
+        W->n_gone = take(4);
     }
     W->total = o;
 }
@@ -681,7 +685,17 @@ int ee_decode_step(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_
             rc = ee_exit_head(m, e, host_thresholds[e], l == R, b, nullptr, s);
         x_ready = false;                                     // the compaction renumbers the list entries
         if (rc == EE_OK) rc = ee_compact_active(b, e, l, s);
-        if (rc == EE_OK) rc = ee_fill_skipped_kv(m, l, R, kv, b, s);
+        if (rc != EE_OK || l == R) continue;
+        if (c.dtype == EE_BF16) {
+            // Sec. 2.2 asks for the skipped layers' K/V of every row that left; when they are computed
+            // within the step is free, since nothing reads them before the next step.  Filling only up
+            // to the next exit layer, for all rows that have left so far in this step, reads W_k, W_v of
+            // every layer once per step instead of once per earlier exit.
+            rc = bf16_fill_kv(m, l, c.exit_layers[next_exit], kv, b, as_stream(s), b->wsp<int32_t>(b->W.gone_idx),
+                              b->wsp<int32_t>(b->W.n_gone));
+        } else {
+            rc = ee_fill_skipped_kv(m, l, R, kv, b, s);
+        }
     }
     if (rc == EE_OK) rc = launch_end_step(b, as_stream(s));
     return rc;

@@ -48,6 +48,7 @@ struct WsLayout {
     size_t attn_part, attn_part_bytes;                            // attention position shares
     size_t attn_order;                                            // int32 [Mpad]: list entries, longest context first
     size_t kv_seq;                                                // int32 [Mpad]: cache row of each entry (context pass)
+    size_t gone_idx, n_gone;                                      // int32 [Mpad], int32: rows that left at any exit of the running step
 };
 
 struct ee_batch {
@@ -134,4 +135,6 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
                        const float* tail_gain = nullptr, bool* x_done = nullptr);
 int bf16_exit_head(const ee_model* m, int e, float th, int force, ee_batch* b, float* dbg, hipStream_t s,
                    bool x_ready = false);
-int bf16_fill_kv(const ee_model* m, int from_excl, int to_incl, ee_kv* kv, ee_batch* b, hipStream_t s);
+// rows: the batch's exited_idx / n_exited unless another device list (idx, n_ptr) is given
+int bf16_fill_kv(const ee_model* m, int from_excl, int to_incl, ee_kv* kv, ee_batch* b, hipStream_t s,
+                 const int32_t* idx = nullptr, const int32_t* n_ptr = nullptr);

@@ -1332,18 +1332,18 @@ int bf16_exit_head(const ee_model* m, int e, float th, int force, ee_batch* b, f
     return launch_exit_decide(b, V / 32, th, force, s);
 }
 
-int bf16_fill_kv(const ee_model* m, int from_excl, int to_incl, ee_kv* kv, ee_batch* b, hipStream_t s) {
+int bf16_fill_kv(const ee_model* m, int from_excl, int to_incl, ee_kv* kv, ee_batch* b, hipStream_t s,
+                 const int32_t* idx, const int32_t* n_ptr) {
     const ee_model_config& c = m->cfg;
     const ee_batch_layout& L = b->L;
     int B = b->B, d = c.d_model, hd = c.head_dim;
     int kv_n = 2 * c.n_kv_heads * hd;
     int nl = to_incl - from_excl;                       // layers to fill: from_excl + 1 .. to_incl
-    const int32_t* idx = b->st<int32_t>(L.exited_idx);
-    const int32_t* n_ptr = b->st<int32_t>(L.n_exited);
+    if (idx == nullptr) { idx = b->st<int32_t>(L.exited_idx); n_ptr = b->st<int32_t>(L.n_exited); }
     uint4* x = b->wsp<uint4>(b->W.fill_x);              // [layer][Mpad][d] normalised exit rows, tile order
     float* kvb = b->wsp<float>(b->W.fill_kv);           // [layer][Mpad][2 H_kv hd]
     TimedScope t(EE_K_FILL_KV, s);
-    // all skipped layers in three launches (blockIdx.z = layer): the layers differ only in
+    // all layers of the range in three launches (blockIdx.z = layer): the layers differ only in
     // their norm gain and their W_k / W_v
     ZBatch zb{};
     zb.w_tab = m->d_wqkv_tab; zb.g_tab = m->d_gattn_tab; zb.z0 = from_excl;

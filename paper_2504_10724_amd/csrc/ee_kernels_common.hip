@@ -278,7 +278,7 @@ k_compact(int32_t* __restrict__ active_idx, int32_t* __restrict__ n_active, int3
           const uint8_t* __restrict__ head_breach, int32_t* __restrict__ out_tok,
           int32_t* __restrict__ out_layer, float* __restrict__ out_conf, uint8_t* __restrict__ out_breach,
           int32_t* __restrict__ exit_counts, int32_t* __restrict__ breach_count, int exit_idx, int exit_layer,
-          int B) {
+          int B, int32_t* __restrict__ gone_idx, int32_t* __restrict__ n_gone) {
     __shared__ int s_keep[COMPACT_THREADS / 64];
     __shared__ int s_gone[COMPACT_THREADS / 64];
     __shared__ int s_brch[COMPACT_THREADS / 64];
@@ -286,6 +286,9 @@ k_compact(int32_t* __restrict__ active_idx, int32_t* __restrict__ n_active, int3
     if (n > B) n = B;
     int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     int keep_base = 0, gone_base = 0, breaches = 0;
+    // gone_idx collects the leavers of all exits of a step (the first exit starts it again); the
+    // bounds hold whatever order the compactions are called in
+    const int all_base = exit_idx == 0 ? 0 : max(0, min(*n_gone, B));
     for (int base = 0; base < n; base += COMPACT_THREADS) {
         int i = base + threadIdx.x;
         bool valid = i < n;
@@ -306,6 +309,7 @@ k_compact(int32_t* __restrict__ active_idx, int32_t* __restrict__ n_active, int3
         if (stays) active_idx[ko + rk] = row;          // ko + rk <= i: never overtakes a later read
         if (leaves) {
             exited_idx[go + rg] = row;
+            if (all_base + go + rg < B) gone_idx[all_base + go + rg] = row;
             out_tok[row] = head_tok[i];
             out_layer[row] = exit_layer;
             out_conf[row] = head_conf[i];
@@ -317,6 +321,7 @@ k_compact(int32_t* __restrict__ active_idx, int32_t* __restrict__ n_active, int3
     if (threadIdx.x == 0) {
         *n_active = keep_base;
         *n_exited = gone_base;
+        *n_gone = min(all_base + gone_base, B);
         exit_counts[exit_idx] += gone_base;
         *breach_count += breaches;
     }
@@ -330,7 +335,8 @@ int launch_compact(ee_batch* b, int exit_idx, int exit_layer, hipStream_t s) {
                        b->st<float>(L.head_conf), b->st<int32_t>(L.head_tok), b->st<uint8_t>(L.head_exit),
                        b->st<uint8_t>(L.head_breach), b->st<int32_t>(L.out_tok), b->st<int32_t>(L.out_layer),
                        b->st<float>(L.out_conf), b->st<uint8_t>(L.out_breach), b->st<int32_t>(L.exit_counts),
-                       b->st<int32_t>(L.breach_count), exit_idx, exit_layer, b->B);
+                       b->st<int32_t>(L.breach_count), exit_idx, exit_layer, b->B, b->wsp<int32_t>(b->W.gone_idx),
+                       b->wsp<int32_t>(b->W.n_gone));
     EE_LAUNCH_CHECK();
     return EE_OK;
 }
