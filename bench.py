@@ -28,8 +28,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the gate/up GEMM at batch 256 from the rocprofv3 counter runs summarised in
 # profiles/llama2_70b_b256_hbm_traffic.md (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, KiB -> bytes); valid
 # only for the kernel source it was measured on.
-TRAFFIC_KERNEL_SHA1 = "b4763929f7335bd396b2454b52cade00724f4807"
-TRAFFIC_GATE_UP_BYTES = (942294 + 9744) * 1024
+TRAFFIC_KERNEL_SHA1 = "25e643b9c898fdcc323e5713c9f4a99052cc2570"
+TRAFFIC_GATE_UP_BYTES = (943883 + 9632) * 1024
 
 
 def measured_traffic(batch):

@@ -805,7 +805,7 @@ k_bf16_rope_append(const float* __restrict__ buf, int ld, int n_q, const int32_t
 // of the value MFMAs (the grouped V layout is chosen to make that so).
 // q and P enter as bf16 (hi, lo) pairs: two MFMAs each, fp32-grade products.
 template <bool PAIR>
-__global__ void __launch_bounds__(256, 3)
+__global__ void __launch_bounds__(256, PAIR ? 3 : 2)
 k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, int Hq,
             const int32_t* __restrict__ idx, const int32_t* __restrict__ n_ptr, int B,
             const int32_t* __restrict__ pos, KvView kv, uint4* __restrict__ ao, int KB_ao, int n_splits,
@@ -869,8 +869,7 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
     // with n_splits > 1 this workgroup covers the blockIdx.z-th share of the position groups
     const int g_lo = (int)(((int64_t)n_groups * blockIdx.z) / n_splits);
     const int g_hi = (int)(((int64_t)n_groups * (blockIdx.z + 1)) / n_splits);
-    // K and V tiles of one 32-position group as this lane holds them for the MFMAs.  Three
-    // workgroups share a CU: while one wave waits for its group the others compute.
+    // K and V tiles of one 32-position group as this lane holds them for the MFMAs
     struct KVTiles { uint4 k[2][4]; uint4 v[8]; };
     auto load_kv = [&](int t) -> KVTiles {
         KVTiles x;
@@ -887,9 +886,21 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
         for (int hb = 0; hb < 8; ++hb) x.v[hb] = load_nt(reinterpret_cast<const uint4*>(vg + hb * 512));
         return x;
     };
+    // Decode: a wave asks for its next group before it works on the current one (two workgroups per
+    // CU then; against three workgroups that load and compute in turn: -2..4 % from 64 to 192 rows,
+    // equal at 256).  Context pass with two entries per workgroup: three workgroups, no prefetch
+    // (0.8 % faster there).
+    KVTiles nxt;
+    if constexpr (!PAIR) nxt = load_kv(min(g_lo + w, max(g_hi - 1, 0)));   // a group this workgroup's row has
     for (int t = g_lo + w; t < g_hi; t += 4) {
         const int p0 = t << 5;
-        const KVTiles cur = load_kv(t);
+        KVTiles cur;
+        if constexpr (PAIR) {
+            cur = load_kv(t);
+        } else {
+            cur = nxt;
+            if (t + 4 < g_hi) nxt = load_kv(t + 4);
+        }
         floatx4 S0 = {0.f, 0.f, 0.f, 0.f}, S1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
