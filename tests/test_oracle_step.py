@@ -249,6 +249,25 @@ def test_no_holes_and_skipped_layer_kv_formula():
                     assert np.array_equal(newK[g], k) and np.array_equal(newV[g], v)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_fill_of_a_layer_range_equals_the_fills_of_its_parts(dtype):
+    # Sec. 2.2: a skipped layer's key/value depends on the token's exit state, the layer and the
+    # position only, so the layers of a range may be filled in any grouping and at any later time
+    # within the step; a step that fills (exit layer, next exit layer] for all rows that have left
+    # so far ends with the same cache as one that fills (exit layer, R] at every exit.
+    s = small_shape(dtype=dtype, n_layers=6, resident=6, exit_layers=(1, 3, 6), thresholds=(0.8, 0.8, 0.8), batch=4)
+    a, b2 = OracleSide(s, std=0.3), OracleSide(s, std=0.3)
+    rng = np.random.default_rng(5)
+    for b in range(s.batch):
+        h = rng.standard_normal(s.d_model).astype(np.float32)
+        p = int(a.ctx[b])
+        assert orc.fill_skipped_kv(a.model, 1, 6, a.kv, b, p, h) == 0
+        for lo, hi in ((3, 6), (1, 3)):                      # parts, deliberately out of order
+            assert orc.fill_skipped_kv(b2.model, lo, hi, b2.kv, b, p, h) == 0
+    assert np.array_equal(a.kv.K, b2.kv.K) and np.array_equal(a.kv.V, b2.kv.V)
+    assert np.any(a.kv.K[5] != 0) and not np.any(a.kv.K[0, :, :, int(a.ctx.max()):])   # layer 1 untouched at the new positions
+
+
 def test_identity_tail_makes_early_exit_equal_to_vanilla():
     # If the layers after the exit add nothing to the hidden state (W_o = W_d = 0)
     # then leaving at the exit and filling the skipped layers' keys/values from
