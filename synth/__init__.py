@@ -20,8 +20,10 @@ paper evaluates on, which are not available here):
 Each tensor has its own counter-based stream keyed by (seed, tensor name), so a
 tensor's values do not depend on which other tensors were drawn before it.
 """
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field, replace
 import hashlib
+import os
 
 import numpy as np
 
@@ -109,13 +111,36 @@ def bf16_bits_to_f32(b):
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+_CHUNK = 1 << 22      # values per independently seeded piece of a tensor
+
+
+def _workers():
+    n = int(os.environ.get("OMP_NUM_THREADS", 0) or os.cpu_count() or 1)
+    return max(1, min(16, n))
+
+
 def normal(seed, name, shape, std, dtype):
     """N(0, std^2) tensor in the storage type of the model: float32 for "f32",
-    bfloat16 bit patterns (uint16) for "bf16"."""
-    g = stream(seed, name)
-    x = g.standard_normal(size=shape, dtype=np.float32)
-    x *= np.float32(std)
-    return to_bf16_bits(x) if dtype == "bf16" else x
+    bfloat16 bit patterns (uint16) for "bf16".  The tensor is drawn in pieces of
+    _CHUNK values (flat, row-major order), piece k from the stream (seed,
+    "name#k"), so the values do not depend on how many threads draw them."""
+    n = int(np.prod(shape))
+    out = np.empty(n, np.uint16 if dtype == "bf16" else np.float32)
+
+    def piece(k):
+        lo, hi = k * _CHUNK, min(n, (k + 1) * _CHUNK)
+        x = stream(seed, f"{name}#{k}").standard_normal(size=hi - lo, dtype=np.float32)
+        x *= np.float32(std)
+        out[lo:hi] = to_bf16_bits(x) if dtype == "bf16" else x
+
+    n_pieces = (n + _CHUNK - 1) // _CHUNK
+    if n_pieces <= 1:
+        for k in range(n_pieces):
+            piece(k)
+    else:
+        with ThreadPoolExecutor(_workers()) as pool:
+            list(pool.map(piece, range(n_pieces)))
+    return out.reshape(shape)
 
 
 def layer_weights(s: Shape, layer: int, std=0.02):
