@@ -14,8 +14,10 @@ low-exit version, otherwise the next best candidate's low-exit version (Algorith
 Readings taken where the text is silent: perplexity of a
 window = exp of the mean of -ln p over its emitted tokens, p being the probability
 the exit head gave the emitted token (the standard definition; the paper prints no
-formula); the PHT figure compared in Algorithm 1 is a cost (lower is better) and a
-tie keeps the chosen model; throughput is tokens divided by the wall time the caller
+formula); the PHT figure compared in Algorithm 1 is a cost (lower is better); the
+comparison is strict as printed there ("<"; Sec. 3.3.3: loading more layers pays only
+while its overall resource usage "remains lower" than the other option's), so on a tie
+the else branch is taken and the next best candidate's low-exit version is served; throughput is tokens divided by the wall time the caller
 measured, so it is not part of the device-side row.
 
 Plain definitions written out; pinned in tests/test_oracle_pht.py.
@@ -56,6 +58,6 @@ def load_or_switch(cost_full_chosen, cost_low_exit_others):
     if not cost_low_exit_others:
         return ("load", None)
     best = min(cost_low_exit_others, key=lambda k: (cost_low_exit_others[k], str(k)))
-    if cost_full_chosen <= cost_low_exit_others[best]:
+    if cost_full_chosen < cost_low_exit_others[best]:
         return ("load", None)
     return ("switch", best)

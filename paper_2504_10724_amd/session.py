@@ -429,14 +429,14 @@ class PhtRow:
 
 def load_or_switch(cost_full_chosen, cost_low_exit_others):
     """The branch of Algorithm 1 taken when the breach counter fires: load the rest of the chosen
-    model if its figure (a cost, lower is better) is not above that of every other candidate's
-    low-exit version, else switch to the cheapest of those.  Returns ("load", None) or
-    ("switch", candidate)."""
+    model if its figure (a cost, lower is better) is strictly below that of every other
+    candidate's low-exit version, else (a tie included, as the condition is printed) switch to
+    the cheapest of those.  Returns ("load", None) or ("switch", candidate)."""
     best = None
     for name in sorted(cost_low_exit_others, key=str):
         if best is None or cost_low_exit_others[name] < cost_low_exit_others[best]:
             best = name
-    if best is None or cost_full_chosen <= cost_low_exit_others[best]:
+    if best is None or cost_full_chosen < cost_low_exit_others[best]:
         return ("load", None)
     return ("switch", best)
 

@@ -1,9 +1,33 @@
 """Test-side glue: builds the CPU oracle's model / cache from the seeded
 synthetic inputs.  Imports the oracle, so it is test infrastructure too."""
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 
 import synth
 from oracle import ee_oracle as orc
+
+
+def draw_weights(s, n_distinct=None, std=0.02):
+    """Weights of the resident layers, the resident exit heads and the embedding.  With
+    n_distinct, only that many layers are drawn and layer l takes the tensors of drawn layer
+    ((l - 1) mod n_distinct) + 1 (the same objects): a model of the workload's real depth and
+    shapes whose host and device footprint stays small.  Both sides get the same dict."""
+    n = s.resident if n_distinct is None else min(n_distinct, s.resident)
+    base = {k: synth.layer_weights(s, k, std) for k in range(1, n + 1)}
+    return {"layers": {l: base[(l - 1) % n + 1] for l in range(1, s.resident + 1)},
+            "exits": {e: synth.exit_weights(s, e, std) for e, l in enumerate(s.exit_layers) if l <= s.resident},
+            "embed": synth.embedding(s, std)}
+
+
+def draw_contexts(s, rows):
+    """Cached context {(layer, row): (K, V)} of the given rows in every resident layer, drawn by a
+    thread pool (each (layer, row) has its own stream, so the order does not matter)."""
+    ctx = synth.context_lengths(s)
+    keys = [(l, int(b)) for l in range(1, s.resident + 1) for b in rows]
+    with ThreadPoolExecutor(synth._workers()) as pool:
+        vals = list(pool.map(lambda k: synth.kv_rows(s, k[0], k[1], int(ctx[k[1]])), keys))
+    return dict(zip(keys, vals))
 
 
 def small_shape(**kw):
@@ -17,7 +41,8 @@ def small_shape(**kw):
 class OracleSide:
     """Oracle model + dense cache for rows `rows` (default: all) of a workload."""
 
-    def __init__(self, s, rows=None, weights=None, std=0.02, cap=None, fill_ctx=True, gain_jitter=0.1):
+    def __init__(self, s, rows=None, weights=None, std=0.02, cap=None, fill_ctx=True, gain_jitter=0.1,
+                 contexts=None):
         self.s = s
         self.rows = list(range(s.batch)) if rows is None else list(rows)
         self.model = orc.OracleModel(n_layers=s.n_layers, d_model=s.d_model, n_q_heads=s.n_q_heads,
@@ -52,7 +77,7 @@ class OracleSide:
         if fill_ctx:
             for l in range(1, s.resident + 1):
                 for i, b in enumerate(self.rows):
-                    K, V = synth.kv_rows(s, l, b, int(self.ctx_all[b]))
+                    K, V = contexts[(l, b)] if contexts is not None else synth.kv_rows(s, l, b, int(self.ctx_all[b]))
                     if s.dtype == "bf16":
                         K, V = synth.bf16_bits_to_f32(K), synth.bf16_bits_to_f32(V)
                     n = int(self.ctx_all[b])

@@ -4,18 +4,26 @@ Per call (same inputs on both sides): exit masks, tokens, breach flags and
 compaction indices bit-exact, except rows whose oracle confidence lies within
 NEAR = 1e-3 of the threshold, which are counted separately.  Hidden states and
 logits: per row, max |gpu - oracle| <= tol * max |oracle| with tol = 2e-2 for
-bf16 models and 2e-4 for fp32 models.
+bf16 models and 2e-4 for fp32 models.  The teacher-forced tests
+(test_gpu_configs.py) apply exactly this at every layer, exit and fill of a
+model: before each call the GPU is given the oracle's state.
 
-Whole decode steps run both sides freely through several layers.  Under the
+Whole decode steps run both sides freely through many layers.  Under the
 bf16 contract every matrix-product operand is rounded to bfloat16, and a chain
 of such roundings turns a difference of one fp32 ulp (a different summation
 order) into differences of bf16 size within a few layers, in the oracle as in
 any other implementation.  The step comparison therefore measures that noise
-with the oracle itself: a second oracle whose fp32 RMSNorm gains are perturbed
-by one part in 10^6 runs beside the first, and the largest confidence change it
-shows at an exit widens that exit's band (never below 1e-3).  Rows inside a band
-are "near"; rows within the 1e-3 band are also counted on their own.  Every
-other row must match bit-exactly on exit layer, token and breach flag.
+with the oracle itself: further oracles whose fp32 RMSNorm gains are perturbed
+by one part in 10^6 ("shadows") run beside the first, and the largest confidence
+change they show at an exit is that exit's band (never below 1e-3).  Rows
+whose confidence lies inside the band of an exit with a deciding threshold are
+"near"; rows within the 1e-3 band are also counted on their own.  Every other
+row must match bit-exactly on exit layer, token and breach flag, its confidence
+within the band of the exit it left at and its hidden state there within the
+hidden-state tolerance.  A row whose confidence differs by more than the band
+but less than four times the band is excluded and counted too (the band is the
+largest of a few hundred draws of the noise; one more draw exceeds it now and
+then); beyond four times the band it is a mismatch.
 """
 import numpy as np
 import torch
@@ -41,10 +49,11 @@ def rows_close(got, want, tol):
 class GpuSide:
     """libee model + cache + batch state for the same synthetic workload the oracle sees."""
 
-    def __init__(self, s, weights=None, std=0.02, cap_multiple=32, max_pos=None, synth_rows=None):
+    def __init__(self, s, weights=None, std=0.02, cap_multiple=32, max_pos=None, synth_rows=None, contexts=None):
         """synth_rows: if given, only these rows get their cached context from the seeded host
         generator (the rows an oracle will recompute); the others are filled on the device from
-        the same distribution, which is much faster for large batches."""
+        the same distribution, which is much faster for large batches.  contexts: what
+        helpers.draw_contexts returned for those rows (drawn once for both sides)."""
         self.s = s
         if weights is None:
             weights = {
@@ -56,8 +65,15 @@ class GpuSide:
         self.cap = synth.capacity_for(self.ctx, s.steps, cap_multiple)
         mp = int(self.cap.max()) if max_pos is None else max_pos
         self.model = S.Model.from_shape(s, max_pos=mp)
+        on_device = {}                      # layers that share their host tensors share the device copies
         for l, w in weights["layers"].items():
-            self.model.set_layer(l, **w)
+            if id(w) not in on_device:
+                self.model.set_layer(l, **w)
+                on_device[id(w)] = self.model._keep[("layer", l)]
+            else:
+                g_attn, w_qkv, w_o, g_ffn, w_gate_up, w_down = on_device[id(w)]
+                self.model.set_layer_device(l, g_attn=g_attn, w_qkv=w_qkv, w_o=w_o, g_ffn=g_ffn,
+                                            w_gate_up=w_gate_up, w_down=w_down)
         for e, w in weights["exits"].items():
             self.model.set_exit(e, **w)
         self.model.set_embed(weights["embed"])
@@ -66,10 +82,12 @@ class GpuSide:
             gen = torch.Generator(device="cuda")
             gen.manual_seed(s.seed + 1)
             pool = self.kv.pool.view(torch.bfloat16 if s.dtype == "bf16" else torch.float32)
-            pool.normal_(0.0, 0.02 * float(np.sqrt(s.d_model)), generator=gen)
+            chunk = 1 << 30
+            for i in range(0, pool.numel(), chunk):
+                pool[i:i + chunk].normal_(0.0, 0.02 * float(np.sqrt(s.d_model)), generator=gen)
         for l in range(1, s.resident + 1):
             for b in (range(s.batch) if synth_rows is None else synth_rows):
-                K, V = synth.kv_rows(s, l, b, int(self.ctx[b]))
+                K, V = contexts[(l, int(b))] if contexts is not None else synth.kv_rows(s, l, b, int(self.ctx[b]))
                 self.kv.write_context(l, b, K, V)
         self.batch = S.Batch(self.model, s.batch)
         self.batch.reset(synth.first_tokens(s), self.ctx.astype(np.int32), None)
@@ -85,11 +103,11 @@ class GpuSide:
                     conf=f("out_conf").cpu().numpy(), breach=f("out_breach").cpu().numpy(),
                     counts=f("exit_counts").cpu().numpy(), status=int(f("status").cpu()[0]),
                     n_active=int(f("n_active").cpu()[0]), pos=f("pos").cpu().numpy(),
-                    tok_in=f("tok_in").cpu().numpy())
+                    tok_in=f("tok_in").cpu().numpy(), h=f("h").cpu().numpy())
 
 
-def shadow_of(o, rel=1e-6, seed=7):
-    """A second oracle on the same workload whose fp32 norm gains differ by `rel`
+def shadow_of(o, rel=1e-6, seed=7, contexts=None):
+    """A further oracle on the same workload (same rows) whose fp32 norm gains differ by `rel`
     (relative): the probe of how far the precision contract's own rounding
     lets two correct implementations drift apart."""
     s = o.s
@@ -99,35 +117,43 @@ def shadow_of(o, rel=1e-6, seed=7):
     for w in w2["layers"].values():
         for k in ("g_attn", "g_ffn"):
             w[k] = (w[k].astype(np.float64) * (1 + rel * rng.standard_normal(s.d_model))).astype(np.float32)
-    return OracleSide(s, rows=o.rows, weights=w2, cap=o.cap, gain_jitter=0)
+    return OracleSide(s, rows=o.rows, weights=w2, cap=o.cap, gain_jitter=0, contexts=contexts)
 
 
-def compare_step(s, o, g, step_idx, thresholds=None, sticky=None, shadow=None):
-    """Runs decode step `step_idx` on the oracle, on the GPU and (if given) on the
-    shadow oracle, and classifies every row.  `sticky`: rows already excluded."""
+def compare_step(s, o, g, step_idx, thresholds=None, sticky=None, shadow=None, band_floor=NEAR):
+    """Runs decode step `step_idx` on the oracle, on the GPU and on the shadow oracles (one, a
+    list, or none), and classifies every row the oracle holds (o.rows: all rows of the batch, or a
+    sample; the GPU always runs the whole batch).  `sticky`: rows (indices into o.rows) already
+    excluded.  band_floor: lowest band (a handful of sampled rows cannot estimate the tail of the
+    noise, so the sampled tests keep the floor that the batch-wide tests measure)."""
     th = np.asarray(s.thresholds if thresholds is None else thresholds, np.float32)
-    sc = o.scale(step_idx)
-    if shadow is not None:
-        shadow.tok = o.tok.copy()          # the probe follows the oracle's token stream
+    rows = np.asarray(o.rows)
+    n = rows.size
+    sc_all = synth.row_scale(s, step_idx)
+    sc = sc_all[rows]
+    shadows = [] if shadow is None else (list(shadow) if isinstance(shadow, (list, tuple)) else [shadow])
+    for sh in shadows:
+        sh.tok = o.tok.copy()              # the probes follow the oracle's token stream
     og = o.step(step_idx, thresholds=th, want_h=True, scale=sc)
-    gg = g.step(step_idx, thresholds=th, scale=sc)
-    assert og["rc"] == 0 and gg["rc"] == 0, (og["rc"], gg["rc"])
-    assert gg["status"] == 0, f"device status {gg['status']}"
-    B = s.batch
+    ga = g.step(step_idx, thresholds=th, scale=sc_all)
+    assert og["rc"] == 0 and ga["rc"] == 0, (og["rc"], ga["rc"])
+    assert ga["status"] == 0, f"device status {ga['status']}"
+    per_row = ("tok", "layer", "conf", "breach", "pos", "tok_in", "h")
+    gg = {k: (v[rows] if k in per_row else v) for k, v in ga.items()}
     res_exits = s.resident_exits
     tr = og["conf_trace"]
-    band = np.full(len(res_exits), NEAR, np.float64)
-    unstable = np.zeros(B, bool)
-    if shadow is not None:
-        sg = shadow.step(step_idx, thresholds=th, scale=sc)
+    band = np.full(len(res_exits), max(NEAR, band_floor), np.float64)
+    unstable = np.zeros(n, bool)
+    for sh in shadows:
+        sg = sh.step(step_idx, thresholds=th, scale=sc)
         assert sg["rc"] == 0
         unstable |= (sg["tok"] != og["tok"]) | (sg["layer"] != og["layer"])
         for e in range(len(res_exits)):
             both = np.isfinite(tr[:, e]) & np.isfinite(sg["conf_trace"][:, e])
             if both.any():
-                band[e] = max(NEAR, float(np.abs(tr[both, e] - sg["conf_trace"][both, e]).max()))
-    strict = np.zeros(B, bool)
-    noisy = np.zeros(B, bool)
+                band[e] = max(band[e], float(np.abs(tr[both, e] - sg["conf_trace"][both, e]).max()))
+    strict = np.zeros(n, bool)
+    noisy = np.zeros(n, bool)
     for e in range(len(res_exits)):
         if not (0.0 < th[e] <= 1.0):
             continue   # a threshold <= 0 is always met and one above 1 never: nothing to decide
@@ -135,32 +161,53 @@ def compare_step(s, o, g, step_idx, thresholds=None, sticky=None, shadow=None):
         reached = np.isfinite(c)
         strict |= reached & (np.abs(c - th[e]) <= NEAR)
         noisy |= reached & (np.abs(c - th[e]) <= band[e])
+    left_at = np.array([res_exits.index(int(l)) if int(l) in res_exits else 0 for l in og["layer"]])
     # a different token is tolerated only where the oracle's own top candidates are closer than
     # the noise allows (one probability may fall by the band while the other rises by it):
     # p_oracle(tok_oracle) - p_oracle(tok_gpu) <= 2 * band at the exit the row left
-    tok_amb = np.zeros(B, bool)
-    for b in np.nonzero((og["tok"] != gg["tok"]) & (og["layer"] == gg["layer"]))[0]:
-        e = res_exits.index(int(og["layer"][b]))
-        _, _, z = orc.exit_head(o.model, s.exit_layers.index(res_exits[e]), og["h"][b], float(sc[b]), want_logits=True)
+    tok_amb = np.zeros(n, bool)
+    for i in np.nonzero((og["tok"] != gg["tok"]) & (og["layer"] == gg["layer"]))[0]:
+        e = left_at[i]
+        _, _, z = orc.exit_head(o.model, s.exit_layers.index(res_exits[e]), og["h"][i], float(sc[i]), want_logits=True)
         p = np.exp(z.astype(np.float64) - z.max()); p /= p.sum()
-        tok_amb[b] = (p.max() - p[gg["tok"][b]]) <= 2 * band[e]
-    near = noisy | unstable | tok_amb
+        tok_amb[i] = (p.max() - p[gg["tok"][i]]) <= 2 * band[e]
+    cerr = np.abs(og["conf"].astype(np.float64) - gg["conf"])
+    row_band = band[left_at] if s.dtype == "bf16" else np.full(n, 1e-4)
+    same_exit = og["layer"] == gg["layer"]
+    conf_soft = same_exit & (cerr > row_band) & (cerr <= 4 * row_band)
+    near = noisy | unstable | tok_amb | conf_soft
+    near_now = near.copy()
     if sticky is not None:
         sticky |= near
         near = sticky.copy()
     ok = ~near
     bad = ok & ((og["tok"] != gg["tok"]) | (og["layer"] != gg["layer"]) | (og["breach"] != gg["breach"]))
-    conf_tol = 1e-4 if s.dtype == "f32" else max(5e-3, 4 * float(band.max()))
-    cerr = np.abs(og["conf"] - gg["conf"])
-    bad |= ok & (cerr > conf_tol)
+    bad |= ok & (cerr > row_band)
+    # hidden state where the row left the stack
+    herr = np.abs(gg["h"].astype(np.float64) - og["h"]).max(1) / np.maximum(np.abs(og["h"]).max(1), 1e-30)
+    bad |= ok & (herr > TOL[s.dtype])
+    # what the strict contract alone (1e-3 band, nothing else excluded) would report
+    differs = (og["tok"] != gg["tok"]) | (og["layer"] != gg["layer"]) | (og["breach"] != gg["breach"])
     rep = dict(mismatch=int(bad.sum()), near=int(near.sum()), near_strict=int(strict.sum()),
                near_noise=int((noisy & ~strict).sum()), near_unstable=int((unstable & ~noisy).sum()),
-               near_token=int((tok_amb & ~noisy & ~unstable).sum()), rows=int(ok.sum()), band=band.tolist(),
-               max_conf_err=float(cerr[ok].max()) if ok.any() else 0.0, oracle=og, gpu=gg)
-    rep["detail"] = [dict(row=int(b), oracle=(int(og["tok"][b]), int(og["layer"][b]), float(og["conf"][b])),
-                          gpu=(int(gg["tok"][b]), int(gg["layer"][b]), float(gg["conf"][b])),
-                          trace=tr[b].tolist()) for b in np.nonzero(bad)[0][:8]]
+               near_token=int((tok_amb & ~noisy & ~unstable).sum()),
+               near_conf=int((conf_soft & ~noisy & ~unstable & ~tok_amb).sum()), rows=int(ok.sum()), band=band.tolist(),
+               max_conf_err=float(cerr[ok].max()) if ok.any() else 0.0,
+               max_h_err=float(herr[ok].max()) if ok.any() else 0.0,
+               strict_only_differs=int((differs & ~strict).sum()), excluded_now=near_now, oracle=og, gpu=gg, gpu_all=ga)
+    rep["detail"] = [dict(row=int(rows[i]), oracle=(int(og["tok"][i]), int(og["layer"][i]), float(og["conf"][i])),
+                          gpu=(int(gg["tok"][i]), int(gg["layer"][i]), float(gg["conf"][i])), h_err=float(herr[i]),
+                          trace=tr[i].tolist()) for i in np.nonzero(bad)[0][:8]]
     assert np.array_equal(gg["pos"], o.pos), "positions diverged"
-    if not near.any() and not bad.any():
+    if n == s.batch and not near.any() and not bad.any():
         assert np.array_equal(gg["tok_in"], og["tok"])
     return rep
+
+
+def report_line(step, rep):
+    return (f"  step {step}: compared {rep['rows']} rows, mismatch {rep['mismatch']}; excluded: 1e-3 band "
+            f"{rep['near_strict']}, noise band {rep['near_noise']}, unstable {rep['near_unstable']}, token "
+            f"{rep['near_token']}, confidence {rep['near_conf']} (bands {['%.1e' % x for x in rep['band']]}); "
+            f"under the 1e-3 band alone {rep['strict_only_differs']} rows would differ; max conf err "
+            f"{rep['max_conf_err']:.2e}, max hidden err {rep['max_h_err']:.2e}; exits "
+            f"{np.bincount(rep['oracle']['layer'])[1:].tolist()}")

@@ -9,7 +9,7 @@ import torch
 import synth
 from oracle import ee_oracle as orc
 from helpers import OracleSide
-from parity import GpuSide, compare_step, shadow_of, rows_close, TOL, NEAR
+from parity import GpuSide, compare_step, report_line, shadow_of, rows_close, TOL, NEAR
 from paper_2504_10724_amd import capi as ee
 from paper_2504_10724_amd import session as S
 
@@ -169,19 +169,17 @@ def test_calls_one_by_one(s):
 def test_decode_steps(s):
     _say(f"[case] decode_steps {s.name} seed={s.seed} B={s.batch} steps={s.steps}")
     o, g = _fresh(s, jitter=0.0)
-    shadow = shadow_of(o) if s.dtype == "bf16" else None
+    shadows = [shadow_of(o, seed=k) for k in (7, 8, 9)] if s.dtype == "bf16" else None
     sticky = np.zeros(s.batch, bool)
     layers_seen = set()
     for step in range(s.steps):
-        rep = compare_step(s, o, g, step, sticky=sticky, shadow=shadow)
-        _say(f"  step {step}: compared {rep['rows']} rows, mismatch {rep['mismatch']}; near: 1e-3 band "
-             f"{rep['near_strict']}, noise band {rep['near_noise']}, unstable {rep['near_unstable']}, "
-             f"token {rep['near_token']} (bands {['%.1e' % x for x in rep['band']]}); max conf err "
-             f"{rep['max_conf_err']:.2e}; exits {np.bincount(rep['oracle']['layer'])[1:].tolist()}")
+        rep = compare_step(s, o, g, step, sticky=sticky, shadow=shadows)
+        _say(report_line(step, rep))
         assert rep["mismatch"] == 0, rep["detail"]
         layers_seen |= set(rep["oracle"]["layer"].tolist())
-        assert rep["gpu"]["n_active"] == 0
-    assert sticky.sum() <= max(3, s.batch * s.steps // 10), f"{sticky.sum()} of {s.batch} rows excluded"
+        assert rep["gpu_all"]["n_active"] == 0
+    _say(f"  excluded after {s.steps} steps: {int(sticky.sum())} of {s.batch} rows ({sticky.mean():.1%})")
+    assert sticky.sum() <= max(3, s.batch * s.steps // 20), f"{sticky.sum()} of {s.batch} rows excluded"
     if len(s.resident_exits) > 1:
         assert len(layers_seen) > 1, "workload must use more than one exit"
     # cache after the steps: all positions of sampled rows, every resident layer.  bf16: 1e-2 normwise
@@ -219,7 +217,7 @@ def test_two_runs_are_bitwise_identical():
     for k in ("tok", "layer", "conf", "breach"):
         assert np.array_equal(r1[k], r2[k]), k
     assert torch.equal(g1.batch.field("h"), g2.batch.field("h"))
-    assert torch.equal(g1.kv.pool, g2.kv.pool) or True   # untouched pool bytes are uninitialised; compare rows below
+    # untouched pool bytes are uninitialised: the cache is compared through the rows read back below
     for b in (0, s.batch - 1):
         for l in (1, s.resident):
             K1, V1 = g1.kv.read_context(l, b, int(g1.ctx[b]) + 1)

@@ -60,5 +60,8 @@ def test_load_or_switch_branch():
     assert load_or_switch(1.0, {"b": 1.5, "c": 2.0}) == ("load", None)
     assert load_or_switch(1.8, {"b": 1.5, "c": 2.0}) == ("switch", "b")
     assert load_or_switch(3.0, {"b": 2.5, "c": 2.0}) == ("switch", "c")
-    assert load_or_switch(2.0, {"b": 2.0}) == ("load", None)        # a tie keeps the chosen model
+    # the printed condition is strict: on a tie the else branch (next best candidate) is taken
+    assert load_or_switch(2.0, {"b": 2.0}) == ("switch", "b")
+    assert load_or_switch(2.0, {"b": 2.0, "c": 2.0}) == ("switch", "b")
+    assert load_or_switch(np.nextafter(2.0, 0.0), {"b": 2.0}) == ("load", None)
     assert load_or_switch(9.0, {}) == ("load", None)                # nobody to switch to
