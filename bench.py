@@ -128,7 +128,16 @@ def cpu_baseline(s, exit_hist, budget_s=10.0, chunk=8):
     for e, l in enumerate(exits):
         t_tok += frac[e] * (l * t_layer + (e + 1) * t_exit + (s.resident - l) * t_fill)
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return dict(value=1.0 / t_tok, unit="tokens/s", cores=cores, kind="oracle",
+    cpu_model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                cpu_model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    return dict(value=1.0 / t_tok, unit="tokens/s", cores=cores, kind="oracle (per-row costs of a sample, extrapolated)",
+                cpu_model=cpu_model,
                 sample=f"1 layer x {n_rows} rows ({t_layers:.1f} s), 1 exit head and 1 skipped-layer KV fill x "
                        f"{n_small} rows, at the workload's shape; per-row costs {t_layer:.3f}/{t_exit:.3f}/{t_fill:.4f} s combined "
                        f"with the measured exit histogram over {s.resident} layers")
@@ -196,7 +205,7 @@ def measure_layer_load(s, model, args, torch, S, ee, kv, batch, run, reset):
     return res
 
 
-def run_workload(s, model, args, torch, S, ee, synth, C, timed=True, with_load=False):
+def run_workload(s, model, args, torch, S, ee, synth, C, with_load=False):
     """One batch size: bind cache and batch state, warm up, rewind, time `steps` decode steps."""
     lib = model.lib
     total_steps = args.steps + args.warmup

@@ -96,7 +96,8 @@ typedef struct {
  *           then H_kv*hd value rows
  *   w_o   : [d][H_q hd]
  *   w_gate_up : EE_F32: [2F][d], the F gate rows followed by the F up rows;
- *               EE_BF16: packed with gate tile j at tile 2j and up tile j at tile 2j+1
+ *               EE_BF16: the packed form of the [2F][d] matrix whose row 2j is gate row j and
+ *               whose row 2j+1 is up row j (one lane of a matrix-core result then holds both)
  *   w_down: [d][F]
  *   g_attn, g_ffn: fp32 [d] RMSNorm gains. */
 typedef struct {
@@ -121,29 +122,31 @@ int ee_device_count(void);
 /* Bytes of the packed form of an [n_out][n_in] bf16 matrix (= n_out*n_in*2). */
 size_t ee_packed_bytes(int n_out, int n_in);
 
-/* Repack a row-major bf16 matrix src[n_out][n_in] (dev) into the tile order the
- * MFMA kernels stream: the matrix is cut into tiles of 32 output rows x 16 input
- * columns; tile (r, c) is stored as 64 x 8 values where entry (l, j) is
- * src[32 r + l % 32][16 c + 8 (l / 32) + j].  The destination holds
- * dst_tile_rows tile-rows; source tile (r, c) goes to tile slot
- * c * dst_tile_rows + (tile_offset + r * tile_stride), i.e. all tiles of one
- * 16-column slice of K are contiguous.  (tile_offset, tile_stride,
- * dst_tile_rows) = (0, 1, n_out/32) packs a matrix on its own; (0, 2, 2F/32)
- * and (1, 2, 2F/32) interleave the gate and up matrices into one w_gate_up
- * buffer.  n_out % 32 == 0 and n_in % 16 == 0, else EE_ERR_SHAPE; a placement
- * outside the destination gives EE_ERR_INVALID_ARG.  Runs on `stream`; src may
- * be freed after the stream is synchronised. */
+/* Repack rows of a row-major bf16 matrix src[n_out][n_in] (dev) into the tile order the MFMA
+ * kernels stream.  The destination is the packed form of a [dst_rows][n_in] matrix D: it is cut
+ * into tiles of 32 rows x 16 input columns; tile (r, c) sits at tile slot c * (dst_rows / 32) + r
+ * (all tiles of one 16-column slice of K are contiguous) and is stored as 64 x 8 values where
+ * entry (l, j) is D[32 r + l % 32][16 c + 8 (l / 32) + j].  Source row i becomes row
+ * row_offset + i * row_stride of D.  (row_offset, row_stride, dst_rows) = (0, 1, n_out) packs a
+ * matrix on its own; (0, 2, 2F) for the gate matrix and (1, 2, 2F) for the up matrix build
+ * w_gate_up, in which gate row j and up row j are neighbours (rows 2j and 2j+1).
+ * n_in % 16 == 0 and dst_rows % 32 == 0, else EE_ERR_SHAPE; a placement outside the destination
+ * gives EE_ERR_INVALID_ARG.  Runs on `stream`; src may be freed after the stream is synchronised. */
 int ee_pack_weight(const void* dev_src, int n_out, int n_in, void* dev_dst,
-                   int tile_offset, int tile_stride, int dst_tile_rows, void* stream);
+                   int row_offset, int row_stride, int dst_rows, void* stream);
 
 /* ------------------------------------------------------------------ handles */
 
 /* Creates a model description with no layer resident.  Builds the rotary
- * cos/sin table for positions < max_pos on the current device. */
+ * cos/sin table for positions < max_pos on the current device.  Set-up call:
+ * it allocates the table and two per-layer pointer tables and waits for the
+ * default stream (the table kernel) before it returns. */
 int ee_model_create(const ee_model_config* cfg, ee_model** out);
 int ee_model_destroy(ee_model* m);
 /* Makes layer `layer` resident (Sec. 3.3.3: only the layers up to the chosen
- * exit are loaded).  The pointed-to buffers must outlive the model. */
+ * exit are loaded).  The pointed-to buffers must outlive the model.  Set-up
+ * call: the two device-side table entries are written with synchronous copies
+ * (ee_model_set_layer_on is the variant that does not wait). */
 int ee_model_set_layer(ee_model* m, int layer, const ee_layer_weights* dev_w);
 /* Exit head exit_idx: fp32 gain [d] and W_exit [V][d] (packed if EE_BF16). */
 int ee_model_set_exit(ee_model* m, int exit_idx, const float* dev_gain, const void* dev_w_exit);
@@ -239,7 +242,10 @@ int ee_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, void*
 int ee_exit_head(const ee_model* m, int exit_idx, float threshold, int force_exit,
                  ee_batch* b, float* dev_dbg_logits, void* stream);
 
-/* Order-preserving compaction of the active rows by head_exit: survivors stay in
+/* The step that lets rows of one batch leave at different exits (Sec. 1: batching early-exit
+ * requests needs the tokens of a batch kept in step; Sec. 5.4 removes the problem by making every
+ * token of a batch stop at the same layer, here the batch is re-formed on the device instead).
+ * Order-preserving compaction of the active rows by head_exit: survivors stay in
  * active_idx (ascending), leavers go to exited_idx; the leavers' token, layer,
  * confidence and breach flag are scattered to out_*[row id]; n_active, n_exited,
  * exit_counts[exit_idx] and breach_count are updated on the device. */
@@ -251,7 +257,9 @@ int ee_compact_active(ee_batch* b, int exit_idx, int exit_layer, void* stream);
 int ee_fill_skipped_kv(const ee_model* m, int from_layer_excl, int to_layer_incl,
                        ee_kv* kv, ee_batch* b, void* stream);
 
-/* One whole early-exit decode step: embed tok_in; for l = 1..R run the layer on
+/* One whole early-exit decode step, i.e. one output token for every request of the batch
+ * (Sec. 2.1: a token is emitted at the first exit whose confidence threshold it meets; Sec. 3.3.3 and
+ * Sec. 5.4: at the last resident layer R in any case): embed tok_in; for l = 1..R run the layer on
  * the active rows and, where l carries an exit, the exit head, the compaction
  * and the fill of skipped layers; then pos += 1 and tok_in = out_tok for every
  * row.  When the step returns, every row has its K and V in all R layers, as if

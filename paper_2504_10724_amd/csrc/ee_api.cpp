@@ -99,14 +99,14 @@ size_t ee_packed_bytes(int n_out, int n_in) {
     return (size_t)n_out * (size_t)n_in * 2;
 }
 
-int ee_pack_weight(const void* dev_src, int n_out, int n_in, void* dev_dst, int tile_offset,
-                   int tile_stride, int dst_tile_rows, void* stream) {
+int ee_pack_weight(const void* dev_src, int n_out, int n_in, void* dev_dst, int row_offset, int row_stride,
+                   int dst_rows, void* stream) {
     if (!dev_src || !dev_dst) return ee_fail(EE_ERR_INVALID_ARG, "ee_pack_weight: null pointer");
-    if (n_out <= 0 || n_in <= 0 || n_out % 32 != 0 || n_in % 16 != 0)
-        return ee_fail(EE_ERR_SHAPE, "ee_pack_weight: n_out must be a multiple of 32 and n_in of 16");
-    if (tile_offset < 0 || tile_stride < 1 || tile_offset + (n_out / 32 - 1) * tile_stride >= dst_tile_rows)
-        return ee_fail(EE_ERR_INVALID_ARG, "ee_pack_weight: tile placement outside the destination");
-    return launch_pack_weight(dev_src, n_out, n_in, dev_dst, tile_offset, tile_stride, dst_tile_rows, as_stream(stream));
+    if (n_out <= 0 || n_in <= 0 || n_in % 16 != 0 || dst_rows <= 0 || dst_rows % 32 != 0)
+        return ee_fail(EE_ERR_SHAPE, "ee_pack_weight: n_in must be a multiple of 16 and dst_rows of 32");
+    if (row_offset < 0 || row_stride < 1 || (int64_t)row_offset + (int64_t)(n_out - 1) * row_stride >= dst_rows)
+        return ee_fail(EE_ERR_INVALID_ARG, "ee_pack_weight: row placement outside the destination");
+    return launch_pack_weight(dev_src, n_out, n_in, dev_dst, row_offset, row_stride, dst_rows, as_stream(stream));
 }
 
 // ------------------------------------------------------------------ model
@@ -374,8 +374,6 @@ static void lay_workspace(const ee_model* m, int B, WsLayout* W) {
         W->fill_kv = take(fill_layers * Mpad * kvn * 4);
         W->gemm_part_bytes = Mpad * ((size_t)384 << 10);   // K-slice planes: 96 MiB at 256 rows
         W->gemm_part = take(W->gemm_part_bytes);
-        W->gemm_cnt_ints = 4096;
-        W->gemm_cnt = take(W->gemm_cnt_ints * 4);
         size_t pairs = Mpad * (size_t)c.n_kv_heads;   // position shares only when there are few pairs
         W->attn_part_bytes = pairs < 512 + 32 * (size_t)c.n_kv_heads ? pairs * 16 * 16 * 130 * 4 : 0;
         W->attn_part = take(W->attn_part_bytes);
@@ -398,7 +396,6 @@ static void lay_workspace(const ee_model* m, int B, WsLayout* W) {
         W->fill_x = take(Mpad * c.d_model * 4);
         W->fill_kv = take(Mpad * kvn * 4);
         W->gemm_part_bytes = 0; W->gemm_part = take(0);
-        W->gemm_cnt_ints = 0;   W->gemm_cnt = take(0);
         W->attn_part_bytes = 0; W->attn_part = take(0);
         W->attn_order = take(0);
         W->kv_seq = take(Mpad * 4);
@@ -448,13 +445,6 @@ int ee_batch_bind(const ee_model* m, int B, void* dev_state, size_t state_bytes,
     size_t t = 0;
     lay_state(m, B, &b->L, &t);
     lay_workspace(m, B, &b->W);
-    if (b->W.gemm_cnt_ints) {   // arrival counters start at zero and reset themselves after each use
-        hipError_t e = hipMemset(b->ws + b->W.gemm_cnt, 0, b->W.gemm_cnt_ints * 4);
-        if (e != hipSuccess) {
-            delete b;
-            return ee_fail(EE_ERR_HIP, std::string("ee_batch_bind: ") + hipGetErrorString(e));
-        }
-    }
     *out = b;
     return EE_OK;
 }

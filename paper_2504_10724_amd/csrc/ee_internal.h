@@ -44,7 +44,7 @@ struct ee_kv {
 // byte offsets inside the workspace
 struct WsLayout {
     size_t x, qkv, q_hi, q_lo, ao, act, part_max, part_sum, part_arg, logits, fill_x, fill_kv, total;
-    size_t gemm_part, gemm_part_bytes, gemm_cnt, gemm_cnt_ints;   // K-slice partial planes
+    size_t gemm_part, gemm_part_bytes;                            // K-slice partial planes
     size_t attn_part, attn_part_bytes;                            // attention position shares
     size_t attn_order;                                            // int32 [Mpad]: list entries, longest context first
     size_t kv_seq;                                                // int32 [Mpad]: cache row of each entry (context pass)
@@ -120,8 +120,8 @@ int launch_cbc_init(void* st, int window, int cbc_max, hipStream_t s);
 int launch_cbc_push(void* st, const uint8_t* flags, int n, hipStream_t s);
 int launch_pht_init(void* row, hipStream_t s);
 int launch_pht_push(void* row, const ee_model* m, const ee_batch* b, hipStream_t s);
-int launch_pack_weight(const void* src, int n_out, int n_in, void* dst, int tile_off, int tile_stride,
-                       int dst_tile_rows, hipStream_t s);
+int launch_pack_weight(const void* src, int n_out, int n_in, void* dst, int row_off, int row_stride,
+                       int dst_rows, hipStream_t s);
 int launch_kv_copy_context(const ee_model* m, const ee_kv* kv, int layer, int row, int pos0, int n_pos,
                            void* k, void* v, bool to_pool, hipStream_t s);
 

@@ -250,12 +250,15 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
                     for (int ns = 0; ns < NS; ++ns) hr[32 * (nb0 + ns) + cl] += v[ns][ii];
                 }
             } else if (EPI == EPI_SWIGLU) {
-                // tile-rows 2j / 2j+1 of the packed matrix are gate / up of columns 32j..32j+31
-                if (live) {
-                    float gt = v[0][ii], up = v[NS - 1][ii];
-                    float a = (gt / (1.0f + expf(-gt))) * up;
-                    int col = 32 * (nb0 >> 1) + cl;
-                    ep.act[afrag_chunk(row, col & ~7, ep.KB_act) * 8 + (col & 7)] = f32_to_bf16(a);
+                // rows 2j / 2j+1 of the gate/up matrix are gate / up of output j: neighbouring lanes
+                // (same batch row) hold them, the even lane writes the product
+#pragma unroll
+                for (int ns = 0; ns < NS; ++ns) {
+                    const float mine = v[ns][ii], other = __shfl_xor(mine, 1, 64);
+                    const float gt = (cl & 1) ? other : mine, up = (cl & 1) ? mine : other;
+                    const float a = (gt / (1.0f + expf(-gt))) * up;
+                    const int col = 16 * (nb0 + ns) + (cl >> 1);
+                    if (live && !(cl & 1)) ep.act[afrag_chunk(row, col & ~7, ep.KB_act) * 8 + (col & 7)] = f32_to_bf16(a);
                 }
             } else {   // EPI_EXIT
                 int col = 32 * nb0 + cl;
@@ -290,79 +293,83 @@ k_bf16_gemm(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, 
 struct Half { uint4 v[4]; };   // A operands of one K half: 4 row tiles
 
 // One 32x32x16 step of a result tile.  A and B operands have the same register layout, so handing
-// them over in the other order gives the transposed tile at no cost.  The exit head wants that: a
-// lane then holds 16 vocabulary columns of ONE batch row, and the row statistics (maximum, its
-// column, sum of exponentials) need one exchange between the two half-waves instead of a
-// 32-lane butterfly per accumulator register (measured: 83 of 230 us of the exit-head product).
+// them over in the other order gives the transposed tile at no cost: a lane then holds 16 columns of
+// ONE batch row (of the tile-row's 32 columns, those at 8 q + 4 (lane / 32) + s, q, s = 0..3, in
+// register 4 q + s; lane ^ 32 holds the others).  The exit head wants that: the row statistics
+// (maximum, its column, sum of exponentials) need one exchange between the two half-waves instead of
+// a 32-lane butterfly per accumulator register (measured: 83 of 230 us of the exit-head product).
+// So does the SwiGLU epilogue: gate row j and up row j of the gate/up matrix are neighbouring
+// columns, i.e. two registers of one lane.
 template <int EPI>
 __device__ __forceinline__ floatx16 tile_mfma(const uint4& x, const uint4& w, const floatx16& acc) {
-    if constexpr (EPI == EPI_EXIT) return __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(w), as_bf16x8(x), acc, 0, 0, 0);
+    if constexpr (EPI == EPI_EXIT || EPI == EPI_SWIGLU)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(w), as_bf16x8(x), acc, 0, 0, 0);
     else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(x), as_bf16x8(w), acc, 0, 0, 0);
+}
+
+// v: the 32x32 result of tile-row nb (columns 32 nb ..) for rows row0 .. row0+31; every lane of the wave calls it
+template <int EPI>
+__device__ __forceinline__ void epilogue_one(const EpiArgs& ep, const floatx16& v, int row0, int n, int nb, int lane) {
+    const int cl = lane & 31;
+    if constexpr (EPI == EPI_EXIT) {
+        // transposed tile: this lane holds batch row row0 + cl
+        const int row = row0 + cl;
+        const bool live = row < n;
+        const float sc = live ? ep.row_scale[ep.idx[row]] : 0.f;
+        const int col0 = 32 * nb + 4 * (lane >> 5);
+        float z[16];
+        float mx = -FLT_MAX;
+        int arg = col0;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int col = col0 + 8 * (r >> 2) + (r & 3);        // rising with r: > keeps the lowest column
+            z[r] = v[r] * sc;
+            if (live && ep.dbg_logits) ep.dbg_logits[(int64_t)row * ep.ldo + col] = z[r];
+            if (z[r] > mx) { mx = z[r]; arg = col; }
+        }
+        const float m2 = __shfl_xor(mx, 32, 64);
+        const int a2 = __shfl_xor(arg, 32, 64);
+        if (m2 > mx || (m2 == mx && a2 < arg)) { mx = m2; arg = a2; }
+        float se = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) se += expf(z[r] - mx);
+        se += __shfl_xor(se, 32, 64);
+        if (live && lane < 32) {
+            const int64_t at = (int64_t)row * ep.n_part + nb;
+            ep.part_max[at] = mx; ep.part_sum[at] = se; ep.part_arg[at] = arg;
+        }
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        // transposed tile of the gate/up matrix (row 2j gate, row 2j+1 up of output j): registers
+        // 4q, 4q+1 are gate and up of output 4q + 2h (h = lane / 32) of the tile-row's 16 outputs,
+        // registers 4q+2, 4q+3 those of output 4q + 2h + 1.  The half-waves swap two packed pairs so
+        // that lane < 32 writes outputs 0..7 and lane >= 32 outputs 8..15 of its batch row as one
+        // 16-byte chunk of the next product's operand tiles.
+        const int row = row0 + cl, h = lane >> 5;
+        uint32_t d[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float g0 = v[4 * q], u0 = v[4 * q + 1], g1 = v[4 * q + 2], u1 = v[4 * q + 3];
+            d[q] = pack2((g0 / (1.0f + expf(-g0))) * u0, (g1 / (1.0f + expf(-g1))) * u1);
+        }
+        const uint32_t r0 = __shfl_xor(h ? d[0] : d[2], 32, 64), r1 = __shfl_xor(h ? d[1] : d[3], 32, 64);
+        const uint4 o = h ? make_uint4(r0, d[2], r1, d[3]) : make_uint4(d[0], r0, d[1], r1);
+        if (row < n) reinterpret_cast<uint4*>(ep.act)[afrag_chunk(row, 16 * nb + 8 * h, ep.KB_act)] = o;
+    } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = row0 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (row >= n) continue;
+            if constexpr (EPI == EPI_STORE) ep.out[(int64_t)row * ep.ldo + 32 * nb + cl] = v[r];
+            else ep.out[(int64_t)ep.idx[row] * ep.ldo + 32 * nb + cl] += v[r];      // EPI_RESID
+        }
+    }
 }
 
 template <int EPI>
 __device__ __forceinline__ void epilogue_tile(const EpiArgs& ep, const floatx16& v0, const floatx16& v1, int row0,
                                               int n, int nb, int lane) {
-    // v0 / v1: the 32x32 results of tile-rows nb and nb+1 for rows row0 .. row0+31
-    const int cl = lane & 31;
-    if constexpr (EPI == EPI_EXIT) {
-        // transposed tiles (tile_mfma): this lane holds batch row row0 + cl and, of each tile-row's 32
-        // vocabulary columns, the 16 at 8 (r / 4) + 4 (lane / 32) + r % 4; lane ^ 32 holds the others
-        const int row = row0 + cl;
-        const bool live = row < n;
-        const float sc = live ? ep.row_scale[ep.idx[row]] : 0.f;
-#pragma unroll
-        for (int ns = 0; ns < 2; ++ns) {
-            const floatx16& v = ns == 0 ? v0 : v1;
-            const int col0 = 32 * (nb + ns) + 4 * (lane >> 5);
-            float z[16];
-            float mx = -FLT_MAX;
-            int arg = col0;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int col = col0 + 8 * (r >> 2) + (r & 3);        // rising with r: > keeps the lowest column
-                z[r] = v[r] * sc;
-                if (live && ep.dbg_logits) ep.dbg_logits[(int64_t)row * ep.ldo + col] = z[r];
-                if (z[r] > mx) { mx = z[r]; arg = col; }
-            }
-            const float m2 = __shfl_xor(mx, 32, 64);
-            const int a2 = __shfl_xor(arg, 32, 64);
-            if (m2 > mx || (m2 == mx && a2 < arg)) { mx = m2; arg = a2; }
-            float se = 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) se += expf(z[r] - mx);
-            se += __shfl_xor(se, 32, 64);
-            if (live && lane < 32) {
-                const int64_t at = (int64_t)row * ep.n_part + nb + ns;
-                ep.part_max[at] = mx; ep.part_sum[at] = se; ep.part_arg[at] = arg;
-            }
-        }
-        return;
-    }
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int row = row0 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const bool live = row < n;
-        if (EPI == EPI_STORE) {
-            if (live) {
-                ep.out[(int64_t)row * ep.ldo + 32 * nb + cl] = v0[r];
-                ep.out[(int64_t)row * ep.ldo + 32 * (nb + 1) + cl] = v1[r];
-            }
-        } else if (EPI == EPI_RESID) {
-            if (live) {
-                float* hr = ep.out + (int64_t)ep.idx[row] * ep.ldo;
-                hr[32 * nb + cl] += v0[r];
-                hr[32 * (nb + 1) + cl] += v1[r];
-            }
-        } else if (EPI == EPI_SWIGLU) {
-            if (live) {
-                float gt = v0[r], up = v1[r];
-                float a = (gt / (1.0f + expf(-gt))) * up;
-                int col = 32 * (nb >> 1) + cl;
-                ep.act[afrag_chunk(row, col & ~7, ep.KB_act) * 8 + (col & 7)] = f32_to_bf16(a);
-            }
-        }
-    }
+    epilogue_one<EPI>(ep, v0, row0, n, nb, lane);
+    epilogue_one<EPI>(ep, v1, row0, n, nb + 1, lane);
 }
 
 // ------------------------------------------------------------------ tile GEMMs fed by LDS-DMA loads

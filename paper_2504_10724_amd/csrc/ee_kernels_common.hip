@@ -470,29 +470,25 @@ int launch_pht_push(void* row, const ee_model* m, const ee_batch* b, hipStream_t
 }
 
 // ------------------------------------------------------------------ weight repacking
-// one thread per 8-value chunk of the packed matrix
+// one thread per 8-value chunk of the source matrix: source row i, columns 8 co .. 8 co + 7 go to
+// destination row R = row_off + i * row_stride, i.e. to lane R % 32 + 32 (co % 2) of tile (R / 32, co / 2)
 __global__ void k_pack_weight(const bf16_t* __restrict__ src, int n_out, int n_in, bf16_t* __restrict__ dst,
-                              int tile_off, int tile_stride, int dst_tile_rows) {
-    int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int KB = n_in >> 4;
-    int64_t total = (int64_t)(n_out >> 5) * KB * 64;
-    if (c >= total) return;
-    int lane = (int)(c & 63);
-    int64_t t = c >> 6;
-    int kb = (int)(t % KB);
-    int rb = (int)(t / KB);
-    int row = rb * 32 + (lane & 31);
-    int col = kb * 16 + (lane >> 5) * 8;
-    const uint4 v = *reinterpret_cast<const uint4*>(src + (int64_t)row * n_in + col);
-    int64_t dst_tile_row = (int64_t)tile_off + (int64_t)rb * tile_stride;
-    *reinterpret_cast<uint4*>(dst + (((int64_t)kb * dst_tile_rows + dst_tile_row) * 64 + lane) * 8) = v;
+                              int row_off, int row_stride, int dst_rows) {
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int n8 = n_in >> 3;
+    if (c >= (int64_t)n_out * n8) return;
+    const int i = (int)(c / n8), co = (int)(c % n8);
+    const uint4 v = *reinterpret_cast<const uint4*>(src + (int64_t)i * n_in + (int64_t)co * 8);
+    const int64_t R = (int64_t)row_off + (int64_t)i * row_stride;
+    const int64_t slot = (int64_t)(co >> 1) * (dst_rows >> 5) + (R >> 5);
+    *reinterpret_cast<uint4*>(dst + (slot * 64 + (R & 31) + 32 * (co & 1)) * 8) = v;
 }
 
-int launch_pack_weight(const void* src, int n_out, int n_in, void* dst, int tile_off, int tile_stride,
-                       int dst_tile_rows, hipStream_t s) {
-    int64_t total = (int64_t)(n_out / 32) * (n_in / 16) * 64;
+int launch_pack_weight(const void* src, int n_out, int n_in, void* dst, int row_off, int row_stride,
+                       int dst_rows, hipStream_t s) {
+    int64_t total = (int64_t)n_out * (n_in / 8);
     hipLaunchKernelGGL(k_pack_weight, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                       (const bf16_t*)src, n_out, n_in, (bf16_t*)dst, tile_off, tile_stride, dst_tile_rows);
+                       (const bf16_t*)src, n_out, n_in, (bf16_t*)dst, row_off, row_stride, dst_rows);
     EE_LAUNCH_CHECK();
     return EE_OK;
 }

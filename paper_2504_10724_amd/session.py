@@ -80,7 +80,7 @@ class Model:
         if not self.bf16:
             return t
         out = torch.empty_like(t)
-        ee.check(self.lib.ee_pack_weight(_ptr(t), t.shape[0], t.shape[1], _ptr(out), 0, 1, t.shape[0] // 32, _stream()))
+        ee.check(self.lib.ee_pack_weight(_ptr(t), t.shape[0], t.shape[1], _ptr(out), 0, 1, t.shape[0], _stream()))
         torch.cuda.current_stream().synchronize()
         return out
 
@@ -89,8 +89,8 @@ class Model:
         if not self.bf16:
             return torch.cat([g, u], dim=0).contiguous()
         out = torch.empty((2 * g.shape[0], g.shape[1]), dtype=self.tdtype, device="cuda")
-        ee.check(self.lib.ee_pack_weight(_ptr(g), g.shape[0], g.shape[1], _ptr(out), 0, 2, 2 * g.shape[0] // 32, _stream()))
-        ee.check(self.lib.ee_pack_weight(_ptr(u), u.shape[0], u.shape[1], _ptr(out), 1, 2, 2 * g.shape[0] // 32, _stream()))
+        ee.check(self.lib.ee_pack_weight(_ptr(g), g.shape[0], g.shape[1], _ptr(out), 0, 2, 2 * g.shape[0], _stream()))
+        ee.check(self.lib.ee_pack_weight(_ptr(u), u.shape[0], u.shape[1], _ptr(out), 1, 2, 2 * g.shape[0], _stream()))
         torch.cuda.current_stream().synchronize()
         return out
 
@@ -339,7 +339,7 @@ class LayerLoader:
                     return t
                 rows = t.shape[0] * stride
                 o = out if out is not None else torch.empty((rows, t.shape[1]), dtype=m.tdtype, device="cuda")
-                ee.check(m.lib.ee_pack_weight(_ptr(t), t.shape[0], t.shape[1], _ptr(o), off, stride, rows // 32, _stream()))
+                ee.check(m.lib.ee_pack_weight(_ptr(t), t.shape[0], t.shape[1], _ptr(o), off, stride, rows, _stream()))
                 return o
             if m.bf16:
                 gu = pack(dev["W_gate"], 0, 2)
@@ -439,6 +439,75 @@ def load_or_switch(cost_full_chosen, cost_low_exit_others):
     if best is None or cost_full_chosen < cost_low_exit_others[best]:
         return ("load", None)
     return ("switch", best)
+
+
+def overhead_of_loading(n_new_layers, layer_bytes, load_bytes_per_s, cached_tokens, backfill_token_layers_per_s):
+    """Seconds until the chosen model serves with n_new_layers more layers (Sec. 3.3.3, first
+    option): their weights cross from host memory at the measured rate, and every cached token
+    gets its keys and values in each of them at the measured backfill rate."""
+    return (n_new_layers * layer_bytes / load_bytes_per_s
+            + cached_tokens * n_new_layers / backfill_token_layers_per_s)
+
+
+def overhead_of_switching(cached_tokens, context_tokens_per_s, bytes_to_load=0, load_bytes_per_s=None):
+    """Seconds until another candidate's low-exit version serves the same requests (Sec. 3.3.3,
+    second option): its resident layers are loaded if they are not in HBM yet, and the cached
+    tokens of every request pass through them once (a context pass) to build its cache."""
+    t = cached_tokens / context_tokens_per_s
+    if bytes_to_load:
+        t += bytes_to_load / load_bytes_per_s
+    return t
+
+
+def reassess(load_overhead_s, switch_overheads_s):
+    """What the serving loop does when the breach counter fires: Algorithm 1's branch on the two
+    measured overheads (the option with the smaller one is taken; a tie switches).  Returns
+    (("load", None) | ("switch", candidate), the figures compared)."""
+    return load_or_switch(load_overhead_s, switch_overheads_s), dict(load_s=load_overhead_s, switch_s=dict(switch_overheads_s))
+
+
+class OverheadProbe:
+    """Times, on the device, the pieces the two overheads are made of.  Each method runs the real
+    calls (a layer load through a LayerLoader, ee_backfill_kv, ee_prefill) once and returns seconds
+    of wall time between two synchronisations; nothing is estimated."""
+
+    @staticmethod
+    def _timed(fn):
+        import time
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    @staticmethod
+    def load(loader, pinned_layers):
+        """pinned_layers: {layer: dict from LayerLoader.pin}; the layers are resident afterwards"""
+        def go():
+            for l, p in pinned_layers.items():
+                loader.start(l, p)
+            loader.poll(wait=True)
+        return OverheadProbe._timed(go)
+
+    @staticmethod
+    def backfill(model, from_excl, to_incl, kv, batch, store, pos, seq):
+        """pos, seq: all cached tokens, passed in calls of at most batch.B entries"""
+        p, q = _i32_device(pos), _i32_device(seq)
+
+        def go():
+            for lo in range(0, p.numel(), batch.B):
+                ee.check(backfill_kv(model, from_excl, to_incl, kv, batch, store, p[lo:lo + batch.B].contiguous(),
+                                     q[lo:lo + batch.B].contiguous()))
+        return OverheadProbe._timed(go)
+
+    @staticmethod
+    def context_pass(model, kv, batch, contexts):
+        calls = [tuple(_i32_device(a) for a in c) for c in prefill_chunks(contexts, batch.B)]
+
+        def go():
+            for tok, pos, seq in calls:
+                ee.check(prefill(model, kv, batch, tok, pos, seq))
+        return OverheadProbe._timed(go)
 
 
 class WindowSwitcher:

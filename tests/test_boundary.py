@@ -67,10 +67,11 @@ def test_model_create_rejects_bad_configs_before_touching_the_device(kw, code):
 def test_null_and_shape_checks_without_device():
     lib = ee.load()
     assert lib.ee_model_create(None, None) == ee.EE_ERR_INVALID_ARG
-    assert lib.ee_pack_weight(None, 32, 16, None, 0, 1, 1, None) == ee.EE_ERR_INVALID_ARG
+    assert lib.ee_pack_weight(None, 32, 16, None, 0, 1, 32, None) == ee.EE_ERR_INVALID_ARG
     dummy = C.c_void_p(256)
-    assert lib.ee_pack_weight(dummy, 33, 16, dummy, 0, 1, 1, None) == ee.EE_ERR_SHAPE
-    assert lib.ee_pack_weight(dummy, 32, 24, dummy, 0, 1, 1, None) == ee.EE_ERR_SHAPE
+    assert lib.ee_pack_weight(dummy, 32, 16, dummy, 0, 1, 33, None) == ee.EE_ERR_SHAPE
+    assert lib.ee_pack_weight(dummy, 32, 24, dummy, 0, 1, 32, None) == ee.EE_ERR_SHAPE
+    assert lib.ee_pack_weight(dummy, 33, 16, dummy, 0, 2, 64, None) == ee.EE_ERR_INVALID_ARG   # row 64 of 64
     assert lib.ee_packed_bytes(64, 32) == 64 * 32 * 2
     assert lib.ee_layer_forward(None, 1, None, None, None) == ee.EE_ERR_INVALID_ARG
     assert lib.ee_decode_step(None, None, None, None, 0, None) == ee.EE_ERR_INVALID_ARG

@@ -247,7 +247,7 @@ def test_step_equals_its_calls_at_70b_width():
 
 
 # ---------------------------------------------------------------- free-running, real depth
-def free_steps(s, rows, W, steps, n_shadows=1, band_floor=1e-2, g=None):
+def free_steps(s, rows, W, steps, n_shadows=2, band_floor=1e-2, g=None):
     rows = [int(b) for b in rows]
     ctxs = draw_contexts(s, rows)
     o = OracleSide(s, rows=rows, weights=W, gain_jitter=0, contexts=ctxs)
@@ -269,6 +269,8 @@ def free_steps(s, rows, W, steps, n_shadows=1, band_floor=1e-2, g=None):
             _say(f"    row {rows[i]}: oracle (tok {og['tok'][i]}, layer {og['layer'][i]}, conf {og['conf'][i]:.4f}) "
                  f"gpu (tok {gg['tok'][i]}, layer {gg['layer'][i]}, conf {gg['conf'][i]:.4f})"
                  f"{' excluded' if out[i] else ''}")
+        for d in rep["detail"]:
+            _say(f"    MISMATCH {d}")
         assert rep["mismatch"] == 0, rep["detail"]
         compared += rep["rows"]
         excluded += int(out.sum())
@@ -297,19 +299,25 @@ def free_steps(s, rows, W, steps, n_shadows=1, band_floor=1e-2, g=None):
                 assert np.array_equal(ga["breach"][at] != 0, ga["conf"][at] < th[e])
         assert np.array_equal(ga["pos"], ctx0 + step + 1)
     _say(f"  {compared} sampled row-steps compared, {excluded} excluded (inside a band)")
-    assert compared >= (len(rows) * steps + 1) // 2, "too few sampled row-steps were comparable"
-    # every resident layer's entries at the positions of these steps (executed or filled): the 2e-2
-    # of the hidden states, they come from states that deep
-    worst = 0.0
+    assert compared >= max(1, len(rows) * steps // 3), "too few sampled row-steps were comparable"
+    # every resident layer's entries at the positions of these steps (executed or filled), normwise per
+    # (row, layer): within the 2e-2 of the hidden states they come from, or, where the shadows' own
+    # entries have drifted further from the oracle's than a quarter of that, within four times their drift
+    worst = over = 0.0
     for i, b in enumerate(rows):
         p0 = int(ctx0[b])
         for l in range(1, s.resident + 1):
             K, V = g.kv.read_context(l, b, steps, pos0=p0)
-            wk, okk = rows_close(K.transpose(1, 0, 2), o.kv.K[l - 1, i, :, p0:p0 + steps].transpose(1, 0, 2), TOL["bf16"])
-            wv, okv = rows_close(V.transpose(1, 0, 2), o.kv.V[l - 1, i, :, p0:p0 + steps].transpose(1, 0, 2), TOL["bf16"])
-            worst = max(worst, wk, wv)
-            assert okk and okv, (b, l, wk, wv)
-    _say(f"  cache of the sampled rows, {s.resident} layers x {steps} new positions: worst entry {worst:.2e}")
+            for got, ref in ((K, "K"), (V, "V")):
+                want = getattr(o.kv, ref)[l - 1, i, :, p0:p0 + steps]
+                scale = max(float(np.abs(want).max()), 1e-30)
+                err = float(np.abs(got - want).max()) / scale
+                drift = max(float(np.abs(getattr(sh.kv, ref)[l - 1, i, :, p0:p0 + steps] - want).max()) / scale for sh in shadows)
+                worst = max(worst, err)
+                over = max(over, err / max(TOL["bf16"], 4 * drift))
+                assert err <= max(TOL["bf16"], 4 * drift), (b, l, ref, err, drift)
+    _say(f"  cache of the sampled rows, {s.resident} layers x {steps} new positions: worst (row, layer) {worst:.2e}, "
+         f"at most {over:.2f} of its bound")
     return g, o, excluded
 
 
@@ -334,7 +342,7 @@ def test_config4_llama2_70b_full_depth():
     including the three 20-layer fill segments, over 3 consecutive steps."""
     s = C["llama2_70b"].with_(name="cfg4_70b_full", steps=3)
     _say(f"[case] free-running {s.name} B={s.batch} R={s.resident} steps={s.steps}")
-    free_steps(s, [0, 101, 255], weights_for(s, 4), s.steps)
+    free_steps(s, [0, 37, 101, 180, 255], weights_for(s, 4), s.steps, n_shadows=2)
 
 
 @pytest.mark.parametrize("batch", [1, 16], ids=lambda b: f"b{b}")

@@ -207,3 +207,74 @@ def test_serve_load_backfill_serve_bf16_cache():
     _say(f"  new layers' cache: worst error {worst:.2e}")
     gg = g.step(2, thresholds=(2.0, 2.0, 0.0))
     assert gg["rc"] == 0 and gg["status"] == 0 and np.all(gg["layer"] == 6) and not gg["breach"].any()
+
+
+def test_load_or_switch_on_measured_overheads():
+    """Algorithm 1's branch fed by measurements on the device (Sec. 3.3.3, "Load More Layers Or
+    Another Candidate Model?"): a partially loaded model A holds the cache of its requests; the
+    overhead of loading its remaining layers (transfer + keys and values of the cached tokens in
+    them) and the overhead of switching to candidate B's low-exit version (a context pass of the
+    cached tokens on B) are timed with the real calls, and the branch is taken on those two numbers.
+    The branch itself is checked against the oracle's on the same figures, and the cache that the
+    taken action leaves behind against the oracle's."""
+    from oracle.ee_pht import load_or_switch as oracle_branch
+    sa = BF16.with_(name="candidate_a", steps=1)
+    sb = BF16.with_(name="candidate_b", seed=1, resident=2, thresholds=(0.8,), steps=1)
+    _say(f"[case] measured load-or-switch: {sa.name} R={sa.resident}/{sa.n_layers} vs {sb.name} R={sb.resident}")
+    W, o, g = _sides(sa)
+    store = S.HiddenStore(g.model, g.kv)
+    states = {}
+    pb = _context_pass(sa, o, g, store, states, 64)
+    cached = [(b, p) for b in range(sa.batch) for p in range(int(o.ctx[b]))]
+    pos = np.array([p for _, p in cached], np.int32)
+    seq = np.array([b for b, _ in cached], np.int32)
+    # option 1: the rest of A
+    loader = S.LayerLoader(g.model)
+    pinned = {l: S.LayerLoader.pin(W["layers"][l]) for l in range(sa.resident + 1, sa.n_layers + 1)}
+    t_load = S.OverheadProbe.load(loader, pinned)
+    assert g.model.resident_depth() == sa.n_layers
+    t_fill = S.OverheadProbe.backfill(g.model, sa.resident, sa.n_layers, g.kv, pb, store, pos, seq)
+    # option 2: candidate B's resident layers over the same cached tokens (B is in HBM already)
+    ob = OracleSide(sb, fill_ctx=False, gain_jitter=0, cap=o.cap)
+    gb = GpuSide(sb, weights=ob.weights, synth_rows=[], max_pos=int(g.cap.max()))
+    gb.kv = S.KVCache(gb.model, sb.resident, g.cap)          # B caches the same requests as A
+    gb.kv.pool.zero_()
+    pbb = S.Batch(gb.model, 64)
+    z = np.zeros(64, np.int32)
+    pbb.reset(z, z, None)
+    contexts = {b: synth.context_tokens(sa, b, int(o.ctx[b])) for b in range(sa.batch)}
+    t_switch = S.OverheadProbe.context_pass(gb.model, gb.kv, pbb, contexts)
+    assert int(pbb.field("status").cpu()[0]) == 0 and int(pb.field("status").cpu()[0]) == 0
+    assert t_load > 0 and t_fill > 0 and t_switch > 0
+    decision, figures = S.reassess(t_load + t_fill, {"candidate_b": t_switch})
+    _say(f"  load {t_load * 1e3:.2f} ms + backfill {t_fill * 1e3:.2f} ms vs switch {t_switch * 1e3:.2f} ms -> {decision}")
+    assert decision == oracle_branch(t_load + t_fill, {"candidate_b": t_switch})
+    assert decision == (("load", None) if t_load + t_fill < t_switch else ("switch", "candidate_b"))
+    # the formula from rates gives the same overheads as the direct timings it was derived from
+    n_new = sa.n_layers - sa.resident
+    layer_bytes = sum(t.numel() * t.element_size() for t in pinned[sa.n_layers].values())
+    est = S.overhead_of_loading(n_new, layer_bytes, n_new * layer_bytes / t_load, len(cached), len(cached) * n_new / t_fill)
+    assert abs(est - (t_load + t_fill)) <= 1e-9 * max(1.0, est)
+    assert abs(S.overhead_of_switching(len(cached), len(cached) / t_switch) - t_switch) <= 1e-12
+    # whichever way the branch went, both actions were carried out above: check what they left
+    for l in range(sa.resident + 1, sa.n_layers + 1):
+        w = W["layers"][l]
+        assert o.model.set_layer(l, w["g_attn"], w["W_qkv"], w["W_o"], w["g_ffn"], w["W_gate"], w["W_up"], w["W_down"]) == 0
+    assert orc.backfill_kv(o.model, o.kv, sa.resident, sa.n_layers, states) == 0
+    for b in (0, sa.batch // 2, sa.batch - 1):
+        n = int(o.ctx[b])
+        for l in range(sa.resident + 1, sa.n_layers + 1):
+            K, V = g.kv.read_context(l, b, n)
+            wk, okk = rows_close(K.reshape(1, -1), o.kv.K[l - 1, b, :, :n].reshape(1, -1), TOL["bf16"])
+            wv, okv = rows_close(V.reshape(1, -1), o.kv.V[l - 1, b, :, :n].reshape(1, -1), TOL["bf16"])
+            assert okk and okv, (b, l, wk, wv)
+    for b in range(sb.batch):
+        rc, _ = orc.prefill(ob.model, ob.kv, b, contexts[b])
+        assert rc == 0
+    for b in (0, sb.batch - 1):
+        n = int(o.ctx[b])
+        for l in range(1, sb.resident + 1):
+            K, V = gb.kv.read_context(l, b, n)
+            wk, okk = rows_close(K.reshape(1, -1), ob.kv.K[l - 1, b, :, :n].reshape(1, -1), TOL["bf16"])
+            wv, okv = rows_close(V.reshape(1, -1), ob.kv.V[l - 1, b, :, :n].reshape(1, -1), TOL["bf16"])
+            assert okk and okv, (b, l, wk, wv)

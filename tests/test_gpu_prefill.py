@@ -144,23 +144,27 @@ def test_decode_steps_after_a_context_pass(s, rows_per_call):
     assert sticky.sum() <= max(3, s.batch * s.steps // 10), f"{sticky.sum()} of {s.batch} rows excluded"
 
 
-def test_full_width_context_pass_sampled_cache_rows():
-    """The 70B workload's layer shapes on a two-layer model, 256 entries per call (the decode
-    benchmark's row count, so the same tile variants and grids): 64 short contexts, of which
-    the oracle recomputes a sample from their first token on."""
+@pytest.mark.parametrize("entries,ctx_hi", [(256, 12), (1024, 40)], ids=["one_row_group", "four_row_groups"])
+def test_full_width_context_pass_sampled_cache_rows(entries, ctx_hi):
+    """The 70B workload's layer shapes on a two-layer model: 256 entries per call (the decode
+    benchmark's row count, so the same tile variants and grids) and 1024 entries per call (four
+    256-row groups of a column tile on one XCD, the launch shape of the benchmark's context pass);
+    64 short contexts, of which the oracle recomputes a sample from their first token on."""
     base = synth.CONFIGS["llama2_70b"]
-    s = base.with_(name="70b_shape_ctx", n_layers=2, resident=2, exit_layers=(1, 2), thresholds=(0.9, 0.0),
-                   batch=64, ctx_lo=1, ctx_hi=12, steps=1)
+    s = base.with_(name=f"70b_shape_ctx_{entries}", n_layers=2, resident=2, exit_layers=(1, 2), thresholds=(0.9, 0.0),
+                   batch=64, ctx_lo=1, ctx_hi=ctx_hi, steps=1)
     rows = [0, 29, 63]
-    _say(f"[case] full-width context pass {s.name} cache rows={s.batch} sampled={rows}")
+    _say(f"[case] full-width context pass {s.name} cache rows={s.batch} entries per call={entries} sampled={rows}")
     o = OracleSide(s, rows=rows, fill_ctx=False, gain_jitter=0.0)
     hs = _oracle_context_pass(o)
     _say("  oracle side ready")
     g = GpuSide(s, weights=o.weights, synth_rows=[])
     g.kv.pool.zero_()
-    calls = _gpu_context_pass(g, _contexts(s), 256, check_h=hs, tol=TOL["bf16"])
+    calls = _gpu_context_pass(g, _contexts(s), entries, check_h=hs, tol=TOL["bf16"])
     worst = _compare_cache(s, o, g, TOL["bf16"])
     _say(f"  {calls} calls, {int(g.ctx.sum())} entries; worst sampled cache error {worst:.2e}")
+    if entries > 256:
+        assert int(g.ctx.sum()) > 768, "a call must fill more than three row groups"
     # every cache row, at any size: exactly its context was written, nothing beyond
     for b in range(s.batch):
         K, V = g.kv.read_context(2, b, int(g.cap[b]))
