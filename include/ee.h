@@ -242,6 +242,24 @@ int ee_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, void*
 int ee_exit_head(const ee_model* m, int exit_idx, float threshold, int force_exit,
                  ee_batch* b, float* dev_dbg_logits, void* stream);
 
+/* ee_exit_head for callers that cannot allocate device memory and bring no workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same
+ * results (bit for bit) and same outputs in the batch state as ee_exit_head without the debug
+ * pointer, but what that call keeps in the batch's workspace (normalised operand rows, per-tile
+ * softmax statistics, for EE_F32 also the logits) goes to a device array of EE_STATIC_SCRATCH_BYTES
+ * that the library holds on every GPU it runs on until the process ends.  The call allocates
+ * nothing and frees nothing (its first call on a device looks the array's address up); the
+ * batch's own workspace is not touched.  Nothing in the array has to start at zero: every value
+ * read was written by this call.  All calls on one GPU share the array: calls that overlap in
+ * time on one GPU (different streams or threads) race; calls on one stream are safe.  Kernel
+ * timing (ee_timing_enable) creates events and must be off for a caller that may not allocate.
+ * Errors as ee_exit_head; EE_ERR_CAPACITY if the batch and model need more than
+ * EE_STATIC_SCRATCH_BYTES (about Mpad * (2 d + 12 V / 32) bytes for EE_BF16 with Mpad = the
+ * batch's rows rounded up to 32: 7.2 MiB for 256 rows at d = 8192, V = 32000). */
+#define EE_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+int ee_exit_head_static(const ee_model* m, int exit_idx, float threshold, int force_exit, ee_batch* b,
+                        void* stream);
+
 /* The step that lets rows of one batch leave at different exits (Sec. 1: batching early-exit
  * requests needs the tokens of a batch kept in step; Sec. 5.4 removes the problem by making every
  * token of a batch stop at the same layer, here the batch is re-formed on the device instead).

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libee.so")
-SOURCES = ["ee_api.cpp", "ee_kernels_common.hip", "ee_kernels_f32.hip", "ee_kernels_bf16.hip"]
+SOURCES = ["ee_api.cpp", "ee_kernels_common.hip", "ee_kernels_f32.hip", "ee_kernels_bf16.hip", "ee_static.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-Wall", "-Wno-unused-function"]

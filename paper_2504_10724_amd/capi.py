@@ -67,6 +67,7 @@ _SIGS = {
     "ee_batch_begin_step": (_i, [_vp, _vp, _vp]),
     "ee_layer_forward": (_i, [_vp, _i, _vp, _vp, _vp]),
     "ee_exit_head": (_i, [_vp, _i, _f, _i, _vp, _vp, _vp]),
+    "ee_exit_head_static": (_i, [_vp, _i, _f, _i, _vp, _vp]),
     "ee_compact_active": (_i, [_vp, _i, _i, _vp]),
     "ee_fill_skipped_kv": (_i, [_vp, _i, _i, _vp, _vp, _vp]),
     "ee_decode_step": (_i, [_vp, _vp, _vp, C.POINTER(C.c_float), _i, _vp]),

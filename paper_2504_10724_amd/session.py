@@ -230,6 +230,11 @@ def exit_head(model, exit_idx, threshold, force_exit, batch, dbg_logits=None):
     return model.lib.ee_exit_head(model.h, exit_idx, threshold, int(force_exit), batch.h, _ptr(dbg_logits), _stream())
 
 
+def exit_head_static(model, exit_idx, threshold, force_exit, batch):
+    """ee_exit_head on the library's own scratch array: no workspace, no allocation"""
+    return model.lib.ee_exit_head_static(model.h, exit_idx, threshold, int(force_exit), batch.h, _stream())
+
+
 def compact_active(batch, exit_idx, exit_layer):
     return batch.model.lib.ee_compact_active(batch.h, exit_idx, exit_layer, _stream())
 
