@@ -469,4 +469,58 @@ int orc_prefill(const orc_model* m, orc_kv* kv, int b, const int32_t* tok, int n
     return ORC_OK;
 }
 
+int orc_accept_drafts(const int32_t* drafts, const int32_t* verified, int k, int32_t* emitted) {
+    int a = 0;
+    while (a < k && drafts[a] == verified[a]) ++a;
+    int n = a + 1 < k ? a + 1 : k;
+    for (int j = 0; j < n; ++j) emitted[j] = verified[j];
+    return n;
+}
+
+int orc_selfspec_round(const orc_model* m, orc_kv* kv, int b, int32_t tok_in, int32_t* pos, int draft_exit,
+                       int k, int32_t* drafts, int32_t* verified, int32_t* n_emitted, int32_t* emitted) {
+    if (!m || !kv || !pos || !drafts || !verified || !n_emitted || !emitted) return ORC_ERR_ARG;
+    if (b < 0 || b >= kv->B || k < 1 || m->rope_theta == 0.0) return ORC_ERR_ARG;
+    const orc_config& c = m->cfg;
+    int R = orc_model_resident_depth(m);
+    if (R < 1 || draft_exit < 0 || draft_exit >= c.n_exits) return ORC_ERR_ARG;
+    int Le = c.exit_layers[draft_exit];
+    int head = -1;
+    for (int e = 0; e < c.n_exits; ++e)
+        if (c.exit_layers[e] == R) head = e;
+    if (head < 0 || Le >= R) return ORC_ERR_NOT_RESIDENT;
+    int p0 = *pos, d = c.d_model;
+    if ((int64_t)p0 + k > kv->cap || (int64_t)p0 + k > m->max_pos) return ORC_ERR_ARG;
+    std::vector<float> S((size_t)k * d);      // state of each drafted position after layer L_e
+    float conf;
+    // 1. draft
+    int32_t tok = tok_in;
+    for (int j = 0; j < k; ++j) {
+        float* h = &S[(size_t)j * d];
+        int rc = orc_embed(m, tok, h);
+        if (rc != ORC_OK) return rc;
+        for (int l = 1; l <= Le; ++l) {
+            rc = layer_forward_row(m, l, kv, b, p0 + j, h);
+            if (rc != ORC_OK) return rc;
+        }
+        rc = orc_exit_head(m, draft_exit, h, 1.0f, nullptr, &conf, &drafts[j]);
+        if (rc != ORC_OK) return rc;
+        tok = drafts[j];
+    }
+    // 2. verify
+    for (int l = Le + 1; l <= R; ++l)
+        for (int j = 0; j < k; ++j) {
+            int rc = layer_forward_row(m, l, kv, b, p0 + j, &S[(size_t)j * d]);
+            if (rc != ORC_OK) return rc;
+        }
+    for (int j = 0; j < k; ++j) {
+        int rc = orc_exit_head(m, head, &S[(size_t)j * d], 1.0f, nullptr, &conf, &verified[j]);
+        if (rc != ORC_OK) return rc;
+    }
+    // 3. accept
+    *n_emitted = orc_accept_drafts(drafts, verified, k, emitted);
+    *pos = p0 + *n_emitted;
+    return ORC_OK;
+}
+
 }  // extern "C"

@@ -145,6 +145,30 @@ int orc_vanilla_step(const orc_model* m, orc_kv* kv, const int32_t* tok_in, int3
 int orc_prefill(const orc_model* m, orc_kv* kv, int b, const int32_t* tok, int n, int32_t pos0,
                 float* h_out);
 
+/* Self-speculative decoding with one exit head as the drafter (Sec. 6: an early-exit model with an
+ * intermediate exit below its loaded depth can also be served by exit-layer speculative decoding;
+ * the scheme is the published draft-then-verify one, with the model's own first layers as the draft
+ * model).  Acceptance rule alone: drafts d[0..k) against the full-depth tokens v[0..k) for the same
+ * positions; with a = number of leading positions where they agree, the round emits
+ * n = min(a + 1, k) tokens, namely v[0..n) (the accepted drafts, then the first correction).  Returns n. */
+int orc_accept_drafts(const int32_t* drafts, const int32_t* verified, int k, int32_t* emitted);
+
+/* One round for row b, written out step by step:
+ *   1. draft: for j = 0..k-1 the input token (tok_in for j = 0, else draft j-1) at position pos+j runs
+ *      layers 1..L_e (L_e = layer of exit `draft_exit`), which appends their K, V; its state after
+ *      layer L_e is kept; exit head `draft_exit` gives draft j (greedy, lowest index on ties);
+ *   2. verify: the k kept states run layers L_e+1..R, layer by layer and within a layer in rising
+ *      position order (causal), appending those layers' K, V; the exit head at R gives verified[j];
+ *   3. accept: orc_accept_drafts.  *pos advances by the number of emitted tokens; the input of the
+ *      next round is the last emitted token.
+ * What the scheme reaches is a plain definition: the emitted tokens and every cache entry below the
+ * new position are those of full-depth greedy decoding (orc_vanilla_step), bit for bit here, whatever
+ * k and draft_exit are; entries at positions from the new position on are leftovers of rejected drafts
+ * and are overwritten when those positions are decoded.
+ * drafts, verified, emitted: [k].  R must carry an exit head; L_e < R. */
+int orc_selfspec_round(const orc_model* m, orc_kv* kv, int b, int32_t tok_in, int32_t* pos, int draft_exit,
+                       int k, int32_t* drafts, int32_t* verified, int32_t* n_emitted, int32_t* emitted);
+
 #ifdef __cplusplus
 }
 #endif

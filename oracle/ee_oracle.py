@@ -274,3 +274,22 @@ def backfill_kv(model, kv, from_excl, to_incl, exit_states):
         if rc != ORC_OK:
             return rc
     return ORC_OK
+
+
+def accept_drafts(drafts, verified):
+    d = np.ascontiguousarray(drafts, dtype=np.int32)
+    v = np.ascontiguousarray(verified, dtype=np.int32)
+    out = np.zeros(d.size, np.int32)
+    n = lib().orc_accept_drafts(_p(d), _p(v), d.size, _p(out))
+    return out[:n].copy()
+
+
+def selfspec_round(model, kv, b, tok_in, pos, draft_exit, k):
+    """One self-speculative round of row b (Sec. 6; see ee_oracle.h).  Returns a dict with the
+    drafts, the full-depth tokens of the same positions, the emitted tokens and the new position."""
+    drafts, verified, emitted = np.zeros(k, np.int32), np.zeros(k, np.int32), np.zeros(k, np.int32)
+    n, p = C.c_int32(), C.c_int32(int(pos))
+    s = kv.struct()
+    rc = lib().orc_selfspec_round(model.h, C.byref(s), int(b), int(tok_in), C.byref(p), int(draft_exit), int(k),
+                                  _p(drafts), _p(verified), C.byref(n), _p(emitted))
+    return dict(rc=rc, drafts=drafts, verified=verified, emitted=emitted[:n.value].copy(), pos=p.value)
