@@ -397,6 +397,50 @@ def run_context_pass(s, model, torch, S, ee, synth, C, entries_per_call, n_ctx=8
     return res
 
 
+def run_self_speculative(s, model, torch, S, ee, synth, batch=64, k=4, rounds=4):
+    """Exit-layer self-speculative decoding (ee_draft_step, ee_verify_drafts) at the workload's shape,
+    outside the timed decode region: the first exit drafts k tokens per row, the remaining layers verify
+    all k positions of all rows in one pass.  Random-init heads never agree, so every round emits one
+    token per row; the round time against the time of a full-depth step gives the number of tokens a
+    round must emit on average to break even."""
+    lib = model.lib
+    sb = s.with_(batch=batch)
+    ctx = synth.context_lengths(sb)
+    cap = synth.capacity_for(ctx, (rounds + 2) * k + rounds + 2, 32)
+    kv = S.KVCache(model, s.resident, cap)
+    fill_cache(kv, sb, torch)
+    b = S.Batch(model, batch)
+    b.reset(synth.first_tokens(sb), ctx.astype(np.int32), None)
+    sp = S.Speculator(model, kv, b, 0, k)
+    never = [2.0] * len(s.resident_exits)            # no row leaves before the last resident layer
+
+    def timed(fn, n):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    def full_step():
+        rc = S.decode_step(model, kv, b, never)
+        if rc != 0:
+            raise ee.EEError(rc, lib.ee_last_error().decode())
+    t_full = timed(full_step, rounds)
+    b.reset(synth.first_tokens(sb), ctx.astype(np.int32), None)
+    t_round = timed(sp.round, rounds)
+    emitted = float(sp.n_emit.float().mean())
+    assert int(b.field("status").cpu()[0]) == 0 and int(sp.entries.field("status").cpu()[0]) == 0
+    res = dict(batch=batch, drafts_per_round=k, draft_layers=s.resident_exits[0], verify_layers=s.resident - s.resident_exits[0],
+               round_ms=t_round * 1e3, full_depth_step_ms=t_full * 1e3, tokens_per_round_measured=emitted,
+               tokens_per_round_to_break_even=t_round / t_full,
+               tokens_per_s_if_all_accepted=batch * k / t_round, tokens_per_s_full_depth=batch / t_full)
+    del sp, b, kv
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -409,6 +453,7 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the smaller batch sizes of the sweep")
     ap.add_argument("--no-layer-load", action="store_true", help="skip the layer-load and backfill measurement")
     ap.add_argument("--no-context-pass", action="store_true", help="skip the context-pass (ee_prefill) measurement")
+    ap.add_argument("--no-speculative", action="store_true", help="skip the self-speculative decoding measurement")
     ap.add_argument("--context-pass-only", type=int, nargs="*", default=None, metavar="ENTRIES",
                     help="only time the context pass (ee_prefill) with these numbers of entries per call")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -471,6 +516,8 @@ def main():
                                             "layer_gemms", "exit_head_plus_compaction_us_per_step", "breach_counter", "pht_row", "kernels_ms")},
                batch_sweep=sweep)
     out["detail"]["context_pass"] = context_pass
+    out["detail"]["self_speculative"] = (None if args.no_speculative or len(s.resident_exits) < 2 else
+                                         run_self_speculative(s, model, torch, S, ee, synth))
     out["detail"]["layer_load"] = head.get("layer_load")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(s, head["counts"])

@@ -15,7 +15,8 @@
  * SwiGLU).
  *
  * Around the step, in the order of this file: the context pass that builds the
- * cache a step reads (ee_prefill); loading further layers while steps run and
+ * cache a step reads (ee_prefill); exit-layer self-speculative decoding on the
+ * same kernels (ee_draft_step, ee_verify_drafts); loading further layers while steps run and
  * giving the cached tokens keys and values in them (ee_model_set_layer_on,
  * ee_hstore_*, ee_backfill_kv); and the two device-side records the serving
  * loop reads instead of per-row outputs, the confidence-breach counter
@@ -312,6 +313,46 @@ int ee_decode_step(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_
  * EE_ERR_LAYER_NOT_RESIDENT / EE_ERR_INVALID_ARG as for ee_decode_step. */
 int ee_prefill(const ee_model* m, ee_kv* kv, ee_batch* b, const int32_t* dev_tok,
                const int32_t* dev_pos, const int32_t* dev_seq, int n, void* stream);
+
+/* ------------------------------------------------------------------ exit-layer self-speculative decoding
+ *
+ * An early-exit model with an exit below its loaded depth can also be served by speculative decoding
+ * with that exit as the drafter (Sec. 6, comparison with speculative decoding): the first layers and
+ * their exit head draft k tokens one by one, the remaining layers check all k positions in one pass,
+ * and the longest agreeing prefix is kept.  The emitted tokens are those of full-depth greedy decoding
+ * (exit head at the last resident layer R); the gain is that the deep layers run once per round over
+ * k positions instead of once per token.  One round on a batch of B rows:
+ *     k times:  ee_draft_step, then ee_hstore_put_step (keeps each row's state after the draft layers)
+ *     once:     ee_verify_drafts
+ */
+
+/* One draft token for every row: embeds tok_in, runs layers 1 .. exit_layers[draft_exit] on all rows
+ * (their K, V are appended), takes the greedy token of that exit head (lowest index on ties), then
+ * pos += 1 and tok_in = the draft.  Deeper layers are not touched and get no K, V here.  out_tok,
+ * out_conf and out_layer hold the draft, its probability and the draft layer; h holds each row's state
+ * after the draft layers; the batch's exit counters count the drafts like exits and mean nothing
+ * during a round.  dev_draft_out (nullable): B int32, receives the drafts.
+ * Errors: as ee_decode_step; EE_ERR_INVALID_ARG if the draft exit is not below the deepest resident
+ * layer; EE_ERR_EXIT_NOT_RESIDENT if the draft head or the head of the deepest resident layer is not set. */
+int ee_draft_step(const ee_model* m, ee_kv* kv, ee_batch* b, int draft_exit, int32_t* dev_draft_out, void* stream);
+
+/* Verification of k drafts per row.  b: the batch that made k ee_draft_step calls since its last emitted
+ * token (its pos is k ahead).  vb: a second batch of the same model with at least B * k rows, used as
+ * the list of entries (its state and workspace are overwritten); entry r * k + j is cache row r at
+ * position pos[r] - k + j with the state kept in dev_store (see ee_hstore_bytes) as its residual stream.
+ * All entries pass layers exit_layers[draft_exit] + 1 .. R in one pass (causal within a row, K and V of
+ * those layers appended), the exit head at R gives each entry's full-depth token v_j, and with a = the
+ * number of leading positions where draft and full-depth token agree the row emits n = min(a + 1, k)
+ * tokens v_0 .. v_{n-1}.  Outputs: dev_n_emit [B] = n; dev_emit [B][k] = the emitted tokens, -1 beyond n;
+ * b's pos = position before the drafts + n, tok_in = out_tok = v_{n-1}.  Cache entries from the new
+ * position on are leftovers of rejected drafts and are overwritten when those positions are decoded.
+ * dev_drafts: [k][B] int32, draft j of row r at j * B + r (what ee_draft_step wrote).
+ * Refusals (a position outside its cache row) set status bit 1 of vb.  Enqueue-only.
+ * Errors: as ee_draft_step; EE_ERR_CAPACITY if vb has fewer than B * k rows; EE_ERR_INVALID_ARG on null
+ * arrays, k < 1 or vb == b. */
+int ee_verify_drafts(const ee_model* m, ee_kv* kv, ee_batch* b, ee_batch* vb, int draft_exit, int k,
+                     const float* dev_store, const int32_t* dev_drafts, int32_t* dev_n_emit, int32_t* dev_emit,
+                     void* stream);
 
 /* ------------------------------------------------------------------ loading more layers while serving
  *

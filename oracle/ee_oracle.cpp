@@ -477,8 +477,20 @@ int orc_accept_drafts(const int32_t* drafts, const int32_t* verified, int k, int
     return n;
 }
 
+// (largest - second largest) / largest magnitude of z[0..V)
+static float relative_margin(const float* z, int V) {
+    float top = -INFINITY, second = -INFINITY, mag = 0.f;
+    for (int j = 0; j < V; ++j) {
+        if (z[j] > top) { second = top; top = z[j]; }
+        else if (z[j] > second) second = z[j];
+        if (std::fabs(z[j]) > mag) mag = std::fabs(z[j]);
+    }
+    return mag > 0.f ? (top - second) / mag : 0.f;
+}
+
 int orc_selfspec_round(const orc_model* m, orc_kv* kv, int b, int32_t tok_in, int32_t* pos, int draft_exit,
-                       int k, int32_t* drafts, int32_t* verified, int32_t* n_emitted, int32_t* emitted) {
+                       int k, int32_t* drafts, int32_t* verified, int32_t* n_emitted, int32_t* emitted,
+                       float* draft_margin, float* verify_margin) {
     if (!m || !kv || !pos || !drafts || !verified || !n_emitted || !emitted) return ORC_ERR_ARG;
     if (b < 0 || b >= kv->B || k < 1 || m->rope_theta == 0.0) return ORC_ERR_ARG;
     const orc_config& c = m->cfg;
@@ -492,6 +504,7 @@ int orc_selfspec_round(const orc_model* m, orc_kv* kv, int b, int32_t tok_in, in
     int p0 = *pos, d = c.d_model;
     if ((int64_t)p0 + k > kv->cap || (int64_t)p0 + k > m->max_pos) return ORC_ERR_ARG;
     std::vector<float> S((size_t)k * d);      // state of each drafted position after layer L_e
+    std::vector<float> z(c.vocab);
     float conf;
     // 1. draft
     int32_t tok = tok_in;
@@ -503,8 +516,9 @@ int orc_selfspec_round(const orc_model* m, orc_kv* kv, int b, int32_t tok_in, in
             rc = layer_forward_row(m, l, kv, b, p0 + j, h);
             if (rc != ORC_OK) return rc;
         }
-        rc = orc_exit_head(m, draft_exit, h, 1.0f, nullptr, &conf, &drafts[j]);
+        rc = orc_exit_head(m, draft_exit, h, 1.0f, z.data(), &conf, &drafts[j]);
         if (rc != ORC_OK) return rc;
+        if (draft_margin) draft_margin[j] = relative_margin(z.data(), c.vocab);
         tok = drafts[j];
     }
     // 2. verify
@@ -514,8 +528,9 @@ int orc_selfspec_round(const orc_model* m, orc_kv* kv, int b, int32_t tok_in, in
             if (rc != ORC_OK) return rc;
         }
     for (int j = 0; j < k; ++j) {
-        int rc = orc_exit_head(m, head, &S[(size_t)j * d], 1.0f, nullptr, &conf, &verified[j]);
+        int rc = orc_exit_head(m, head, &S[(size_t)j * d], 1.0f, z.data(), &conf, &verified[j]);
         if (rc != ORC_OK) return rc;
+        if (verify_margin) verify_margin[j] = relative_margin(z.data(), c.vocab);
     }
     // 3. accept
     *n_emitted = orc_accept_drafts(drafts, verified, k, emitted);

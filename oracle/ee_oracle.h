@@ -165,9 +165,13 @@ int orc_accept_drafts(const int32_t* drafts, const int32_t* verified, int k, int
  * new position are those of full-depth greedy decoding (orc_vanilla_step), bit for bit here, whatever
  * k and draft_exit are; entries at positions from the new position on are leftovers of rejected drafts
  * and are overwritten when those positions are decoded.
- * drafts, verified, emitted: [k].  R must carry an exit head; L_e < R. */
+ * drafts, verified, emitted: [k].  R must carry an exit head; L_e < R.
+ * draft_margin, verify_margin (nullable, [k]; a diagnostic for comparisons, not part of the method):
+ * for each head evaluation (largest logit - second largest logit) / largest |logit|, i.e. how far the
+ * greedy choice is from a tie relative to the size of the logits. */
 int orc_selfspec_round(const orc_model* m, orc_kv* kv, int b, int32_t tok_in, int32_t* pos, int draft_exit,
-                       int k, int32_t* drafts, int32_t* verified, int32_t* n_emitted, int32_t* emitted);
+                       int k, int32_t* drafts, int32_t* verified, int32_t* n_emitted, int32_t* emitted,
+                       float* draft_margin, float* verify_margin);
 
 #ifdef __cplusplus
 }

@@ -288,8 +288,10 @@ def selfspec_round(model, kv, b, tok_in, pos, draft_exit, k):
     """One self-speculative round of row b (Sec. 6; see ee_oracle.h).  Returns a dict with the
     drafts, the full-depth tokens of the same positions, the emitted tokens and the new position."""
     drafts, verified, emitted = np.zeros(k, np.int32), np.zeros(k, np.int32), np.zeros(k, np.int32)
+    dm, vm = np.zeros(k, np.float32), np.zeros(k, np.float32)
     n, p = C.c_int32(), C.c_int32(int(pos))
     s = kv.struct()
     rc = lib().orc_selfspec_round(model.h, C.byref(s), int(b), int(tok_in), C.byref(p), int(draft_exit), int(k),
-                                  _p(drafts), _p(verified), C.byref(n), _p(emitted))
-    return dict(rc=rc, drafts=drafts, verified=verified, emitted=emitted[:n.value].copy(), pos=p.value)
+                                  _p(drafts), _p(verified), C.byref(n), _p(emitted), _p(dm), _p(vm))
+    return dict(rc=rc, drafts=drafts, verified=verified, emitted=emitted[:n.value].copy(), pos=p.value,
+                draft_margin=dm, verify_margin=vm)

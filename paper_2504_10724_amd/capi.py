@@ -72,6 +72,8 @@ _SIGS = {
     "ee_fill_skipped_kv": (_i, [_vp, _i, _i, _vp, _vp, _vp]),
     "ee_decode_step": (_i, [_vp, _vp, _vp, C.POINTER(C.c_float), _i, _vp]),
     "ee_prefill": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _vp]),
+    "ee_draft_step": (_i, [_vp, _vp, _vp, _i, _vp, _vp]),
+    "ee_verify_drafts": (_i, [_vp, _vp, _vp, _vp, _i, _i, _vp, _vp, _vp, _vp, _vp]),
     "ee_model_set_layer_on": (_i, [_vp, _i, C.POINTER(ee_layer_weights), _vp]),
     "ee_hstore_bytes": (_sz, [_vp, _vp]),
     "ee_hstore_put_step": (_i, [_vp, _vp, _vp, _vp, _vp]),

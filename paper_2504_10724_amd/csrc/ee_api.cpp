@@ -593,6 +593,95 @@ int ee_backfill_kv(const ee_model* m, int from_layer_excl, int to_layer_incl, ee
     return rc;
 }
 
+// ------------------------------------------------------------------ self-speculative decoding
+// layers first .. last on the batch's active rows, the way the decode step chains them: the kernel that
+// finishes a layer leaves the normalised operand of what comes next (next layer, or the head `then_gain`)
+static int run_layers(const ee_model* m, int first, int last, ee_kv* kv, ee_batch* b, const float* then_gain,
+                      hipStream_t s, bool* x_ready_out) {
+    int rc = EE_OK;
+    bool x_ready = false;
+    for (int l = first; l <= last && rc == EE_OK; ++l) {
+        if (m->cfg.dtype == EE_BF16) {
+            const float* tail_gain = l < last ? (const float*)m->layers[l].g_attn : then_gain;
+            bool x_done = false;
+            rc = bf16_layer_forward(m, l, kv, b, s, x_ready, tail_gain, &x_done);
+            x_ready = x_done;
+        } else {
+            rc = f32_layer_forward(m, l, kv, b, s);
+        }
+    }
+    *x_ready_out = x_ready;
+    return rc;
+}
+
+static int head_on(const ee_model* m, int e, ee_batch* b, hipStream_t s, bool x_ready) {
+    // greedy token of head e for every active row: threshold 0 is always met, so no row is a breach
+    return m->cfg.dtype == EE_BF16 ? bf16_exit_head(m, e, 0.0f, 1, b, nullptr, s, x_ready)
+                                   : f32_exit_head(m, e, 0.0f, 1, b, nullptr, s);
+}
+
+static int check_speculation(const char* who, const ee_model* m, const ee_kv* kv, int draft_exit, int* Le, int* R,
+                             int* last_exit) {
+    const ee_model_config& c = m->cfg;
+    *R = ee_model_resident_depth(m);
+    if (*R < 0) return *R;
+    if (*R == 0) return ee_fail(EE_ERR_LAYER_NOT_RESIDENT, std::string(who) + ": no layer is resident");
+    if (draft_exit < 0 || draft_exit >= c.n_exits) return ee_fail(EE_ERR_INVALID_ARG, std::string(who) + ": exit index out of range");
+    *Le = c.exit_layers[draft_exit];
+    *last_exit = -1;
+    for (int e = 0; e < c.n_exits; ++e)
+        if (c.exit_layers[e] == *R) *last_exit = e;
+    if (*last_exit < 0 || !m->exits[*last_exit].set)
+        return ee_fail(EE_ERR_EXIT_NOT_RESIDENT, std::string(who) + ": the deepest resident layer carries no exit head");
+    if (*Le >= *R) return ee_fail(EE_ERR_INVALID_ARG, std::string(who) + ": the draft exit must lie below the deepest resident layer");
+    if (!m->exits[draft_exit].set) return ee_fail(EE_ERR_EXIT_NOT_RESIDENT, std::string(who) + ": the draft exit head was never set");
+    if (kv->n_layers < *R) return ee_fail(EE_ERR_CAPACITY, std::string(who) + ": cache was bound for fewer layers than are resident");
+    if (!m->emb) return ee_fail(EE_ERR_INVALID_ARG, std::string(who) + ": embedding not set");
+    return EE_OK;
+}
+
+int ee_draft_step(const ee_model* m, ee_kv* kv, ee_batch* b, int draft_exit, int32_t* dev_draft_out, void* stream) {
+    int rc = check_pair("ee_draft_step", m, kv, b);
+    if (rc != EE_OK) return rc;
+    int Le, R, last_exit;
+    rc = check_speculation("ee_draft_step", m, kv, draft_exit, &Le, &R, &last_exit);
+    if (rc != EE_OK) return rc;
+    hipStream_t s = as_stream(stream);
+    rc = ee_batch_begin_step(m, b, stream);
+    bool x_ready = false;
+    if (rc == EE_OK) rc = run_layers(m, 1, Le, kv, b, (const float*)m->exits[draft_exit].gain, s, &x_ready);
+    if (rc == EE_OK) rc = head_on(m, draft_exit, b, s, x_ready);
+    if (rc == EE_OK) rc = ee_compact_active(b, draft_exit, Le, stream);          // every row leaves: out_tok = its draft
+    if (rc == EE_OK) rc = launch_end_step(b, s);
+    if (rc == EE_OK && dev_draft_out)
+        EE_HIP_CHECK(hipMemcpyAsync(dev_draft_out, b->st<int32_t>(b->L.out_tok), sizeof(int32_t) * b->B,
+                                    hipMemcpyDeviceToDevice, s));
+    return rc;
+}
+
+int ee_verify_drafts(const ee_model* m, ee_kv* kv, ee_batch* b, ee_batch* vb, int draft_exit, int k,
+                     const float* dev_store, const int32_t* dev_drafts, int32_t* dev_n_emit, int32_t* dev_emit,
+                     void* stream) {
+    int rc = check_pair("ee_verify_drafts", m, kv, b);
+    if (rc != EE_OK) return rc;
+    if (!vb || vb->m != m || vb == b) return ee_fail(EE_ERR_INVALID_ARG, "ee_verify_drafts: the entries batch must be another batch of this model");
+    if (!dev_store || !dev_drafts || !dev_n_emit || !dev_emit) return ee_fail(EE_ERR_INVALID_ARG, "ee_verify_drafts: null array");
+    if (k < 1) return ee_fail(EE_ERR_INVALID_ARG, "ee_verify_drafts: at least one draft per row");
+    if ((int64_t)b->B * k > vb->B) return ee_fail(EE_ERR_CAPACITY, "ee_verify_drafts: the entries batch has fewer than B * k rows");
+    int Le, R, last_exit;
+    rc = check_speculation("ee_verify_drafts", m, kv, draft_exit, &Le, &R, &last_exit);
+    if (rc != EE_OK) return rc;
+    hipStream_t s = as_stream(stream);
+    rc = launch_verify_begin(m, kv, b, vb, k, dev_store, s);
+    vb->kv_seq = vb->wsp<int32_t>(vb->W.kv_seq);   // the layers address the cache through the entry's row
+    bool x_ready = false;
+    if (rc == EE_OK) rc = run_layers(m, Le + 1, R, kv, vb, (const float*)m->exits[last_exit].gain, s, &x_ready);
+    vb->kv_seq = nullptr;
+    if (rc == EE_OK) rc = head_on(m, last_exit, vb, s, x_ready);
+    if (rc == EE_OK) rc = launch_accept_drafts(b, vb, k, dev_drafts, dev_n_emit, dev_emit, s);
+    return rc;
+}
+
 size_t ee_cbc_state_bytes(int window) {
     if (window < 1 || window > EE_CBC_MAX_WINDOW) return 0;
     return align_up(sizeof(ee_cbc_state) + (size_t)window, 8);

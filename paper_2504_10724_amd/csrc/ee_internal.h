@@ -116,6 +116,10 @@ int launch_hstore_put(const ee_model* m, const ee_kv* kv, const ee_batch* b, int
                       hipStream_t s);
 int launch_backfill_begin(const ee_model* m, const ee_kv* kv, ee_batch* b, const float* store, const int32_t* pos,
                           const int32_t* seq, int n, hipStream_t s);
+int launch_verify_begin(const ee_model* m, const ee_kv* kv, const ee_batch* b, ee_batch* vb, int k, const float* store,
+                        hipStream_t s);
+int launch_accept_drafts(ee_batch* b, const ee_batch* vb, int k, const int32_t* drafts, int32_t* n_emit, int32_t* emit,
+                         hipStream_t s);
 int launch_cbc_init(void* st, int window, int cbc_max, hipStream_t s);
 int launch_cbc_push(void* st, const uint8_t* flags, int n, hipStream_t s);
 int launch_pht_init(void* row, hipStream_t s);

@@ -201,6 +201,83 @@ int launch_backfill_begin(const ee_model* m, const ee_kv* kv, ee_batch* b, const
     return EE_OK;
 }
 
+// ------------------------------------------------------------------ self-speculative decoding
+// Verification pass: entry i = r * k + j (row r < n_rows, draft position j < k) becomes row i of the
+// entries batch: cache row r, position pos[r] - k + j (pos[r] = the decode batch's position after its
+// k draft steps), residual stream = the state kept for that position after the draft layers.  An entry
+// whose position lies outside its cache row gets position -1 (refused by the append kernel, status bit 1).
+__global__ void __launch_bounds__(256)
+k_verify_begin(const float* __restrict__ store, int d, int n_rows, int k, const int32_t* __restrict__ pos,
+               const int64_t* __restrict__ off, const int32_t* __restrict__ cap, float* __restrict__ h,
+               int32_t* __restrict__ e_pos, int32_t* __restrict__ kv_seq, int32_t* __restrict__ active_idx,
+               int32_t* __restrict__ n_active, int32_t* __restrict__ n_exited, float* __restrict__ row_scale,
+               int32_t* __restrict__ status) {
+    const int i = blockIdx.x;
+    if (i >= n_rows * k) return;
+    const int r = i / k, j = i % k;
+    int p = pos[r] - k + j;
+    const bool ok = p >= 0 && p < cap[r];
+    if (!ok) {
+        if (threadIdx.x == 0) atomicOr(status, 1);
+        p = -1;
+    }
+    if (threadIdx.x == 0) {
+        e_pos[i] = p;
+        kv_seq[i] = r;
+        active_idx[i] = i;
+        row_scale[i] = 1.0f;
+        if (i == 0) { *n_active = n_rows * k; *n_exited = 0; }
+    }
+    float4* dst = reinterpret_cast<float4*>(h + (int64_t)i * d);
+    if (ok) {
+        const float4* src = reinterpret_cast<const float4*>(store + (off[r] + p) * (int64_t)d);
+        for (int c = threadIdx.x; c < d / 4; c += 256) dst[c] = src[c];
+    } else {
+        for (int c = threadIdx.x; c < d / 4; c += 256) dst[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+
+int launch_verify_begin(const ee_model* m, const ee_kv* kv, const ee_batch* b, ee_batch* vb, int k, const float* store,
+                        hipStream_t s) {
+    const ee_batch_layout& L = vb->L;
+    hipLaunchKernelGGL(k_verify_begin, dim3(b->B * k), dim3(256), 0, s, store, m->cfg.d_model, b->B, k,
+                       b->st<int32_t>(b->L.pos), kv->d_off, kv->d_cap, vb->st<float>(L.h), vb->st<int32_t>(L.pos),
+                       vb->wsp<int32_t>(vb->W.kv_seq), vb->st<int32_t>(L.active_idx), vb->st<int32_t>(L.n_active),
+                       vb->st<int32_t>(L.n_exited), vb->st<float>(L.row_scale), vb->st<int32_t>(L.status));
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
+// Acceptance, one thread per row: drafts d_j = drafts[j * n_rows + r] against the full-depth tokens
+// v_j = head_tok[r * k + j] of the same positions; with a = number of leading positions where they
+// agree, the row emits n = min(a + 1, k) tokens v_0 .. v_{n-1}, its position becomes its position
+// before the drafts + n and its next input token v_{n-1}.
+__global__ void k_accept_drafts(const int32_t* __restrict__ drafts, const int32_t* __restrict__ head_tok, int k,
+                                int n_rows, int32_t* __restrict__ pos, int32_t* __restrict__ tok_in,
+                                int32_t* __restrict__ out_tok, int32_t* __restrict__ n_emit,
+                                int32_t* __restrict__ emit) {
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= n_rows) return;
+    int a = 0;
+    while (a < k && drafts[(int64_t)a * n_rows + r] == head_tok[(int64_t)r * k + a]) ++a;
+    const int n = a + 1 < k ? a + 1 : k;
+    for (int j = 0; j < k; ++j) emit[(int64_t)r * k + j] = j < n ? head_tok[(int64_t)r * k + j] : -1;
+    const int last = head_tok[(int64_t)r * k + n - 1];
+    n_emit[r] = n;
+    pos[r] = pos[r] - k + n;
+    tok_in[r] = last;
+    out_tok[r] = last;
+}
+
+int launch_accept_drafts(ee_batch* b, const ee_batch* vb, int k, const int32_t* drafts, int32_t* n_emit, int32_t* emit,
+                         hipStream_t s) {
+    hipLaunchKernelGGL(k_accept_drafts, dim3((b->B + 255) / 256), dim3(256), 0, s, drafts, vb->st<int32_t>(vb->L.head_tok),
+                       k, b->B, b->st<int32_t>(b->L.pos), b->st<int32_t>(b->L.tok_in), b->st<int32_t>(b->L.out_tok),
+                       n_emit, emit);
+    EE_LAUNCH_CHECK();
+    return EE_OK;
+}
+
 // every row advances one position, whatever layer it left at, and the token it
 // emitted is the input of the next step
 __global__ void k_end_step(int32_t* __restrict__ pos, int32_t* __restrict__ tok_in,

@@ -308,6 +308,33 @@ def backfill_kv(model, from_excl, to_incl, kv, batch, store, pos, seq):
                                     int(p.numel()), _stream())
 
 
+class Speculator:
+    """Exit-layer self-speculative decoding on one batch: the device buffers a round needs (drafts,
+    emitted tokens, the states kept after the draft layers, the batch of B * k entries the verification
+    pass runs on) and the call sequence of a round.  Every step is libee's."""
+
+    def __init__(self, model, kv, batch, draft_exit, k):
+        self.model, self.kv, self.batch, self.draft_exit, self.k = model, kv, batch, draft_exit, k
+        B = batch.B
+        self.store = HiddenStore(model, kv)
+        self.entries = Batch(model, B * k)
+        z = np.zeros(B * k, np.int32)
+        self.entries.reset(z, z, None)                 # clears the status word
+        self.drafts = torch.zeros((k, B), dtype=torch.int32, device="cuda")
+        self.n_emit = torch.zeros(B, dtype=torch.int32, device="cuda")
+        self.emit = torch.zeros((B, k), dtype=torch.int32, device="cuda")
+
+    def round(self):
+        """k draft steps and one verification; enqueue only.  Afterwards n_emit[r] tokens emit[r, :n]
+        are row r's output and the batch stands at its new position."""
+        lib, m = self.model.lib, self.model
+        for j in range(self.k):
+            ee.check(lib.ee_draft_step(m.h, self.kv.h, self.batch.h, self.draft_exit, _ptr(self.drafts[j]), _stream()))
+            ee.check(self.store.put_step(self.batch))
+        ee.check(lib.ee_verify_drafts(m.h, self.kv.h, self.batch.h, self.entries.h, self.draft_exit, self.k,
+                                      _ptr(self.store.buf), _ptr(self.drafts), _ptr(self.n_emit), _ptr(self.emit), _stream()))
+
+
 class LayerLoader:
     """Brings further layers of a model into HBM while decode steps keep running: the copies from
     pinned host memory and the repacking run on a stream of their own; a layer becomes resident
