@@ -519,6 +519,21 @@ def main():
     out["detail"]["self_speculative"] = (None if args.no_speculative or len(s.resident_exits) < 2 else
                                          run_self_speculative(s, model, torch, S, ee, synth))
     out["detail"]["layer_load"] = head.get("layer_load")
+    ll = head.get("layer_load")
+    if ll and context_pass and len(exits) > 1:
+        # Algorithm 1's branch on these measurements (Sec. 3.3.3): this model loaded up to its first exit
+        # and serving the batch's cached tokens, against a candidate of the same shape whose low-exit
+        # version (as deep) is not in HBM yet; rates as measured above, the context pass scaled to that depth
+        ctx_mean = (s.ctx_lo + s.ctx_hi) / 2.0
+        cached = s.batch * ctx_mean
+        r0 = exits[0]
+        load_s = S.overhead_of_loading(s.n_layers - r0, ll["layer_bytes"], ll["under_decode_gbs"] * 1e9, cached,
+                                       ll["backfill"]["token_layers_per_s"])
+        switch_s = S.overhead_of_switching(cached, context_pass["tokens_per_s"] * s.resident / r0,
+                                           bytes_to_load=r0 * ll["layer_bytes"], load_bytes_per_s=ll["under_decode_gbs"] * 1e9)
+        decision, figures = S.reassess(load_s, {"same_shape_low_exit": switch_s})
+        out["detail"]["load_or_switch"] = dict(resident_layers=r0, cached_tokens=cached, load_overhead_s=load_s,
+                                               switch_overhead_s=switch_s, decision=list(decision))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(s, head["counts"])
     print(json.dumps(out))
