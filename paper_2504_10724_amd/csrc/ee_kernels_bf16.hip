@@ -18,6 +18,7 @@
 #include "ee_device.h"
 
 #include <float.h>
+#include <type_traits>
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
@@ -693,6 +694,163 @@ k_bf16_gemm_dma8(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int
 #undef EPI_ROW
 }
 
+// ------------------------------------------------------------------ tile of 192 columns
+// k_bf16_gemm_cols<EPI, NT>: 256 rows x 32 NT columns per workgroup (NT = 5 .. 7; 6 is used), for products whose
+// column tiles fill the 256 CUs badly at 128 or 256 columns (gate/up of the 34B shape has 1376
+// tile-rows: 344 workgroups of 4 take two rounds, 172 of 8 leave a third of the CUs idle, 230 of 6 run
+// in one round).  Same operand path, staging and waits as k_bf16_gemm_dma8, same wave layout: wave
+// (wm, wn) = (w / 4, w % 4) owns row tiles 4 wm .. 4 wm + 3, and the NT column tiles are dealt out
+// over wn (the four SIMDs) as evenly as they go, one or two each, so that whatever the number of
+// live row tiles every SIMD with the same number of column tiles carries the same MFMA work.  LDS: 5
+// stage buffers of 32 slots, X tile (row tile m, K half kk) at 2 m + kk, W tile (column tile nb, K half
+// kk) at 16 + 2 nb + kk; wave w sends the X tiles of row tile w (if live) and the W tiles of column
+// tile w (if w < NT), four stages ahead.  The last workgroup of a product whose tile-rows are no
+// multiple of NT re-reads its last tile-row in place of the missing ones and drops their results.
+struct ColsCtx {
+    uint4*       lds;        // [5][32][64]
+    const uint4* xg;
+    const uint4* wg;
+    int KB, NBs, ks_lo, T, mbs, nt_live, wave, lane, row_base, n, nb0;
+};
+
+template <int EPI, int NT, int NC>
+__device__ __forceinline__ void cols_wave(const ColsCtx& c, const int c0, const EpiArgs& ep) {
+    const int wave = c.wave, lane = c.lane, wm = wave >> 2;
+    const int cnt = max(0, min(4, c.mbs - 4 * wm));           // live row tiles among 4 wm .. 4 wm + 3
+    const unsigned lane_bytes = (unsigned)lane * 16u;
+    const unsigned lds0 = (unsigned)(size_t)c.lds;
+    const bool sends_x = wave < c.mbs, sends_w = wave < NT;
+
+    floatx16 acc[4][NC];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < NC; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // j-th load of a stage: j = 0, 1 the X tile of row tile `wave`, K half j; j = 2, 3 the W tile of
+    // column tile `wave`, K half j - 2.  Address = the stage's base pointer (scalar, once per stage)
+    // plus a lane offset that is the same in every stage.
+    unsigned voff[4];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) voff[j] = lane_bytes + ((unsigned)(min(wave, c.mbs - 1) * c.KB + j) << 10);
+#pragma unroll
+    for (int j = 2; j < 4; ++j) voff[j] = lane_bytes + ((unsigned)((j - 2) * c.NBs + min(wave, c.nt_live - 1)) << 10);
+    auto x_base = [&](int t) { return c.xg + (int64_t)(2 * (c.ks_lo + min(t, c.T - 1))) * 64; };
+    auto w_base = [&](int t) { return c.wg + (int64_t)(2 * (c.ks_lo + min(t, c.T - 1))) * c.NBs * 64; };
+    auto issue = [&](const uint4* xs, const uint4* ws, int buf, int j) {
+        if (j < 2) dma_tile(xs, voff[j], lds0 + (unsigned)((buf * 32 + wave * 2 + j) << 10));
+        else dma_tile<true>(ws, voff[j], lds0 + (unsigned)((buf * 32 + 16 + wave * 2 + (j - 2)) << 10));
+    };
+    uint4 a[2][4], b[2][NC];                                  // [K half][row tile], [K half][column tile]
+    auto slot = [&](int buf, int s_) { return (c.lds + lane + buf * (32 * 64))[s_ * 64]; };
+    auto rd_a = [&](int buf, int kk, int i) { a[kk][i] = slot(buf, (4 * wm + i) * 2 + kk); };
+    auto rd_b = [&](int buf, int kk, int j) { b[kk][j] = slot(buf, 16 + (c0 + j) * 2 + kk); };
+
+    int bc = 0, bn = 1, bi = 4;   // buffers of the current stage, the next one and the one being requested (stage + 4)
+    // One stage: the MFMAs of K half 0 while K half 1 is read from LDS and the X tiles of stage + 4 are
+    // requested, then those of K half 1 while K half 0 of the next stage is read and the W tiles are
+    // requested; the loads are issued one behind an MFMA group each.  Two stages of this wave's loads
+    // may stay in flight at the barrier: everything up to stage + 2 has landed.
+    auto stage = [&](auto xl_, auto wl_, auto all_, int t_req) {
+        constexpr bool XL = decltype(xl_)::value, WL = decltype(wl_)::value, ALL = decltype(all_)::value;
+        const uint4* xs = x_base(t_req);
+        const uint4* ws = w_base(t_req);
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const int rb = kk == 0 ? bc : bn;                 // buffer the other K half is read from
+            const int ok = 1 - kk;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                if (ALL || g < cnt) {
+#pragma unroll
+                    for (int j = 0; j < NC; ++j) acc[g][j] = tile_mfma<EPI>(a[kk][g], b[kk][j], acc[g][j]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (g == 0) {
+                    if (kk == 0 ? XL : WL) issue(xs, ws, bi, 2 * kk);
+                    rd_a(rb, ok, 0); rd_a(rb, ok, 1); rd_b(rb, ok, 0);
+                    if (NC > 1) rd_b(rb, ok, 1);
+                } else if (g == 1) {
+                    if (kk == 0 ? XL : WL) issue(xs, ws, bi, 2 * kk + 1);
+                    rd_a(rb, ok, 2); rd_a(rb, ok, 3);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * (2 * (XL ? 1 : 0) + 2 * (WL ? 1 : 0))) : "memory");
+        bc = bn; bn = bn == 4 ? 0 : bn + 1; bi = bi == 4 ? 0 : bi + 1;
+    };
+    auto slice = [&](auto xl_, auto wl_, auto all_) {
+        constexpr bool XL = decltype(xl_)::value, WL = decltype(wl_)::value;
+#pragma unroll
+        for (int st = 0; st < 4; ++st)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (j < 2 ? XL : WL) issue(x_base(st), w_base(st), st, j);
+        // stages 0 and 1 have landed
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * (2 * (XL ? 1 : 0) + 2 * (WL ? 1 : 0))) : "memory");
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { rd_a(0, 0, i); a[1][i] = a[0][i]; }
+#pragma unroll
+        for (int j = 0; j < NC; ++j) { rd_b(0, 0, j); b[1][j] = b[0][j]; }
+        for (int t0 = 0; t0 < c.T; t0 += 4) {
+            stage(xl_, wl_, all_, t0 + 4); stage(xl_, wl_, all_, t0 + 5); stage(xl_, wl_, all_, t0 + 6); stage(xl_, wl_, all_, t0 + 7);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    };
+    using Yes = std::true_type;
+    using No = std::false_type;
+    // the count of loads a wave may leave in flight is per wave and follows from what it sends, so each
+    // combination runs its own copy of the loop; a wave whose four row tiles are live (the common case)
+    // runs a copy without the live-tile test
+    const bool all = cnt == 4;
+    if (sends_x && sends_w) { if (all) slice(Yes{}, Yes{}, Yes{}); else slice(Yes{}, Yes{}, No{}); }
+    else if (sends_x)       { if (all) slice(Yes{}, No{}, Yes{});  else slice(Yes{}, No{}, No{}); }
+    else if (sends_w)       { slice(No{}, Yes{}, No{}); }
+    else                    { slice(No{}, No{}, No{}); }
+
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (i >= cnt) continue;
+#pragma unroll
+        for (int j = 0; j < NC; ++j)
+            if (c0 + j < c.nt_live)
+                epilogue_one<EPI>(ep, acc[i][j], c.row_base + 32 * (4 * wm + i), c.n, c.nb0 + c0 + j, lane);
+    }
+}
+
+template <int EPI, int NT>
+__global__ void __launch_bounds__(512, 2)
+k_bf16_gemm_cols(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int KB, int NBs, int nb_off, int NB_total,
+                 int n_tiles, const int32_t* __restrict__ n_ptr, int B, EpiArgs ep) {
+    static_assert(NT >= 5 && NT <= 7, "column tiles per workgroup");
+    __shared__ uint4 lds[5][32][64];
+    const int n = min(*n_ptr, B);
+    int rg, tile;
+    tile_of_block(n_tiles, rg, tile);
+    if (tile < 0) return;
+    const int row_base = rg * 256;
+    if (row_base >= n) return;
+    ColsCtx c;
+    c.lds = &lds[0][0][0];
+    c.KB = KB; c.NBs = NBs;
+    c.ks_lo = 0;
+    c.T = KB >> 1;                                            // stages: a positive multiple of 4 (K is a multiple of 128)
+    c.mbs = min(8, (n - row_base + 31) >> 5);
+    c.nt_live = min(NT, NB_total - tile * NT);
+    c.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    c.lane = threadIdx.x & 63;
+    c.row_base = row_base; c.n = n; c.nb0 = tile * NT;
+    c.xg = Xp + ((int64_t)rg * 8 * KB) * 64;
+    c.wg = Wp + (int64_t)(nb_off + tile * NT) * 64;            // the tile's NT tile-rows of W
+    // column tiles of SIMD wn: two for wn < NT - 4, one for the others, in rising order
+    const int wn = c.wave & 3;
+    if (wn < NT - 4) cols_wave<EPI, NT, 2>(c, 2 * wn, ep);
+    else cols_wave<EPI, NT, 1>(c, 2 * (NT - 4) + (wn - (NT - 4)), ep);
+}
+
 // ------------------------------------------------------------------ RoPE + cache append
 // buf[i] = [q (n_q heads, may be 0) | k (Hkv heads) | v (Hkv heads)], fp32, hd = 128.
 // Queries are rotated and written as a bf16 pair (hi, lo) with hi + lo = q to 16
@@ -1196,6 +1354,29 @@ static bool gemm_tiled(const ee_batch* b, const void* X, const void* W, int N, i
         const int ww = (N / 256) * row_groups, wn = (N / 128) * row_groups;
         const float fill_w = (float)ww / (float)((ww + 255) / 256 * 256), fill_n = (float)wn / (float)((wn + 255) / 256 * 256);
         wide = fill_w >= fill_n;
+    }
+    if constexpr (EPI == EPI_SWIGLU) if (row_groups == 1 && nz == 1) {
+        // one row group (decode; with several the product is MFMA bound and the rule above stands).
+        // Tile width for the widest product: 256, 192 or 128 columns, whichever makes the column tiles cost
+        // the fewest rounds of 256 workgroups times the tile's width (what a round costs a CU in operand
+        // traffic); ties go to the wider tile, which re-reads the activations less often.  (224 columns
+        // were measured too, for the 70B shape's 1792 tile-rows = 256 x 7: within 2 % of 256 columns.)
+        const int NB = N / 32;
+        int nt = 4, best = 1 << 30;
+        for (int t = 8; t >= 4; t -= 2) {
+            if (t == 8 && N % 256 != 0) continue;
+            const int wgs = (NB + t - 1) / t * row_groups * nz, cost = (wgs + 255) / 256 * t;
+            if (cost < best) { best = cost; nt = t; }
+        }
+        if (nt == 6) {
+            const int n_tiles = (NB + 5) / 6;
+            dim3 grid(n_tiles, 1, 1);
+            hipLaunchKernelGGL((k_bf16_gemm_cols<EPI, 6>), grid, dim3(512), 0, s, (const uint4*)X, (const uint4*)W, K / 16,
+                               NBs, nb_off, NB, n_tiles, n_ptr, B, ep);
+            if (tail.splits_out) *tail.splits_out = 1;
+            return true;
+        }
+        wide = nt == 8;
     }
     int n_tiles = wide ? N / 256 : N / 128;
     int splits = 1;
