@@ -1347,7 +1347,9 @@ static bool gemm_tiled(const ee_batch* b, const void* X, const void* W, int N, i
     // the 256-column tile loads each activation tile once per 256 columns instead of once per 128;
     // worth it when it still gives every CU a workgroup, or when K is long enough that a deeper K
     // slicing costs little
-    bool wide = (N % 256 == 0) && ((N / 256) * row_groups * nz >= 200 || (EPI == EPI_RESID && K >= 2 * N));
+    // (long K: with more than 128 rows the 256-column tile's halved activation traffic outweighs its
+    // doubled K-slice planes; up to 128 rows the 128-column tile is 2-8 % faster on the down projection)
+    bool wide = (N % 256 == 0) && ((N / 256) * row_groups * nz >= 200 || (EPI == EPI_RESID && K >= 2 * N && Mpad > 128));
     if (!wide && N % 256 == 0 && row_groups >= 2 && nz == 1) {
         // several row groups (context pass): the products are MFMA bound and the 256-column tile does
         // more per MFMA issued; take it when its workgroups fill their rounds of 256 CUs no worse
@@ -1382,6 +1384,9 @@ static bool gemm_tiled(const ee_batch* b, const void* X, const void* W, int N, i
     int splits = 1;
     if ((EPI == EPI_STORE || EPI == EPI_RESID) && nz == 1 && n_tiles * row_groups < 200) {
         splits = (256 + n_tiles * row_groups / 2) / (n_tiles * row_groups);
+        // rounding up may push the launch past one round of 256 workgroups (96 column tiles x 3 slices):
+        // one slice fewer then runs in a single round with longer slices and one plane less
+        while (splits > 1 && n_tiles * row_groups * splits > 256 && n_tiles * row_groups * (splits - 1) >= 176) --splits;
         while (splits > 1 && KS / splits < 16) --splits;   // every slice keeps at least 16 K steps (> 4)
         while (splits > 1 && (size_t)splits * Mpad * N * sizeof(float) > b->W.gemm_part_bytes) --splits;
     }
