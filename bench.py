@@ -28,8 +28,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the gate/up GEMM at batch 256 from the rocprofv3 counter runs summarised in
 # profiles/llama2_70b_b256_hbm_traffic.md (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, KiB -> bytes); valid
 # only for the kernel source it was measured on.
-TRAFFIC_KERNEL_SHA1 = "25e643b9c898fdcc323e5713c9f4a99052cc2570"
-TRAFFIC_GATE_UP_BYTES = (943883 + 9632) * 1024
+TRAFFIC_KERNEL_SHA1 = "9a333c40cb15448c192a64bf5ca9fd5deb4c01f8"
+TRAFFIC_GATE_UP_BYTES = (943825 + 9562) * 1024
 
 
 def measured_traffic(batch):
@@ -342,6 +342,25 @@ def run_workload(s, model, args, torch, S, ee, synth, C, with_load=False):
                      exits=pht_row["exits"][:len(exits)], breaches=pht_row["breaches"],
                      perplexity=float(np.exp(pht_row["nll"] / max(1, pht_row["tokens"])))))
     res["layer_gemms"]["hbm_frac"] = res["layer_gemms"]["hbm_gbs"] / HBM_PEAK_GBS
+    if with_load:
+        # the same kernel with every row still in the stack in every launch (no row may leave before the
+        # last layer): the large-batch figure, priced against the bf16 MFMA peak
+        batch.reset(tok0, ctx.astype(np.int32), None)
+        lib.ee_timing_reset()
+        lib.ee_timing_enable(1 << ee.KERNEL_CLASSES.index("gemm_gate_up"))
+        for t in range(2):
+            batch.set_row_scale(scales[t])
+            rc = S.decode_step(model, kv, batch, [2.0] * len(exits))
+            if rc != 0:
+                raise ee.EEError(rc, lib.ee_last_error().decode())
+        torch.cuda.synchronize()
+        lib.ee_timing_enable(0)
+        full = read_classes()["gemm_gate_up"]
+        t_full = full["total_ms"] / max(1, full["launches"]) * 1e-3
+        fl = 2.0 * s.batch * d * 2 * F
+        roof["at_full_rows"] = dict(rows=s.batch, avg_us=t_full * 1e6, bound="mfma", achieved=fl / t_full / 1e12,
+                                    peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=fl / t_full / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                                    hbm_frac=gu_bytes / t_full / 1e9 / HBM_PEAK_GBS)
     if with_load:
         res["layer_load"] = measure_layer_load(s, model, args, torch, S, ee, kv, batch, run,
                                                lambda: batch.reset(tok0, ctx.astype(np.int32), None))
