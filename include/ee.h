@@ -324,6 +324,9 @@ int ee_prefill(const ee_model* m, ee_kv* kv, ee_batch* b, const int32_t* dev_tok
  * k positions instead of once per token.  One round on a batch of B rows:
  *     k times:  ee_draft_step, then ee_hstore_put_step (keeps each row's state after the draft layers)
  *     once:     ee_verify_drafts
+ *     once:     ee_hstore_put_prefill on the entries batch, B * k entries (optional: replaces the kept
+ *               states by those after layer R, which is what ee_backfill_kv needs if further layers
+ *               are loaded later; positions beyond the emitted ones are written again by later rounds)
  */
 
 /* One draft token for every row: embeds tok_in, runs layers 1 .. exit_layers[draft_exit] on all rows
@@ -347,6 +350,8 @@ int ee_draft_step(const ee_model* m, ee_kv* kv, ee_batch* b, int draft_exit, int
  * b's pos = position before the drafts + n, tok_in = out_tok = v_{n-1}.  Cache entries from the new
  * position on are leftovers of rejected drafts and are overwritten when those positions are decoded.
  * dev_drafts: [k][B] int32, draft j of row r at j * B + r (what ee_draft_step wrote).
+ * Afterwards vb holds the entries like a batch after ee_prefill (h = state after layer R, position and
+ * cache row of every entry), so ee_hstore_put_prefill(m, kv, vb, B * k, ...) may follow.
  * Refusals (a position outside its cache row) set status bit 1 of vb.  Enqueue-only.
  * Errors: as ee_draft_step; EE_ERR_CAPACITY if vb has fewer than B * k rows; EE_ERR_INVALID_ARG on null
  * arrays, k < 1 or vb == b. */

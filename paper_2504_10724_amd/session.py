@@ -313,10 +313,12 @@ class Speculator:
     emitted tokens, the states kept after the draft layers, the batch of B * k entries the verification
     pass runs on) and the call sequence of a round.  Every step is libee's."""
 
-    def __init__(self, model, kv, batch, draft_exit, k):
+    def __init__(self, model, kv, batch, draft_exit, k, store=None):
+        """store: the cache's HiddenStore if the caller keeps one (loading further layers later
+        needs it); after a round it holds, for every emitted position, the state after layer R."""
         self.model, self.kv, self.batch, self.draft_exit, self.k = model, kv, batch, draft_exit, k
         B = batch.B
-        self.store = HiddenStore(model, kv)
+        self.store = store if store is not None else HiddenStore(model, kv)
         self.entries = Batch(model, B * k)
         z = np.zeros(B * k, np.int32)
         self.entries.reset(z, z, None)                 # clears the status word
@@ -333,6 +335,9 @@ class Speculator:
             ee.check(self.store.put_step(self.batch))
         ee.check(lib.ee_verify_drafts(m.h, self.kv.h, self.batch.h, self.entries.h, self.draft_exit, self.k,
                                       _ptr(self.store.buf), _ptr(self.drafts), _ptr(self.n_emit), _ptr(self.emit), _stream()))
+        # the draft steps left the states after the draft layers in the store; what a later backfill of
+        # newly loaded layers needs is the state after layer R, which the verification pass has for all k positions
+        ee.check(self.store.put_prefill(self.entries, self.batch.B * self.k))
 
 
 class LayerLoader:

@@ -209,6 +209,50 @@ def test_serve_load_backfill_serve_bf16_cache():
     assert gg["rc"] == 0 and gg["status"] == 0 and np.all(gg["layer"] == 6) and not gg["breach"].any()
 
 
+def test_layers_loaded_after_speculative_rounds():
+    """Speculative rounds (Sec. 6) on the partially loaded model, then the load action (Sec. 3.3.3): the
+    store must hold, for every emitted position, the state after layer R (the verification pass has it),
+    not the state after the draft layers that the round kept on the way.  The oracle gets the same
+    positions by passing the inputs the GPU used (the token before, then the accepted tokens) through
+    its R layers; the new layers' cache is then compared as in the other load tests."""
+    s = BF16.with_(name="partial_bf16_spec_load", steps=12)
+    k, rounds = 3, 3
+    _say(f"[case] load_layers after {rounds} speculative rounds of {k} drafts, {s.name} B={s.batch}")
+    W, o, g = _sides(s)
+    store = S.HiddenStore(g.model, g.kv)
+    states = {}
+    pb = _context_pass(s, o, g, store, states, 64)
+    g.batch.reset(synth.first_tokens(s), g.ctx.astype(np.int32), None)
+    sp = S.Speculator(g.model, g.kv, g.batch, 0, k, store=store)
+    tok_in, pos = synth.first_tokens(s).copy(), o.ctx.astype(np.int32).copy()
+    e_last = s.exit_layers.index(s.resident)
+    emitted = agree = 0
+    for r in range(rounds):
+        sp.round()
+        torch.cuda.synchronize()
+        assert int(g.batch.field("status").cpu()[0]) == 0 and int(sp.entries.field("status").cpu()[0]) == 0
+        n, e = sp.n_emit.cpu().numpy(), sp.emit.cpu().numpy()
+        for b in range(s.batch):
+            inputs = np.array([tok_in[b]] + e[b, :n[b] - 1].tolist(), np.int32)
+            rc, h = orc.prefill(o.model, o.kv, b, inputs, pos0=int(pos[b]), want_h=True)
+            assert rc == 0
+            for j in range(int(n[b])):
+                states[(b, int(pos[b]) + j)] = h[j].copy()
+                agree += int(orc.exit_head(o.model, e_last, h[j])[1] == e[b, j])
+            emitted += int(n[b])
+            tok_in[b], pos[b] = e[b, n[b] - 1], pos[b] + n[b]
+        assert np.array_equal(g.batch.field("pos").cpu().numpy(), pos)
+    _say(f"  {emitted} tokens emitted, the oracle's full-depth token is the same for {agree}")
+    assert agree >= 0.9 * emitted
+    o.pos = pos
+    _load_rest(s, W, o, g)
+    _backfill(s, o, g, pb, store, states)
+    worst = _compare_new_layers(s, o, g, TOL["bf16"])
+    _say(f"  new layers' cache: worst error {worst:.2e}")
+    gg = g.step(0, thresholds=(2.0, 2.0, 0.0))
+    assert gg["rc"] == 0 and gg["status"] == 0 and np.all(gg["layer"] == 6) and not gg["breach"].any()
+
+
 def test_load_or_switch_on_measured_overheads():
     """Algorithm 1's branch fed by measurements on the device (Sec. 3.3.3, "Load More Layers Or
     Another Candidate Model?"): a partially loaded model A holds the cache of its requests; the
