@@ -18,6 +18,7 @@
 #include "ee_device.h"
 
 #include <float.h>
+#include <algorithm>
 #include <type_traits>
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -1350,12 +1351,40 @@ static bool gemm_tiled(const ee_batch* b, const void* X, const void* W, int N, i
     // (long K: with more than 128 rows the 256-column tile's halved activation traffic outweighs its
     // doubled K-slice planes; up to 128 rows the 128-column tile is 2-8 % faster on the down projection)
     bool wide = (N % 256 == 0) && ((N / 256) * row_groups * nz >= 200 || (EPI == EPI_RESID && K >= 2 * N && Mpad > 128));
+    // K slices of a narrow product when the launch is left to itself: about one workgroup per CU
+    auto slices_for = [&](int tiles) {
+        int sp = (256 + tiles / 2) / tiles;
+        // rounding up may push the launch past one round of 256 workgroups (96 column tiles x 3 slices):
+        // one slice fewer then runs in a single round with longer slices and one plane less
+        while (sp > 1 && tiles * sp > 256 && tiles * (sp - 1) >= 176) --sp;
+        return sp;
+    };
+    auto fit_slices = [&](int sp) {
+        while (sp > 1 && KS / sp < 16) --sp;               // every slice keeps at least 16 K steps (> 4)
+        while (sp > 1 && (size_t)sp * Mpad * N * sizeof(float) > b->W.gemm_part_bytes) --sp;
+        return sp;
+    };
+    const bool sliceable = (EPI == EPI_STORE || EPI == EPI_RESID) && nz == 1;
+    int splits = 0;                                        // 0: not decided yet
     if (!wide && N % 256 == 0 && row_groups >= 2 && nz == 1) {
-        // several row groups (context pass): the products are MFMA bound and the 256-column tile does
-        // more per MFMA issued; take it when its workgroups fill their rounds of 256 CUs no worse
+        // several row groups (context pass, batches above 256): the products are bound by the MFMAs and by
+        // what a CU can pull from L2, and the 256-column tile moves a quarter less per MFMA issued
         const int ww = (N / 256) * row_groups, wn = (N / 128) * row_groups;
-        const float fill_w = (float)ww / (float)((ww + 255) / 256 * 256), fill_n = (float)wn / (float)((wn + 255) / 256 * 256);
-        wide = fill_w >= fill_n;
+        auto fill = [](int wgs) { return (float)wgs / (float)((wgs + 255) / 256 * 256); };
+        if (sliceable && ww <= 256) {
+            // a product that may be K-sliced: the 256-column tile with as many slices (at most 4) as keep
+            // it inside one round of workgroups, against the 128-column tile with the slices it would get
+            // below; ties go to the 256-column tile unless it needs 4 planes for it.  (70B shape, context
+            // pass, per launch with the kernel that adds the planes: QKV at 512 entries 134 -> 104 us, at
+            // 1024 entries 219 -> 198 us; O projection at 768 entries 158 -> 124 us, at 1024 168 -> 148 us.)
+            const int s_w = fit_slices(std::min(4, 256 / ww));
+            const int s_n = fit_slices(wn < 200 ? slices_for(wn) : 1);
+            const float f_w = fill(ww * s_w), f_n = fill(wn * s_n);
+            wide = f_w > f_n || (f_w == f_n && s_w < 4);
+            splits = wide ? s_w : s_n;
+        } else {
+            wide = fill(ww) >= fill(wn);
+        }
     }
     if constexpr (EPI == EPI_SWIGLU) if (row_groups == 1 && nz == 1) {
         // one row group (decode; with several the product is MFMA bound and the rule above stands).
@@ -1381,15 +1410,7 @@ static bool gemm_tiled(const ee_batch* b, const void* X, const void* W, int N, i
         wide = nt == 8;
     }
     int n_tiles = wide ? N / 256 : N / 128;
-    int splits = 1;
-    if ((EPI == EPI_STORE || EPI == EPI_RESID) && nz == 1 && n_tiles * row_groups < 200) {
-        splits = (256 + n_tiles * row_groups / 2) / (n_tiles * row_groups);
-        // rounding up may push the launch past one round of 256 workgroups (96 column tiles x 3 slices):
-        // one slice fewer then runs in a single round with longer slices and one plane less
-        while (splits > 1 && n_tiles * row_groups * splits > 256 && n_tiles * row_groups * (splits - 1) >= 176) --splits;
-        while (splits > 1 && KS / splits < 16) --splits;   // every slice keeps at least 16 K steps (> 4)
-        while (splits > 1 && (size_t)splits * Mpad * N * sizeof(float) > b->W.gemm_part_bytes) --splits;
-    }
+    if (splits == 0) splits = sliceable && n_tiles * row_groups < 200 ? fit_slices(slices_for(n_tiles * row_groups)) : 1;
     dim3 grid(n_tiles * splits, row_groups, nz);
     if (row_groups > 1) grid = dim3((n_tiles * splits + 7) / 8 * 8 * row_groups, 1, nz);   // see tile_of_block
     if (wide)
