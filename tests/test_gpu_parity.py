@@ -52,6 +52,18 @@ SMALL_SLICED = synth.CONFIGS["llama2_7b"].with_(name="small_sliced_bf16", n_laye
                                                 ctx_hi=140, steps=3)
 
 
+# as many exits as the library takes (EE_MAX_EXITS = 16), one after every layer: 16 heads, compactions
+# and fill ranges in one step, rows leaving all along the stack
+ALL_EXITS_F32 = synth.CONFIGS["tiny_f32"].with_(name="all_exits_f32", n_layers=16, resident=16,
+                                                exit_layers=tuple(range(1, 17)),
+                                                thresholds=tuple([0.97 - 0.04 * e for e in range(15)] + [0.0]),
+                                                batch=37, ctx_lo=1, ctx_hi=40, steps=2)
+ALL_EXITS = synth.CONFIGS["llama2_7b"].with_(name="all_exits_bf16", n_layers=16, resident=16, d_model=512, n_q_heads=8,
+                                             n_kv_heads=2, d_ffn=1024, vocab=2048, exit_layers=tuple(range(1, 17)),
+                                             thresholds=tuple([0.97 - 0.04 * e for e in range(15)] + [0.0]),
+                                             batch=45, ctx_lo=3, ctx_hi=90, steps=2)
+
+
 @pytest.fixture(scope="module")
 def sides():
     cache = {}
@@ -165,7 +177,7 @@ def test_calls_one_by_one(s):
 
 
 # ---------------------------------------------------------------- whole steps
-@pytest.mark.parametrize("s", [TINY, MHA, MID, BIG_M, PARTIAL, DEEP, SMALL_SLICED], ids=lambda s: s.name)
+@pytest.mark.parametrize("s", [TINY, MHA, MID, BIG_M, PARTIAL, DEEP, SMALL_SLICED, ALL_EXITS_F32, ALL_EXITS], ids=lambda s: s.name)
 def test_decode_steps(s):
     _say(f"[case] decode_steps {s.name} seed={s.seed} B={s.batch} steps={s.steps}")
     o, g = _fresh(s, jitter=0.0)
