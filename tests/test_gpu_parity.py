@@ -64,6 +64,19 @@ ALL_EXITS = synth.CONFIGS["llama2_7b"].with_(name="all_exits_bf16", n_layers=16,
                                              batch=45, ctx_lo=3, ctx_hi=90, steps=2)
 
 
+# shapes off the 128-wide tile grid: d_model, d_ffn and the vocabulary are multiples of 64, 64 and 32 only, so
+# every product of the layer and the exit head takes the weight-streaming kernel, in each of its row
+# configurations (up to 32, 64, 128 rows, 256 and more).  Checked call by call against the oracle, and the
+# whole step against its calls bit for bit.
+def _odd(batch):
+    return synth.CONFIGS["llama2_7b"].with_(name=f"off_grid_bf16_b{batch}", n_layers=3, resident=3, d_model=576, n_q_heads=4,
+                                            n_kv_heads=2, d_ffn=1088, vocab=2080, exit_layers=(1, 3),
+                                            thresholds=(0.7, 0.0), batch=batch, ctx_lo=3, ctx_hi=70, steps=2)
+
+
+OFF_GRID = [_odd(b) for b in (20, 50, 100, 300)]
+
+
 @pytest.fixture(scope="module")
 def sides():
     cache = {}
@@ -85,7 +98,7 @@ def _fresh(s, jitter=0.1):
 
 
 # ---------------------------------------------------------------- per-call parity
-@pytest.mark.parametrize("s", [TINY, MHA, MID], ids=lambda s: s.name)
+@pytest.mark.parametrize("s", [TINY, MHA, MID] + OFF_GRID, ids=lambda s: s.name)
 def test_calls_one_by_one(s):
     _say(f"[case] calls_one_by_one {s.name} seed={s.seed} B={s.batch}")
     o, g = _fresh(s)
@@ -237,7 +250,7 @@ def test_two_runs_are_bitwise_identical():
             assert np.array_equal(K1, K2) and np.array_equal(V1, V2)
 
 
-@pytest.mark.parametrize("s", [MID, BIG_M], ids=lambda s: s.name)
+@pytest.mark.parametrize("s", [MID, BIG_M, OFF_GRID[1], OFF_GRID[3]], ids=lambda s: s.name)
 def test_step_equals_its_calls_one_by_one(s):
     """ee_decode_step and the same sequence of the per-call entry points give the same bits:
     the step may hand a normalised operand from one kernel to the next, the calls may not."""
