@@ -75,6 +75,11 @@ def _odd(batch):
 
 
 OFF_GRID = [_odd(b) for b in (20, 50, 100, 300)]
+# a residual stream wider than the 8192 values one block of the norm and finish kernels holds in registers:
+# their chunked paths, with K-sliced O and down projections (two slices each)
+WIDE_D = synth.CONFIGS["llama2_7b"].with_(name="wide_d_bf16", n_layers=2, resident=2, d_model=12288, n_q_heads=8,
+                                          n_kv_heads=2, d_ffn=1024, vocab=2048, exit_layers=(1, 2),
+                                          thresholds=(0.7, 0.0), batch=24, ctx_lo=3, ctx_hi=70, steps=2)
 
 
 @pytest.fixture(scope="module")
@@ -98,7 +103,7 @@ def _fresh(s, jitter=0.1):
 
 
 # ---------------------------------------------------------------- per-call parity
-@pytest.mark.parametrize("s", [TINY, MHA, MID] + OFF_GRID, ids=lambda s: s.name)
+@pytest.mark.parametrize("s", [TINY, MHA, MID, WIDE_D] + OFF_GRID, ids=lambda s: s.name)
 def test_calls_one_by_one(s):
     _say(f"[case] calls_one_by_one {s.name} seed={s.seed} B={s.batch}")
     o, g = _fresh(s)
@@ -250,7 +255,7 @@ def test_two_runs_are_bitwise_identical():
             assert np.array_equal(K1, K2) and np.array_equal(V1, V2)
 
 
-@pytest.mark.parametrize("s", [MID, BIG_M, OFF_GRID[1], OFF_GRID[3]], ids=lambda s: s.name)
+@pytest.mark.parametrize("s", [MID, BIG_M, WIDE_D, OFF_GRID[1], OFF_GRID[3]], ids=lambda s: s.name)
 def test_step_equals_its_calls_one_by_one(s):
     """ee_decode_step and the same sequence of the per-call entry points give the same bits:
     the step may hand a normalised operand from one kernel to the next, the calls may not."""
