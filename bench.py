@@ -342,6 +342,21 @@ def run_workload(s, model, args, torch, S, ee, synth, C, with_load=False):
                      exits=pht_row["exits"][:len(exits)], breaches=pht_row["breaches"],
                      perplexity=float(np.exp(pht_row["nll"] / max(1, pht_row["tokens"])))))
     res["layer_gemms"]["hbm_frac"] = res["layer_gemms"]["hbm_gbs"] / HBM_PEAK_GBS
+    if s.batch <= 16:
+        # few requests: the same steps run segment by segment, the host looking at n_active after every exit
+        # and ending the step once no row is left (the layers nobody reaches are never launched)
+        batch.reset(tok0, ctx.astype(np.int32), None)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        segs = 0
+        for t in range(args.steps):
+            batch.set_row_scale(scales[t])
+            segs += S.decode_step_checked(model, kv, batch, th)
+        torch.cuda.synchronize()
+        dt_c = time.perf_counter() - t0
+        assert f("exit_counts").cpu().numpy()[:len(exits)].astype(np.int64).tolist() == counts.tolist()
+        res["step_in_segments"] = dict(tokens_per_s=tokens / dt_c, ms_per_step=dt_c / args.steps * 1e3,
+                                       segments_run_per_step=segs / args.steps, segments=len(exits))
     if with_load:
         # the same kernel with every row still in the stack in every launch (no row may leave before the
         # last layer): the large-batch figure, priced against the bf16 MFMA peak
@@ -521,7 +536,7 @@ def main():
             r = run_workload(s.with_(batch=b), model, args, torch, S, ee, synth, C)
             sweep[str(b)] = {k: r[k] for k in ("tokens_per_s", "ms_per_step", "exit_fractions", "avg_layers_per_token",
                                                "gate_up_gemm", "attention", "layer_gemms",
-                                               "exit_head_plus_compaction_us_per_step")}
+                                               "exit_head_plus_compaction_us_per_step", "step_in_segments") if k in r}
     context_pass = None if args.no_context_pass else run_context_pass(s, model, torch, S, ee, synth, C, 1024)
     exits = s.resident_exits
     out = dict(metric="decoded tokens/s/GPU at Llama2-70B shape", value=head["tokens_per_s"], unit="tokens/s", n_gpus=1,

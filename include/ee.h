@@ -293,6 +293,22 @@ int ee_fill_skipped_kv(const ee_model* m, int from_layer_excl, int to_layer_incl
 int ee_decode_step(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_thresholds,
                    int n_thresholds, void* stream);
 
+/* The same step in pieces, for callers that look at the batch between exits.  With one or a few
+ * requests in the batch (the paper's default is one, Sec. 1) every row has often left well before
+ * layer R, and the launches of the layers that no row reaches then cost more than a look at n_active:
+ * segment e = the layers after exit e - 1 up to exit layer e (segment 0 starts with the embedding), exit
+ * head e, the compaction, and the K/V of the layers up to the next exit for the rows that have left.
+ * A step is ee_decode_segment for e = 0, 1, ... in order, then ee_decode_finish(last segment run); the
+ * caller may stop after any segment once n_active is 0 (it reads that field itself, after synchronising
+ * the stream), and must run all segments otherwise.  ee_decode_finish gives the rows that have left their
+ * K and V in the layers of the segments that were not run, then pos += 1 and tok_in = out_tok as at the
+ * end of ee_decode_step.  Outputs, cache and batch state are those of ee_decode_step, bit for bit.
+ * Finishing while rows are still active leaves those rows without a token: the caller's error, not
+ * detected here.  Errors: as ee_decode_step; EE_ERR_INVALID_ARG if there is no such segment. */
+int ee_decode_segment(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_thresholds,
+                      int n_thresholds, int segment, void* stream);
+int ee_decode_finish(const ee_model* m, ee_kv* kv, ee_batch* b, int last_segment, void* stream);
+
 /* Context pass ("prefill") on the resident layers 1..R: builds the keys and values that the
  * decode step reads; its duration is what bounds the time to first token (Sec. 4.4,
  * Appendix E.1), and with greedy partial loading it runs on R layers only (Sec. 3.3.3).

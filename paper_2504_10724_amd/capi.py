@@ -71,6 +71,8 @@ _SIGS = {
     "ee_compact_active": (_i, [_vp, _i, _i, _vp]),
     "ee_fill_skipped_kv": (_i, [_vp, _i, _i, _vp, _vp, _vp]),
     "ee_decode_step": (_i, [_vp, _vp, _vp, C.POINTER(C.c_float), _i, _vp]),
+    "ee_decode_segment": (_i, [_vp, _vp, _vp, C.POINTER(C.c_float), _i, _i, _vp]),
+    "ee_decode_finish": (_i, [_vp, _vp, _vp, _i, _vp]),
     "ee_prefill": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _vp]),
     "ee_draft_step": (_i, [_vp, _vp, _vp, _i, _vp, _vp]),
     "ee_verify_drafts": (_i, [_vp, _vp, _vp, _vp, _i, _i, _vp, _vp, _vp, _vp, _vp]),

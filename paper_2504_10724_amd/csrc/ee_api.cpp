@@ -717,66 +717,108 @@ int ee_pht_push_step(void* dev_row, const ee_model* m, const ee_batch* b, void* 
     return launch_pht_push(dev_row, m, b, as_stream(stream));
 }
 
-int ee_decode_step(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_thresholds, int n_thresholds,
-                   void* stream) {
-    int rc = check_pair("ee_decode_step", m, kv, b);
+// what every form of the decode step checks first; *R_out = deepest resident layer, *n_res_out = resident exits
+static int check_step(const char* who, const ee_model* m, const ee_kv* kv, const ee_batch* b, const float* host_thresholds,
+                      int n_thresholds, int* R_out, int* n_res_out) {
+    const std::string w(who);
+    int rc = check_pair(who, m, kv, b);
     if (rc != EE_OK) return rc;
-    if (!host_thresholds) return ee_fail(EE_ERR_INVALID_ARG, "ee_decode_step: null thresholds");
+    if (!host_thresholds) return ee_fail(EE_ERR_INVALID_ARG, w + ": null thresholds");
     int R = ee_model_resident_depth(m);
     if (R < 0) return R;
-    if (R == 0) return ee_fail(EE_ERR_LAYER_NOT_RESIDENT, "ee_decode_step: no layer is resident");
+    if (R == 0) return ee_fail(EE_ERR_LAYER_NOT_RESIDENT, w + ": no layer is resident");
     const ee_model_config& c = m->cfg;
     int n_res = 0;
     for (int e = 0; e < c.n_exits; ++e)
         if (c.exit_layers[e] <= R) ++n_res;
     if (n_res == 0 || c.exit_layers[n_res - 1] != R)
-        return ee_fail(EE_ERR_EXIT_NOT_RESIDENT, "ee_decode_step: the deepest resident layer carries no exit head");
+        return ee_fail(EE_ERR_EXIT_NOT_RESIDENT, w + ": the deepest resident layer carries no exit head");
     for (int e = 0; e < n_res; ++e)
-        if (!m->exits[e].set) return ee_fail(EE_ERR_EXIT_NOT_RESIDENT, "ee_decode_step: a resident exit head was never set");
-    if (n_thresholds != n_res) return ee_fail(EE_ERR_INVALID_ARG, "ee_decode_step: one threshold per resident exit is required");
+        if (!m->exits[e].set) return ee_fail(EE_ERR_EXIT_NOT_RESIDENT, w + ": a resident exit head was never set");
+    if (n_thresholds != n_res) return ee_fail(EE_ERR_INVALID_ARG, w + ": one threshold per resident exit is required");
     for (int e = 0; e < n_res; ++e)
-        if (std::isnan(host_thresholds[e])) return ee_fail(EE_ERR_INVALID_ARG, "ee_decode_step: threshold is NaN");
-    if (kv->n_layers < R) return ee_fail(EE_ERR_CAPACITY, "ee_decode_step: cache was bound for fewer layers than are resident");
-    if (!m->emb) return ee_fail(EE_ERR_INVALID_ARG, "ee_decode_step: embedding not set");
+        if (std::isnan(host_thresholds[e])) return ee_fail(EE_ERR_INVALID_ARG, w + ": threshold is NaN");
+    if (kv->n_layers < R) return ee_fail(EE_ERR_CAPACITY, w + ": cache was bound for fewer layers than are resident");
+    if (!m->emb) return ee_fail(EE_ERR_INVALID_ARG, w + ": embedding not set");
+    *R_out = R;
+    *n_res_out = n_res;
+    return EE_OK;
+}
 
-    void* s = stream;
-    rc = ee_batch_begin_step(m, b, s);
-    int next_exit = 0;
+// Segment e of a step: the layers after exit e - 1 up to exit layer e (segment 0 starts with the embedding), the
+// exit head there, the compaction, and the K/V of the layers up to the next exit for the rows that have left.
+static int step_segment(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_thresholds, int e, int R, void* s) {
+    const ee_model_config& c = m->cfg;
+    int rc = e == 0 ? ee_batch_begin_step(m, b, s) : EE_OK;
+    const int first = e == 0 ? 1 : c.exit_layers[e - 1] + 1, last = c.exit_layers[e];
     // bf16: the kernel that finishes a layer can leave the normalised operand of whatever comes
     // next (the exit head, or the next layer when no compaction lies between): one launch less
     bool x_ready = false;
-    for (int l = 1; l <= R && rc == EE_OK; ++l) {
-        const bool exit_here = c.exit_layers[next_exit] == l;
+    for (int l = first; l <= last && rc == EE_OK; ++l) {
         if (c.dtype == EE_BF16) {
-            const float* tail_gain = exit_here ? (const float*)m->exits[next_exit].gain
-                                               : (const float*)m->layers[l].g_attn;   // l < R here
+            const float* tail_gain = l == last ? (const float*)m->exits[e].gain : (const float*)m->layers[l].g_attn;
             bool x_done = false;
             rc = bf16_layer_forward(m, l, kv, b, as_stream(s), x_ready, tail_gain, &x_done);
             x_ready = x_done;
         } else {
             rc = ee_layer_forward(m, l, kv, b, s);
         }
-        if (rc != EE_OK || !exit_here) continue;
-        int e = next_exit++;
-        if (c.dtype == EE_BF16)
-            rc = bf16_exit_head(m, e, host_thresholds[e], l == R ? 1 : 0, b, nullptr, as_stream(s), x_ready);
-        else
-            rc = ee_exit_head(m, e, host_thresholds[e], l == R, b, nullptr, s);
-        x_ready = false;                                     // the compaction renumbers the list entries
-        if (rc == EE_OK) rc = ee_compact_active(b, e, l, s);
-        if (rc != EE_OK || l == R) continue;
-        if (c.dtype == EE_BF16) {
-            // Sec. 2.2 asks for the skipped layers' K/V of every row that left; when they are computed
-            // within the step is free, since nothing reads them before the next step.  Filling only up
-            // to the next exit layer, for all rows that have left so far in this step, reads W_k, W_v of
-            // every layer once per step instead of once per earlier exit.
-            rc = bf16_fill_kv(m, l, c.exit_layers[next_exit], kv, b, as_stream(s), b->wsp<int32_t>(b->W.gone_idx),
-                              b->wsp<int32_t>(b->W.n_gone));
-        } else {
-            rc = ee_fill_skipped_kv(m, l, R, kv, b, s);
-        }
     }
-    if (rc == EE_OK) rc = launch_end_step(b, as_stream(s));
+    if (rc != EE_OK) return rc;
+    if (c.dtype == EE_BF16)
+        rc = bf16_exit_head(m, e, host_thresholds[e], last == R ? 1 : 0, b, nullptr, as_stream(s), x_ready);
+    else
+        rc = ee_exit_head(m, e, host_thresholds[e], last == R, b, nullptr, s);
+    if (rc == EE_OK) rc = ee_compact_active(b, e, last, s);    // renumbers the list entries
+    if (rc != EE_OK || last == R) return rc;
+    if (c.dtype == EE_BF16) {
+        // Sec. 2.2 asks for the skipped layers' K/V of every row that left; when they are computed
+        // within the step is free, since nothing reads them before the next step.  Filling only up
+        // to the next exit layer, for all rows that have left so far in this step, reads W_k, W_v of
+        // every layer once per step instead of once per earlier exit.
+        rc = bf16_fill_kv(m, last, c.exit_layers[e + 1], kv, b, as_stream(s), b->wsp<int32_t>(b->W.gone_idx),
+                          b->wsp<int32_t>(b->W.n_gone));
+    } else {
+        rc = ee_fill_skipped_kv(m, last, R, kv, b, s);
+    }
+    return rc;
+}
+
+int ee_decode_step(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_thresholds, int n_thresholds,
+                   void* stream) {
+    int R = 0, n_res = 0;
+    int rc = check_step("ee_decode_step", m, kv, b, host_thresholds, n_thresholds, &R, &n_res);
+    for (int e = 0; e < n_res && rc == EE_OK; ++e) rc = step_segment(m, kv, b, host_thresholds, e, R, stream);
+    if (rc == EE_OK) rc = launch_end_step(b, as_stream(stream));
+    return rc;
+}
+
+int ee_decode_segment(const ee_model* m, ee_kv* kv, ee_batch* b, const float* host_thresholds, int n_thresholds,
+                      int segment, void* stream) {
+    int R = 0, n_res = 0;
+    int rc = check_step("ee_decode_segment", m, kv, b, host_thresholds, n_thresholds, &R, &n_res);
+    if (rc != EE_OK) return rc;
+    if (segment < 0 || segment >= n_res) return ee_fail(EE_ERR_INVALID_ARG, "ee_decode_segment: no such segment");
+    return step_segment(m, kv, b, host_thresholds, segment, R, stream);
+}
+
+int ee_decode_finish(const ee_model* m, ee_kv* kv, ee_batch* b, int last_segment, void* stream) {
+    int rc = check_pair("ee_decode_finish", m, kv, b);
+    if (rc != EE_OK) return rc;
+    int R = ee_model_resident_depth(m);
+    if (R <= 0) return R < 0 ? R : ee_fail(EE_ERR_LAYER_NOT_RESIDENT, "ee_decode_finish: no layer is resident");
+    const ee_model_config& c = m->cfg;
+    int n_res = 0;
+    for (int e = 0; e < c.n_exits; ++e)
+        if (c.exit_layers[e] <= R) ++n_res;
+    if (last_segment < 0 || last_segment >= n_res) return ee_fail(EE_ERR_INVALID_ARG, "ee_decode_finish: no such segment");
+    if (kv->n_layers < R) return ee_fail(EE_ERR_CAPACITY, "ee_decode_finish: cache was bound for fewer layers than are resident");
+    // the segments that were not run would have filled the K/V of their layers for the rows that have left
+    // (all of them, if the caller stops here rightly); an fp32 segment fills through layer R itself
+    if (c.dtype == EE_BF16 && last_segment + 1 < n_res && c.exit_layers[last_segment + 1] < R)
+        rc = bf16_fill_kv(m, c.exit_layers[last_segment + 1], R, kv, b, as_stream(stream), b->wsp<int32_t>(b->W.gone_idx),
+                          b->wsp<int32_t>(b->W.n_gone));
+    if (rc == EE_OK) rc = launch_end_step(b, as_stream(stream));
     return rc;
 }
 

@@ -248,6 +248,21 @@ def decode_step(model, kv, batch, thresholds):
     return model.lib.ee_decode_step(model.h, kv.h, batch.h, th, len(thresholds), _stream())
 
 
+def decode_step_checked(model, kv, batch, thresholds):
+    """One decode step run segment by segment (ee_decode_segment), with a look at n_active after every
+    exit but the last: once no row is left, ee_decode_finish ends the step and the deeper layers are
+    never launched.  For small batches; each look synchronises the stream.  Returns the number of
+    segments that ran."""
+    th = (C.c_float * len(thresholds))(*thresholds)
+    lib, n_active = model.lib, batch.field("n_active")
+    for e in range(len(thresholds)):
+        ee.check(lib.ee_decode_segment(model.h, kv.h, batch.h, th, len(thresholds), e, _stream()))
+        if e + 1 < len(thresholds) and int(n_active.item()) == 0:
+            break
+    ee.check(lib.ee_decode_finish(model.h, kv.h, batch.h, e, _stream()))
+    return e + 1
+
+
 def _i32_device(a):
     if isinstance(a, torch.Tensor):
         assert a.is_cuda and a.dtype == torch.int32 and a.is_contiguous()
