@@ -82,6 +82,13 @@ WIDE_D = synth.CONFIGS["llama2_7b"].with_(name="wide_d_bf16", n_layers=2, reside
                                           thresholds=(0.7, 0.0), batch=24, ctx_lo=3, ctx_hi=70, steps=2)
 
 
+# long contexts: 4000 to 8200 cached positions per row (256 groups of 32 positions, split over workgroups and
+# merged), rotary angles at high positions
+LONG_CTX = synth.CONFIGS["llama2_7b"].with_(name="long_ctx_bf16", n_layers=2, resident=2, d_model=512, n_q_heads=8,
+                                            n_kv_heads=2, d_ffn=1024, vocab=2048, exit_layers=(1, 2),
+                                            thresholds=(0.7, 0.0), batch=5, ctx_lo=4000, ctx_hi=8200, steps=2)
+
+
 @pytest.fixture(scope="module")
 def sides():
     cache = {}
@@ -103,7 +110,7 @@ def _fresh(s, jitter=0.1):
 
 
 # ---------------------------------------------------------------- per-call parity
-@pytest.mark.parametrize("s", [TINY, MHA, MID, WIDE_D] + OFF_GRID, ids=lambda s: s.name)
+@pytest.mark.parametrize("s", [TINY, MHA, MID, WIDE_D, LONG_CTX] + OFF_GRID, ids=lambda s: s.name)
 def test_calls_one_by_one(s):
     _say(f"[case] calls_one_by_one {s.name} seed={s.seed} B={s.batch}")
     o, g = _fresh(s)
@@ -195,7 +202,8 @@ def test_calls_one_by_one(s):
 
 
 # ---------------------------------------------------------------- whole steps
-@pytest.mark.parametrize("s", [TINY, MHA, MID, BIG_M, PARTIAL, DEEP, SMALL_SLICED, ALL_EXITS_F32, ALL_EXITS], ids=lambda s: s.name)
+@pytest.mark.parametrize("s", [TINY, MHA, MID, BIG_M, PARTIAL, DEEP, SMALL_SLICED, ALL_EXITS_F32, ALL_EXITS, LONG_CTX],
+                         ids=lambda s: s.name)
 def test_decode_steps(s):
     _say(f"[case] decode_steps {s.name} seed={s.seed} B={s.batch} steps={s.steps}")
     o, g = _fresh(s, jitter=0.0)
