@@ -28,8 +28,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the gate/up GEMM at batch 256 from the rocprofv3 counter runs summarised in
 # profiles/llama2_70b_b256_hbm_traffic.md (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, KiB -> bytes); valid
 # only for the kernel source it was measured on.
-TRAFFIC_KERNEL_SHA1 = "a445a430b98d4b55dfea08a784256a1d40155e5c"
-TRAFFIC_GATE_UP_BYTES = (944136 + 9618) * 1024
+TRAFFIC_KERNEL_SHA1 = "4865c2d483da2cb324cb0dddd47a355ec085bc27"
+TRAFFIC_GATE_UP_BYTES = (943832 + 9366) * 1024
 
 
 def measured_traffic(batch):

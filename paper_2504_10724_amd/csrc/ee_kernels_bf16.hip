@@ -984,40 +984,40 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
     const int G = Hq / kv.n_kv_heads;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int n16 = lane & 15, gq = lane >> 4;
-    // PAIR (context pass, 2 G <= 16): the workgroup serves list entries 2 y and 2 y + 1.  If both
-    // read the same cache row they share its K/V stream: entry A's heads are MFMA columns
-    // 0 .. G-1, entry B's G .. 2G-1, each column masked at its own entry's position.  Otherwise
-    // the entries are served one after the other.
-    int iA, iB = -1;
+    // PAIR (context pass and other passes over list entries, 2 G <= 16): the workgroup serves the E = 16 / G
+    // list entries E y .. E y + E - 1.  Consecutive entries that read the same cache row (a context passed
+    // in rising position order) share its K/V stream: entry j of such a run has its G heads in the MFMA
+    // columns G j .. G j + G - 1, each column masked at its own entry's position.  With one query head per
+    // kv head 16 entries share a stream, with eight heads two.  A change of cache row inside the E entries
+    // starts another run, served after the first.
+    int first, cnt = 1;
     if (PAIR) {
-        iA = 2 * (int)blockIdx.y;
-        if (iA >= n) return;
-        if (iA + 1 < n) iB = iA + 1;
+        const int E = 16 / G;
+        first = E * (int)blockIdx.y;
+        if (first >= n) return;
+        cnt = min(E, n - first);
     } else {
         if ((int)blockIdx.y >= n) return;
-        iA = order[blockIdx.y];            // longest contexts first
+        first = order[blockIdx.y];            // longest contexts first
     }
-    bool joint = false;
-    if (PAIR && iB >= 0) joint = kv_row(kv, idx[iA]) == kv_row(kv, idx[iB]);
-    const int n_pass = (PAIR && iB >= 0 && !joint) ? 2 : 1;
-    for (int pass = 0; pass < n_pass; ++pass) {
-    const int e0 = pass == 0 ? iA : iB;                    // entry of columns 0 .. G-1
-    const int e1 = joint ? iB : -1;                        // entry of columns G .. 2G-1, if any
-    const int n_col = e1 >= 0 ? 2 * G : G;                 // live MFMA columns
-    const int sq = kv_row(kv, idx[e0]);
+    for (int r0 = 0; r0 < cnt;) {
+    const int sq = kv_row(kv, idx[first + r0]);
+    int r1 = r0 + 1;
+    if (PAIR) while (r1 < cnt && kv_row(kv, idx[first + r1]) == sq) ++r1;
+    const int n_col = (r1 - r0) * G;                       // live MFMA columns
     const int cap = kv.cap[sq];
-    const int np0 = max(1, min(pos[idx[e0]] + 1, cap));
-    const int np1 = e1 >= 0 ? max(1, min(pos[idx[e1]] + 1, cap)) : 0;
-    const int n_pos = max(np0, np1);                       // positions read
-    const int my_e = n16 < G ? e0 : e1;                    // this lane's column: entry, head, positions
-    const int my_head = n16 < G ? n16 : n16 - G;
-    const int my_np = n16 < G ? np0 : np1;
+    int n_pos = 1;                                         // positions read: the longest of the run
+    for (int j = r0; j < r1; ++j) n_pos = max(n_pos, min(pos[idx[first + j]] + 1, cap));
+    const int my_ent = n16 < n_col ? n16 / G : 0;          // this lane's column: entry, head, positions
+    const int my_e = first + r0 + my_ent;
+    const int my_head = n16 - my_ent * G;
+    const int my_np = n16 < n_col ? max(1, min(pos[idx[my_e]] + 1, cap)) : 0;
     const bf16_t* Kb = reinterpret_cast<const bf16_t*>(kv.pool) + kv_block(kv, sq, g, cap);
 
     bf16x8 qh[4], ql[4];
     {
         uint4 z = make_uint4(0, 0, 0, 0);
-        const int64_t qo = ((int64_t)max(my_e, 0) * Hq + (int64_t)g * G + my_head) * 128 + 8 * gq;
+        const int64_t qo = ((int64_t)my_e * Hq + (int64_t)g * G + my_head) * 128 + 8 * gq;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             qh[c] = as_bf16x8(n16 < n_col ? *reinterpret_cast<const uint4*>(q_hi + qo + 32 * c) : z);
@@ -1138,8 +1138,8 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
     {
         const int head = threadIdx.x >> 4, c0 = (threadIdx.x & 15) * 8;     // head = MFMA column
         if (head < n_col) {
-            const int i = head < G ? e0 : e1;
-            const int hq = head < G ? head : head - G;
+            const int i = first + r0 + head / G;
+            const int hq = head % G;
             float M = fmaxf(fmaxf(sm_m[0][head], sm_m[1][head]), fmaxf(sm_m[2][head], sm_m[3][head]));
             float wgt[4], Lsum = 0.f;
 #pragma unroll
@@ -1166,7 +1166,8 @@ k_bf16_attn(const bf16_t* __restrict__ q_hi, const bf16_t* __restrict__ q_lo, in
             }
         }
     }
-    if (n_pass > 1) __syncthreads();       // the merge has read the shared arrays before the next entry writes them
+    r0 = r1;
+    if (r0 < cnt) __syncthreads();         // the merge has read the shared arrays before the next run writes them
     }
 }
 
@@ -1484,10 +1485,11 @@ int bf16_layer_forward(const ee_model* m, int layer, ee_kv* kv, ee_batch* b, hip
         int n_splits = pairs >= 512 ? 1 : (1024 + pairs - 1) / pairs;
         if (n_splits > 16) n_splits = 16;
         while (n_splits > 1 && (size_t)b->Mpad * c.n_kv_heads * n_splits * 16 * 130 * 4 > b->W.attn_part_bytes) --n_splits;
-        // context pass: two entries per workgroup, which share the K/V stream when they sit in the same cache row
-        const bool pair = b->kv_seq != nullptr && n_splits == 1 && 2 * (c.n_q_heads / c.n_kv_heads) <= 16;
+        // context pass: 16 / G entries per workgroup, which share the K/V stream where they sit in the same cache row
+        const int G = c.n_q_heads / c.n_kv_heads;
+        const bool pair = b->kv_seq != nullptr && n_splits == 1 && 2 * G <= 16;
         if (pair)
-            hipLaunchKernelGGL(k_bf16_attn<true>, dim3(c.n_kv_heads, (B + 1) / 2, 1), dim3(256), 0, s, b->wsp<bf16_t>(b->W.q_hi),
+            hipLaunchKernelGGL(k_bf16_attn<true>, dim3(c.n_kv_heads, (B + 16 / G - 1) / (16 / G), 1), dim3(256), 0, s, b->wsp<bf16_t>(b->W.q_hi),
                                b->wsp<bf16_t>(b->W.q_lo), c.n_q_heads, idx, n_ptr, B, b->st<int32_t>(L.pos), view, ao,
                                qd / 16, 1, b->wsp<float>(b->W.attn_part), b->wsp<int32_t>(b->W.attn_order));
         else

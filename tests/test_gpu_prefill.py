@@ -35,11 +35,17 @@ MID = synth.CONFIGS["llama2_7b"].with_(name="mid_bf16_ctx", n_layers=6, resident
 WIDE = synth.CONFIGS["llama2_7b"].with_(name="wide_bf16_ctx", n_layers=2, resident=2, d_model=512, n_q_heads=8,
                                         n_kv_heads=1, d_ffn=1536, vocab=4096, exit_layers=(1, 2),
                                         thresholds=(0.8, 0.0), batch=40, ctx_lo=5, ctx_hi=70, steps=1)
-# enough (kv head, entry) pairs per call that the attention kernel serves two entries per workgroup
-# (shared K/V stream when they sit in the same cache row), G = 4 query heads per kv head
+# enough (kv head, entry) pairs per call that the attention kernel serves several entries per workgroup
+# (shared K/V stream where they sit in the same cache row), G = 4 query heads per kv head: four entries
 PAIRS = synth.CONFIGS["llama2_7b"].with_(name="pairs_bf16_ctx", n_layers=2, resident=2, d_model=512, n_q_heads=32,
                                          n_kv_heads=8, d_ffn=1024, vocab=2048, exit_layers=(1, 2),
                                          thresholds=(0.8, 0.0), batch=10, ctx_lo=1, ctx_hi=150, steps=1)
+# G = 2 and G = 3 query heads per kv head: 8 and 5 entries per workgroup share a K/V stream (5 x 3 of the 16
+# MFMA columns in use); contexts short enough that several cache rows meet inside one workgroup's entries
+GQA2 = synth.CONFIGS["llama2_7b"].with_(name="gqa2_bf16_ctx", n_layers=2, resident=2, d_model=512, n_q_heads=8,
+                                        n_kv_heads=4, d_ffn=1024, vocab=2048, exit_layers=(1, 2),
+                                        thresholds=(0.8, 0.0), batch=14, ctx_lo=1, ctx_hi=60, steps=1)
+GQA3 = GQA2.with_(name="gqa3_bf16_ctx", n_q_heads=6, n_kv_heads=2, d_model=768)
 # partially loaded model: the pass stops at the last resident layer
 PARTIAL = synth.CONFIGS["codellama_34b_r32"].with_(name="partial_bf16_ctx", n_layers=6, resident=4, d_model=512,
                                                    n_q_heads=8, n_kv_heads=1, d_ffn=1024, vocab=2048,
@@ -101,7 +107,8 @@ def _compare_cache(s, o, g, tol):
     return worst
 
 
-@pytest.mark.parametrize("s,rows_per_call", [(TINY, 13), (MHA, 50), (MID, 72), (WIDE, 300), (PARTIAL, 33), (PAIRS, 72)],
+@pytest.mark.parametrize("s,rows_per_call", [(TINY, 13), (MHA, 50), (MID, 72), (WIDE, 300), (PARTIAL, 33), (PAIRS, 72), (GQA2, 64),
+                                             (GQA3, 47)],
                          ids=lambda v: v.name if hasattr(v, "name") else None)
 def test_context_pass_cache_and_hidden_states(s, rows_per_call):
     _say(f"[case] context_pass {s.name} seed={s.seed} cache rows={s.batch} entries per call={rows_per_call}")
